@@ -1,0 +1,178 @@
+/*
+ * rh.h - C ABI of the region-aware enhancer for AMD MI355X (gfx950).
+ *
+ * The path is the one RegenHance (arXiv 2407.16990) speeds up, Sec. 3.3:
+ *   select   important 16x16 macroblocks (MBs) across all streams of a batch  (Sec. 3.3.1)
+ *   pack     plan (Alg. 1, region-aware bin packing) + stitch pixels into bins (Sec. 3.3.2-3.3.3)
+ *   enhance  run the super-resolution network on the packed bins only         (Sec. 3.3.3)
+ *   unpack   paste enhanced MBs into the bilinearly interpolated frames        (Sec. 3.2.1, 3.3.3)
+ *
+ * General conventions
+ *   - "dev" pointers are HIP device memory on the context's device, "host" pointers are
+ *     ordinary host memory.  The caller owns every data buffer; the library never frees or
+ *     reallocates them.  The context owns a copy of the weights and its scratch memory.
+ *   - All work is enqueued on the context's HIP stream and the calls return after argument
+ *     validation; only rh_read_counts and rh_create/rh_destroy synchronise.
+ *   - Every call returns an rh_status; nothing aborts or throws across the ABI.  Argument
+ *     errors are detected before any launch and leave outputs untouched.  rh_last_error gives
+ *     a text for the last failure on that context.
+ *   - One context serves one stream at a time; calls on one context must not overlap.
+ *   - Tensors are dense, row-major, channels last: frames u8 [F][H][W][3].
+ *   - Flat macroblock index g = (f*MBH + y)*MBW + x with MBW = W/16, MBH = H/16; f counts the
+ *     (stream, frame) pairs of the batch in the caller's order (the MB index of Sec. 3.3.1).
+ */
+#ifndef RH_H
+#define RH_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct rh_ctx rh_ctx;
+
+typedef enum {
+    RH_OK = 0,
+    RH_E_INVALID = 1,       /* null pointer, bad enum, malformed segment list            */
+    RH_E_SHAPE = 2,         /* sizes that the configuration or the kernels cannot take   */
+    RH_E_CAPACITY = 3,      /* more bins/frames/images than the configured capacity      */
+    RH_E_DEVICE = 4,        /* a HIP call failed                                         */
+    RH_E_NOMEM = 5,
+    RH_E_STATE = 6,
+    RH_E_UNIMPLEMENTED = 7
+} rh_status;
+
+enum { RH_FP32 = 0, RH_BF16 = 1 };                   /* rh_config.precision              */
+enum { RH_NET_PLAIN = 0, RH_NET_RES = 1, RH_NET_EDSR = 2 };
+enum { RH_TOPK = 0, RH_THRESHOLD = 1 };              /* rh_select_regions mode           */
+
+/*
+ * The SR network (Sec. 3.3.3 only says "pre-trained EDSR"; the topologies are this build's).
+ * All convolutions are 3x3, stride 1, zero padding at the tensor border, with bias.
+ *   RH_NET_PLAIN: n_blocks convs (>= 2): 3->C ReLU, (n_blocks-2) x [C->C ReLU], C->3*s*s, shuffle s
+ *   RH_NET_RES  : 3->C, n_blocks x [x + conv(ReLU(conv(x)))], C->3*s*s, shuffle s
+ *   RH_NET_EDSR : 3->C (=h), n_blocks residual blocks, C->C then + h,
+ *                 s=2,3: C->C*s*s, shuffle s;  s=4: two (C->4C, shuffle 2) stages;  then C->3
+ * Pixel shuffle by r: out[y*r+i][x*r+j][c] = in[y][x][c*r*r + i*r + j].
+ * The input is u8/255.  Weight blob (host, fp32): for each conv in the order above,
+ * w[cout][ky][kx][cin] followed by b[cout].  With RH_BF16 the weights are rounded to bf16
+ * (nearest even) at rh_create, activations are stored as bf16 between layers and every
+ * convolution accumulates in fp32; with RH_FP32 everything is fp32.
+ */
+typedef struct { int32_t topology, channels, n_blocks, scale; } rh_net_desc;
+
+typedef struct {
+    int32_t frame_w, frame_h;   /* multiples of 16, else RH_E_SHAPE                        */
+    int32_t max_frames;         /* capacity F of one batch                                 */
+    int32_t halo;               /* pixels of context added on each side of a box           */
+    int32_t bin_size;           /* bins are bin_size x bin_size pixels (multiple of 4)     */
+    int32_t max_bins;           /* capacity; more are reported as overflow                 */
+    int32_t connectivity;       /* 4 or 8: neighbourhood for connected regions             */
+    int32_t max_box_mbs;        /* Partition's preset size in MBs; 0 = (bin_size-2*halo)/16 */
+    int32_t precision;          /* RH_FP32 | RH_BF16                                       */
+    rh_net_desc net;
+} rh_config;
+
+/* One selection segment: frames [frame_begin, frame_end).  RH_TOPK uses k, RH_THRESHOLD thr. */
+typedef struct { uint32_t frame_begin, frame_end, k; float thr; } rh_segment;
+
+/* A placed box (Alg. 1): MB rectangle (mbx0, mby0, wmb, hmb) of frame `frame`, packed with its
+ * halo at pixel (bx, by) of bin `bin`; id = smallest flat index of the MBs it owns; rot = 0.
+ * bin = 0xFFFF marks a box that did not fit within max_bins. */
+typedef struct {
+    uint32_t frame;
+    uint16_t mbx0, mby0;
+    uint8_t wmb, hmb, rot, pad0;
+    uint16_t bin, bx, by, pad1;
+    uint32_t id;
+} rh_box;                                             /* 24 bytes */
+
+/* Where one selected MB lives: its 16x16 pixels start at (px, py) of bin `bin`. */
+typedef struct { uint32_t mb_id, box; uint16_t bin, px, py, pad; } rh_mbplace;   /* 16 bytes */
+
+/* Largest N with 256*N <= bin_h*bin_w*n_bins (Sec. 3.3.1, the MB budget). */
+uint32_t rh_budget(uint32_t bin_h, uint32_t bin_w, uint32_t n_bins);
+
+/*
+ * Create a context on the current HIP device.  weights: host fp32 blob (layout above),
+ * n_floats its length (checked against the descriptor).  hip_stream: a hipStream_t (NULL =
+ * the default stream).  Allocates device scratch for the configured capacities.
+ */
+rh_status rh_create(const rh_config* cfg, const float* weights, size_t n_floats,
+                    void* hip_stream, rh_ctx** out);
+void rh_destroy(rh_ctx* ctx);
+rh_status rh_set_stream(rh_ctx* ctx, void* hip_stream);
+const char* rh_last_error(const rh_ctx* ctx);
+
+/*
+ * Cross-stream MB selection (Sec. 3.3.1).  importance: dev f32 [F][MBH][MBW].  segs: host
+ * array of nseg segments, ascending and non-overlapping; frames outside every segment select
+ * nothing.  RH_TOPK takes, per segment, the k most important MBs of the segment's queue
+ * (importance descending; equal importance: lower flat index first; -0 = +0; NaN ranks last;
+ * k is clipped to the segment size).  RH_THRESHOLD takes importance >= thr.
+ * Outputs (dev): mask u8 [F][MBH][MBW] (0/1), list u32 (capacity F*MBH*MBW) = selected flat
+ * indexes ascending, n_sel u32[1].
+ */
+rh_status rh_select_regions(rh_ctx* ctx, const float* importance, int32_t F,
+                            const rh_segment* segs, int32_t nseg, int32_t mode,
+                            uint8_t* mask, uint32_t* list, uint32_t* n_sel);
+
+/*
+ * Region-aware bin packing (Alg. 1) and stitching (Sec. 3.3.3).
+ * Plan, on MB indexes only: connected regions of selected MBs per frame -> bounding boxes ->
+ * boxes larger than max_box_mbs cut on a grid anchored at the box's top-left, each cell shrunk
+ * to the region's own MBs inside it -> sort by importance density (fp32 sum of owned
+ * importance in ascending flat index, divided in fp64 by the box area in MBs), highest first,
+ * ties by id -> first fit over an ordered list of free rectangles; bins are opened on demand.
+ * A box lands on the free rectangle's top-left; the L-shaped remainder becomes its larger
+ * strip plus the rest, rectangles with a side < 16+2*halo are dropped, survivors replace the
+ * free rectangle in the list, smaller area first.  No rotation (rot = 0).
+ * Stitch: bins u8 [max_bins][S][S][3]; inside a placed box the frame's pixels (zero where the
+ * halo leaves the frame), zero elsewhere; only bins [0, n_bins) are written.
+ * Inputs (dev): frames u8 [F][H][W][3], importance, and mask/list/n_sel from rh_select_regions.
+ * Outputs (dev): bins; boxes (capacity F*MBH*MBW) in placement order; places (same capacity)
+ * in ascending mb_id; counts u32[4] = {n_boxes, n_bins, overflow, n_selected}.
+ * If more than max_bins bins are needed, overflow = 1, n_bins = max_bins and the first box that
+ * does not fit and all later ones carry bin = 0xFFFF (so do their MBs' places).
+ */
+rh_status rh_pack(rh_ctx* ctx, const uint8_t* frames, int32_t F, const float* importance,
+                  const uint8_t* mask, const uint32_t* list, const uint32_t* n_sel,
+                  uint8_t* bins, rh_box* boxes, rh_mbplace* places, uint32_t* counts);
+
+/*
+ * SR forward (Sec. 3.3.3) on N images u8 [N][H][W][3] -> raw network output f32
+ * [N][s*H][s*W][3].  Used for the packed bins and, with whole frames, for the frame-based
+ * comparison run.  n_valid (dev u32[1], may be NULL): when given, only images [0, *n_valid)
+ * are computed (pass &counts[1] to avoid a host round trip).  H, W >= 3.
+ */
+rh_status rh_enhance(rh_ctx* ctx, const uint8_t* in, int32_t N, int32_t H, int32_t W,
+                     float* out, const uint32_t* n_valid);
+
+/*
+ * Paste (Sec. 3.3.3; problem statement of Sec. 3.2.1: SR on selected MBs, bilinear IN(.)
+ * elsewhere).  frames_hr u8 [F][s*H][s*W][3] = bilinear interpolation of frames_lr (integer
+ * factor s, half-pixel centres, edge clamp, exact integer arithmetic, round half up); every
+ * placed MB's (16s x 16s) block is replaced by q = floor(255*e + 0.5),
+ * e = clamp(base/255 + net, 0, 1) in fp32, net read from image `bin` of `enhanced`
+ * (f32 [n_img][s*ih][s*iw][3]) at (s*px, s*py).  Places with bin = 0xFFFF stay bilinear.
+ * places/n_places: dev, from rh_pack (n_places = &counts[3]) or rh_identity_places.
+ * sel (dev, may be NULL): f32 [n_places][16s][16s][3], the unquantised e of every placed MB.
+ */
+rh_status rh_unpack(rh_ctx* ctx, const float* enhanced, int32_t n_img, int32_t ih, int32_t iw,
+                    const rh_mbplace* places, const uint32_t* n_places,
+                    const uint8_t* frames_lr, int32_t F, uint8_t* frames_hr, float* sel);
+
+/* Placement rows of the frame-based run: every MB selected, image f = frame f, px = 16*mbx.
+ * places capacity F*MBH*MBW; n_places u32[1] (both dev). */
+rh_status rh_identity_places(rh_ctx* ctx, int32_t F, rh_mbplace* places, uint32_t* n_places);
+
+/* Synchronise the stream and copy counts (dev u32[4], as written by rh_pack) to the host.
+ * Returns RH_E_CAPACITY if the overflow flag is set. */
+rh_status rh_read_counts(rh_ctx* ctx, const uint32_t* counts, uint32_t out[4]);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RH_H */

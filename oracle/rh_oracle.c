@@ -114,8 +114,12 @@ static int imax(int a, int b) { return a > b ? a : b; }
 static int obox_cmp(const void* pa, const void* pb)
 {
     const obox* a = (const obox*)pa; const obox* b = (const obox*)pb;
-    if (a->key > b->key) return -1;       /* higher density first (Alg. 1, Sort) */
-    if (a->key < b->key) return 1;
+    int an = isnan(a->key), bn = isnan(b->key);
+    if (an != bn) return an - bn;                              /* NaN density ranks last */
+    if (!an) {
+        if (a->key > b->key) return -1;   /* higher density first (Alg. 1, Sort) */
+        if (a->key < b->key) return 1;
+    }
     return (a->id > b->id) - (a->id < b->id);
 }
 
@@ -123,7 +127,7 @@ static int obox_cmp(const void* pa, const void* pb)
  *              places_out[j] = {mb_id, box, bin, px, py}  (ascending mb_id)
  * counts_out = {n_boxes, n_bins, overflow}.
  * On overflow (more than max_bins bins needed) the first box that cannot be
- * placed and every later one get bin = 0xFFFF, bx = by = 0.
+ * placed and every later one get bin = 0xFFFF, bx = by = 0 (their MBs px = py = 0).
  * conn: 4 or 8.  T: largest box side in MBs (the partition's preset size).
  * Returns 0, or -1 on invalid geometry. */
 int orc_plan(const uint8_t* mask, const float* imp, int F, int mbh, int mbw,
@@ -263,8 +267,8 @@ int orc_plan(const uint8_t* mask, const float* imp, int F, int mbh, int mbw,
         obox* b = &boxes[found];
         int32_t* o = places_out + 5 * np++;
         o[0] = g; o[1] = found; o[2] = b->bin;
-        o[3] = b->bx + halo + MBS * (x - b->mbx0);
-        o[4] = b->by + halo + MBS * (y - b->mby0);
+        o[3] = b->bin == 0xFFFF ? 0 : b->bx + halo + MBS * (x - b->mbx0);
+        o[4] = b->bin == 0xFFFF ? 0 : b->by + halo + MBS * (y - b->mby0);
     }
     counts_out[0] = nb; counts_out[1] = nbins; counts_out[2] = overflow;
     free(comp); free(stack); free(comp_first); free(bx0); free(bx1); free(by0); free(by1);

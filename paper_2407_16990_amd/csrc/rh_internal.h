@@ -1,0 +1,100 @@
+// Internal declarations shared by the HIP translation units of librh.so.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <vector>
+
+#include "rh.h"
+
+#define RH_MB 16
+#define RH_NO_BIN 0xFFFFu
+
+struct rh_layer {
+    int cin, cout;          // true channel counts
+    size_t w_off, b_off;    // offsets (floats) into the fp32 blob
+    // bf16 path: weights repacked into MFMA fragment order (see conv_mfma.hip)
+    size_t wp_off;          // offset (bytes) into wpack
+    size_t bp_off;          // offset (floats) into bpack (bias, permuted/padded like the weights)
+    int cout_pad;           // cout rounded up to the kernel's M tile
+    int ps;                 // pixel-shuffle factor folded into the output-channel order (1 = none)
+};
+
+// Raw (unsorted) box written by the labelling kernel.
+struct rh_rawbox {
+    uint32_t frame;
+    uint16_t mbx0, mby0;
+    uint16_t wmb, hmb;
+    uint32_t id;
+    float sum;
+    double key;
+};
+
+struct rh_ctx {
+    rh_config cfg;
+    hipStream_t stream;
+    int device;
+    int mbw, mbh, per;      // macroblock grid of one frame
+    int T;                  // partition size in MBs
+    int free_cap;           // capacity of the free-rectangle list (entries)
+    char err[256];
+
+    std::vector<rh_layer> layers;
+    float* w_f32;           // dev: the fp32 blob as given
+    void* wpack;            // dev: bf16 weights in fragment order (RH_BF16 only)
+    float* bpack;           // dev: biases matching wpack's channel order
+
+    // select scratch (dev)
+    int32_t* frame_seg;     // [max_frames] segment of each frame or -1
+    uint32_t* seg_par;      // [max_frames][4] per segment: g_begin, g_end, k, thr bits
+    uint32_t* seg_T;        // [max_frames] per segment: threshold key
+    uint32_t* seg_budget;   // [max_frames] per segment: ties to take
+    uint32_t* frame_nsel;   // [max_frames]
+    uint32_t* frame_ties;   // [max_frames] ties this frame may take
+    // plan scratch (dev)
+    uint32_t* owner_id;     // [total MBs] id of the box owning each selected MB
+    uint32_t* rank_of_id;   // [total MBs] sorted position of the box with that id
+    rh_rawbox* raw;         // [total MBs]
+    rh_rawbox* sorted;      // [total MBs]
+    uint32_t* pcount;       // [8] plan counters: 0 n_raw boxes
+    // unpack scratch
+    int32_t* slot_of_mb;    // [total MBs] index into places or -1
+    // enhance workspace (grow-only)
+    void* act;
+    size_t act_bytes;
+};
+
+#define RH_FAIL(ctx, code, ...)                                           \
+    do {                                                                  \
+        if (ctx) snprintf((ctx)->err, sizeof((ctx)->err), __VA_ARGS__);   \
+        return (code);                                                    \
+    } while (0)
+
+#define RH_HIP(ctx, call)                                                             \
+    do {                                                                              \
+        hipError_t e_ = (call);                                                       \
+        if (e_ != hipSuccess)                                                         \
+            RH_FAIL(ctx, RH_E_DEVICE, "%s failed: %s", #call, hipGetErrorString(e_)); \
+    } while (0)
+
+// kernels' host launchers (each returns after enqueueing)
+rh_status rh_launch_select(rh_ctx*, const float* imp, int F, int nseg, int mode,
+                           uint8_t* mask, uint32_t* list, uint32_t* n_sel);
+rh_status rh_launch_plan(rh_ctx*, int F, const float* imp, const uint8_t* mask,
+                         const uint32_t* list, const uint32_t* n_sel,
+                         rh_box* boxes, rh_mbplace* places, uint32_t* counts);
+rh_status rh_launch_gather(rh_ctx*, const uint8_t* frames, int F, const rh_box* boxes,
+                           const uint32_t* counts, uint8_t* bins);
+rh_status rh_launch_enhance_fp32(rh_ctx*, const uint8_t* in, int N, int H, int W, float* out,
+                                 const uint32_t* n_valid);
+rh_status rh_launch_enhance_bf16(rh_ctx*, const uint8_t* in, int N, int H, int W, float* out,
+                                 const uint32_t* n_valid);
+rh_status rh_launch_unpack(rh_ctx*, const float* enh, int n_img, int ih, int iw,
+                           const rh_mbplace* places, const uint32_t* n_places,
+                           const uint8_t* lr, int F, uint8_t* hr, float* sel);
+rh_status rh_launch_identity_places(rh_ctx*, int F, rh_mbplace* places, uint32_t* n_places);
+rh_status rh_pack_weights_bf16(rh_ctx*, const float* host_blob);
+rh_status rh_upload_segments(rh_ctx*, const rh_segment* segs, int nseg, int F);
+rh_status rh_plan_init(rh_ctx*);
+void rh_fill_i32(rh_ctx*, int32_t* p, int32_t v, size_t n);
+rh_status rh_ensure_workspace(rh_ctx*, size_t bytes);

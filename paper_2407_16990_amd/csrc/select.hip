@@ -1,0 +1,195 @@
+// Cross-stream macroblock selection (Sec. 3.3.1): the top-k of each segment's importance
+// queue, or a threshold, as an exact k-th-key radix select plus an ordered ballot/prefix-sum
+// compaction.  No sort of the queue is materialised: a macroblock is selected iff its key is
+// above the k-th key, or equals it and is among the first `budget` such macroblocks in
+// ascending flat index.
+#include <string.h>
+
+#include "rh_internal.h"
+
+// Order-preserving image of an fp32 importance: larger key = more important.
+// -0 is treated as +0 and every NaN maps to 0, below all numbers (-inf maps to 0x007FFFFF).
+__device__ __forceinline__ uint32_t imp_key(float v)
+{
+    uint32_t b = __float_as_uint(v);
+    if ((b & 0x7FFFFFFFu) > 0x7F800000u) return 0u;
+    if (b == 0x80000000u) b = 0u;
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+
+// Kernel 1: one workgroup per segment.  Finds the segment's threshold key T and tie budget,
+// then the number of selected macroblocks and admitted ties of each of its frames.
+// seg_par[seg] = {g_begin, g_end, k, thr bits}.
+__global__ __launch_bounds__(1024) void k_select_kth(const float* __restrict__ imp,
+                                                     const uint32_t* __restrict__ seg_par, int mode,
+                                                     int per, uint32_t* __restrict__ seg_T,
+                                                     uint32_t* __restrict__ frame_nsel,
+                                                     uint32_t* __restrict__ frame_ties)
+{
+    __shared__ uint32_t hist[256];
+    __shared__ uint32_t s_prefix, s_remaining, s_gt, s_eq;
+    const int tid = threadIdx.x, seg = blockIdx.x;
+    const uint32_t g0 = seg_par[4 * seg], g1 = seg_par[4 * seg + 1];
+    const uint32_t n = g1 - g0;
+    uint32_t k = seg_par[4 * seg + 2];
+    uint32_t T, budget;
+    if (mode == RH_THRESHOLD) {
+        float thr = __uint_as_float(seg_par[4 * seg + 3]);
+        if (thr != thr) { T = 0xFFFFFFFFu; budget = 0u; }       // NaN threshold selects nothing
+        else { T = imp_key(thr); budget = 0xFFFFFFFFu; }         // every key == T is taken
+    } else {
+        if (k > n) k = n;
+        if (k == 0) { T = 0xFFFFFFFFu; budget = 0u; }            // no key reaches 0xFFFFFFFF
+        else {
+            uint32_t prefix = 0, remaining = k;
+            for (int pass = 3; pass >= 0; --pass) {
+                const int shift = pass * 8;
+                const uint32_t hi_mask = (pass == 3) ? 0u : (0xFFFFFFFFu << (shift + 8));
+                for (int i = tid; i < 256; i += 1024) hist[i] = 0;
+                __syncthreads();
+                for (uint32_t i = tid; i < n; i += 1024) {
+                    uint32_t key = imp_key(imp[g0 + i]);
+                    if ((key & hi_mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+                }
+                __syncthreads();
+                if (tid == 0) {
+                    uint32_t c = 0;
+                    for (int b = 255; b >= 0; --b) {
+                        uint32_t h = hist[b];
+                        if (c + h >= remaining) { s_prefix = prefix | ((uint32_t)b << shift); s_remaining = remaining - c; break; }
+                        c += h;
+                    }
+                }
+                __syncthreads();
+                prefix = s_prefix; remaining = s_remaining;
+                __syncthreads();
+            }
+            T = prefix; budget = remaining;
+        }
+    }
+    if (tid == 0) seg_T[seg] = T;
+    // per-frame counts, frames in ascending order so earlier frames get the ties first
+    uint32_t left = budget;
+    const uint32_t f0 = g0 / per, f1 = g1 / per;
+    for (uint32_t f = f0; f < f1; ++f) {
+        if (tid == 0) { s_gt = 0; s_eq = 0; }
+        __syncthreads();
+        uint32_t gt = 0, eq = 0;
+        for (int i = tid; i < per; i += 1024) {
+            uint32_t key = imp_key(imp[(size_t)f * per + i]);
+            gt += key > T; eq += key == T;
+        }
+        if (gt) atomicAdd(&s_gt, gt);
+        if (eq) atomicAdd(&s_eq, eq);
+        __syncthreads();
+        uint32_t ties = s_eq < left ? s_eq : left;
+        if (tid == 0) { frame_nsel[f] = s_gt + ties; frame_ties[f] = ties; }
+        left -= ties;
+        __syncthreads();
+    }
+}
+
+// Exclusive prefix count of a predicate over a 256-thread workgroup, in thread order.
+__device__ __forceinline__ uint32_t block_prefix256(bool pred, uint32_t* s_w /*[4]*/, uint32_t& total)
+{
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    unsigned long long m = __ballot(pred);
+    uint32_t pre = __popcll(m & ((1ull << lane) - 1ull));
+    __syncthreads();                       // s_w free for reuse
+    if (lane == 0) s_w[w] = __popcll(m);
+    __syncthreads();
+    uint32_t off = 0; total = 0;
+    for (int i = 0; i < 4; ++i) { uint32_t c = s_w[i]; if (i < w) off += c; total += c; }
+    return pre + off;
+}
+
+// Kernel 2: one workgroup per frame writes the frame's mask and its slice of the list.
+__global__ __launch_bounds__(256) void k_select_write(const float* __restrict__ imp,
+                                                      const int32_t* __restrict__ frame_seg,
+                                                      const uint32_t* __restrict__ seg_T,
+                                                      const uint32_t* __restrict__ frame_nsel,
+                                                      const uint32_t* __restrict__ frame_ties,
+                                                      int per, int F, uint8_t* __restrict__ mask,
+                                                      uint32_t* __restrict__ list,
+                                                      uint32_t* __restrict__ n_sel)
+{
+    __shared__ uint32_t s_w[4];
+    __shared__ uint32_t s_base;
+    const int tid = threadIdx.x, f = blockIdx.x;
+    if (tid == 0) s_base = 0;
+    __syncthreads();
+    uint32_t local = 0;
+    for (int i = tid; i < f; i += 256) if (frame_seg[i] >= 0) local += frame_nsel[i];
+    if (local) atomicAdd(&s_base, local);
+    __syncthreads();
+    const uint32_t base = s_base;
+    const int seg = frame_seg[f];
+    const size_t fb = (size_t)f * per;
+    if (seg < 0) {
+        for (int i = tid; i < per; i += 256) mask[fb + i] = 0;
+        if (f == F - 1 && tid == 0) *n_sel = base;
+        return;
+    }
+    const uint32_t T = seg_T[seg], ties_allowed = frame_ties[f];
+    uint32_t run_sel = 0, run_eq = 0;
+    for (int c = 0; c < per; c += 256) {
+        const int i = c + tid;
+        const bool valid = i < per;
+        const uint32_t key = valid ? imp_key(imp[fb + i]) : 0u;
+        const bool gt = valid && key > T, eq = valid && key == T;
+        uint32_t tot_eq, tot_sel;
+        uint32_t eq_pre = block_prefix256(eq, s_w, tot_eq);
+        const bool sel = gt || (eq && (run_eq + eq_pre) < ties_allowed);
+        uint32_t sel_pre = block_prefix256(sel, s_w, tot_sel);
+        if (valid) {
+            mask[fb + i] = sel ? 1 : 0;
+            if (sel) list[base + run_sel + sel_pre] = (uint32_t)(fb + i);
+        }
+        run_eq += tot_eq; run_sel += tot_sel;
+    }
+    if (f == F - 1 && tid == 0) *n_sel = base + run_sel;
+}
+
+// Segment tables travel as kernel arguments (copied at launch), so the caller's array may be
+// freed as soon as rh_select_regions returns and no host synchronisation is needed.
+struct seg_chunk { uint32_t n, first; uint32_t fb[64], fe[64], k[64], thr[64]; };
+
+__global__ __launch_bounds__(256) void k_upload_segments(seg_chunk c, int per, uint32_t* __restrict__ seg_par,
+                                                         int32_t* __restrict__ frame_seg)
+{
+    for (uint32_t s = 0; s < c.n; ++s) {
+        if (threadIdx.x == 0) {
+            uint32_t* p = seg_par + 4 * (size_t)(c.first + s);
+            p[0] = c.fb[s] * (uint32_t)per; p[1] = c.fe[s] * (uint32_t)per; p[2] = c.k[s]; p[3] = c.thr[s];
+        }
+        for (uint32_t f = c.fb[s] + threadIdx.x; f < c.fe[s]; f += 256) frame_seg[f] = (int32_t)(c.first + s);
+    }
+}
+
+rh_status rh_upload_segments(rh_ctx* ctx, const rh_segment* segs, int nseg, int F)
+{
+    rh_fill_i32(ctx, ctx->frame_seg, -1, (size_t)F);
+    for (int s0 = 0; s0 < nseg; s0 += 64) {
+        seg_chunk c;
+        c.n = (uint32_t)((nseg - s0) < 64 ? (nseg - s0) : 64); c.first = (uint32_t)s0;
+        for (uint32_t i = 0; i < c.n; ++i) {
+            const rh_segment& g = segs[s0 + i];
+            c.fb[i] = g.frame_begin; c.fe[i] = g.frame_end; c.k[i] = g.k; memcpy(&c.thr[i], &g.thr, 4);
+        }
+        hipLaunchKernelGGL(k_upload_segments, dim3(1), dim3(256), 0, ctx->stream, c, ctx->per, ctx->seg_par, ctx->frame_seg);
+    }
+    RH_HIP(ctx, hipGetLastError());
+    return RH_OK;
+}
+
+rh_status rh_launch_select(rh_ctx* ctx, const float* imp, int F, int nseg, int mode,
+                           uint8_t* mask, uint32_t* list, uint32_t* n_sel)
+{
+    if (nseg > 0)
+        hipLaunchKernelGGL(k_select_kth, dim3(nseg), dim3(1024), 0, ctx->stream, imp, ctx->seg_par, mode,
+                           ctx->per, ctx->seg_T, ctx->frame_nsel, ctx->frame_ties);
+    hipLaunchKernelGGL(k_select_write, dim3(F), dim3(256), 0, ctx->stream, imp, ctx->frame_seg, ctx->seg_T,
+                       ctx->frame_nsel, ctx->frame_ties, ctx->per, F, mask, list, n_sel);
+    RH_HIP(ctx, hipGetLastError());
+    return RH_OK;
+}

@@ -1,0 +1,177 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element.
+Bars: bit-exact selection, plan and packed bytes; pixels rel-L2 <= 1e-5 on the fp32 path and
+<= 1e-2 with max abs <= 2/255 on the bf16 path."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as wl
+from paper_2407_16990_amd import RH, RhError
+from gpu_common import check_select_and_plan, dev, gpu_select, make_rh, rel_l2
+
+pytestmark = pytest.mark.gpu
+
+
+def full_path_check(cfg, n_frames=None, precision=None, segs=None, max_bins=None):
+    F = cfg.n_frames if n_frames is None else n_frames
+    precision = precision or cfg.precision
+    frames, imp = wl.make_frames(cfg, F), wl.make_importance(cfg, F)
+    segs = wl.make_segments(cfg, F) if segs is None else segs
+    blob = wl.make_weights(cfg.net, cfg.weight_seed, precision)
+    rh = make_rh(cfg, blob, F, precision=precision, max_bins=max_bins)
+    o_plan, po, (d_frames, d_imp, o_bins) = check_select_and_plan(rh, cfg, frames, imp, segs)
+    s = cfg.net.scale
+    # enhance: both the exact-N call and the device-count call
+    g_net = rh.enhance(po.bins, n=o_plan.n_bins)
+    o_net = oracle.sr_forward(cfg.net, blob, o_bins)
+    tol = 1e-5 if precision == "fp32" else 1e-2
+    e = rel_l2(g_net.cpu().numpy(), o_net)
+    print(f"[{cfg.name}/{precision}] n_bins={o_plan.n_bins} net rel-L2={e:.3e}", flush=True)
+    assert e <= tol
+    g_net2 = torch.zeros_like(g_net)
+    rh.enhance(po.bins, n=o_plan.n_bins, n_valid=po.counts[1:2], out=g_net2)
+    assert torch.equal(g_net, g_net2)
+    # unpack
+    hr, sel = rh.unpack(g_net, po.places, po.counts[3:4], d_frames, want_sel=True)
+    o_hr, o_sel = oracle.unpack(frames, s, o_net, o_plan.places)
+    k = len(o_plan.places)
+    g_sel = sel[:k].cpu().numpy()
+    e_sel = rel_l2(g_sel, o_sel)
+    print(f"[{cfg.name}/{precision}] enhanced pixels rel-L2={e_sel:.3e} max abs={np.abs(g_sel - o_sel).max():.3e}", flush=True)
+    assert e_sel <= tol
+    g_hr = hr.cpu().numpy()
+    B = 16 * s
+    selmask = np.kron(oracle.select(imp, segs)[0], np.ones((B, B), dtype=np.uint8)).astype(bool)
+    assert np.array_equal(g_hr[~selmask], o_hr[~selmask]), "unselected macroblocks must be the bilinear base exactly"
+    d = np.abs(g_hr.astype(np.int16) - o_hr.astype(np.int16))[selmask]
+    if precision == "fp32":
+        assert d.max() <= 1 and (d > 0).mean() < 1e-3
+    else:
+        assert np.abs(g_sel - o_sel).max() <= 2.0 / 255.0 and d.max() <= 2
+    rh.close()
+
+
+def test_cfg1_whole_path_fp32():
+    full_path_check(wl.config(1))
+
+
+@pytest.mark.parametrize("net", [wl.Net("res", 8, 2, 2, 0.05), wl.Net("edsr", 8, 2, 2, 0.05),
+                                 wl.Net("edsr", 8, 1, 3, 0.05), wl.Net("edsr", 12, 2, 4, 0.05)])
+def test_small_topologies_fp32(net):
+    cfg = wl.replace(wl.config(1), net=net, n_frames=2, halo=5, frac=0.3)
+    full_path_check(cfg)
+
+
+@pytest.mark.parametrize("ci", [1, 2, 3, 5])
+def test_metadata_and_bytes_at_full_size(ci):
+    cfg = wl.config(ci)
+    frames, imp = wl.make_frames(cfg), wl.make_importance(cfg)
+    blob = wl.make_weights(wl.Net("plain", 4, 2, cfg.net.scale), 0, "fp32")
+    rh = make_rh(wl.replace(cfg, net=wl.Net("plain", 4, 2, cfg.net.scale)), blob, precision="fp32")
+    check_select_and_plan(rh, cfg, frames, imp, wl.make_segments(cfg))
+    rh.close()
+
+
+@pytest.mark.parametrize("frac,kind", [(0.05, "clustered"), (0.5, "clustered"), (1.0, "clustered"),
+                                       (0.1, "uniform"), (0.2, "uniform"), (0.5, "uniform")])
+def test_sweep_metadata(frac, kind):
+    cfg = wl.replace(wl.config(4), frac=frac, importance=kind)
+    frames, imp = wl.make_frames(cfg), wl.make_importance(cfg)
+    net = wl.Net("plain", 4, 2, 4)
+    rh = make_rh(wl.replace(cfg, net=net), wl.make_weights(net, 0, "fp32"), precision="fp32")
+    check_select_and_plan(rh, cfg, frames, imp, wl.make_segments(cfg))
+    rh.close()
+
+
+@pytest.mark.parametrize("levels", [10, 2, 1])
+def test_tie_stress_and_connectivity(levels):
+    cfg = wl.replace(wl.config(2), quantize_levels=levels, n_frames=4)
+    frames, imp = wl.make_frames(cfg), wl.make_importance(cfg)
+    net = wl.Net("plain", 4, 2, 2)
+    for conn, T in [(8, 0), (4, 2), (8, 1), (4, 5)]:
+        rh = make_rh(wl.replace(cfg, net=net), wl.make_weights(net, 0, "fp32"), precision="fp32",
+                     connectivity=conn, max_box_mbs=T)
+        segs = np.array([[0, 1, 300], [1, 3, 911], [3, 4, 0]], dtype=np.uint32)
+        check_select_and_plan(rh, cfg, frames, imp, segs, conn=conn, T=T or None)
+        rh.close()
+
+
+def test_select_specials_threshold_and_edges():
+    cfg = wl.replace(wl.config(1), n_frames=3)
+    imp = wl.make_importance(cfg)
+    imp[0, 0, :5] = [np.nan, -0.0, 0.0, np.inf, -np.inf]
+    imp[1, 3, 3] = np.nan
+    net = wl.Net("plain", 4, 2, 2)
+    rh = make_rh(wl.replace(cfg, net=net), wl.make_weights(net, 0, "fp32"), precision="fp32")
+    per = cfg.mbw * cfg.mbh
+    for segs in ([[0, 3, 0]], [[0, 3, 1]], [[0, 3, 3 * per]], [[0, 3, 3 * per - 1]], [[0, 3, 10 ** 6]],
+                 [[0, 1, 50], [1, 2, 239], [2, 3, 240]], [[1, 2, 17]], []):
+        o_mask, o_list = oracle.select(imp, np.array(segs, dtype=np.uint32).reshape(-1, 3))
+        g_mask, g_list, _ = gpu_select(rh, imp, segs)
+        assert np.array_equal(g_mask, o_mask) and np.array_equal(g_list, o_list), segs
+    for thr in (0.5, 0.0, -1.0, 1e9, float("nan"), float("-inf")):
+        segs = np.array([[0, 2, 0], [2, 3, 0]], dtype=np.uint32)
+        t = np.array([thr, 0.3], dtype=np.float32)
+        o_mask, o_list = oracle.select(imp, segs, "threshold", t)
+        g_mask, g_list, _ = gpu_select(rh, imp, [(0, 2, 0, thr), (2, 3, 0, 0.3)], "threshold")
+        assert np.array_equal(g_mask, o_mask) and np.array_equal(g_list, o_list), thr
+    rh.close()
+
+
+def test_empty_selection_and_overflow_and_errors():
+    cfg = wl.replace(wl.config(1), n_frames=2)
+    frames, imp = wl.make_frames(cfg), wl.make_importance(cfg)
+    net = wl.Net("plain", 4, 2, 2)
+    blob = wl.make_weights(net, 0, "fp32")
+    c2 = wl.replace(cfg, net=net)
+    rh = make_rh(c2, blob, precision="fp32")
+    o_plan, po, _ = check_select_and_plan(rh, cfg, frames, imp, np.array([[0, 2, 0]], dtype=np.uint32))
+    assert o_plan.n_bins == 0
+    hr, _ = rh.unpack(torch.zeros((1, 128, 128, 3), device="cuda"), po.places, po.counts[3:4], dev(frames))
+    assert np.array_equal(hr.cpu().numpy()[0], oracle.bilinear(frames[0], 2))
+    rh.close()
+    # capacity: 3 bins allowed, more needed
+    rh = make_rh(c2, blob, precision="fp32", max_bins=3)
+    segs = np.array([[0, 2, 200]], dtype=np.uint32)
+    o_plan, po, _ = check_select_and_plan(rh, cfg, frames, imp, segs, max_bins=3)
+    assert o_plan.overflow
+    with pytest.raises(RhError) as ei:
+        rh.read_counts(po.counts)
+    assert ei.value.status == 3
+    # overflowed MBs stay bilinear, placed ones are enhanced: compare with the oracle end to end
+    g_net = rh.enhance(po.bins, n=3)
+    hr, _ = rh.unpack(g_net, po.places, po.counts[3:4], dev(frames))
+    o_net = oracle.sr_forward(net, blob, oracle.gather(frames, o_plan.boxes, cfg.halo, cfg.bin_size, 3))
+    o_hr, _ = oracle.unpack(frames, 2, o_net, o_plan.places)
+    assert np.abs(hr.cpu().numpy().astype(int) - o_hr.astype(int)).max() <= 1
+    # argument errors are reported, not crashed on
+    with pytest.raises(RhError):
+        rh.select_regions(dev(imp), [(0, 3, 5)])
+    with pytest.raises(RhError):
+        rh.select_regions(dev(imp), [(1, 2, 5), (0, 1, 5)])
+    with pytest.raises(RhError):
+        RH(frame_w=100, frame_h=64, max_frames=1, halo=4, bin_size=64, max_bins=4, net=net, weights=blob, precision="fp32")
+    with pytest.raises(RhError):
+        RH(frame_w=64, frame_h=64, max_frames=1, halo=30, bin_size=64, max_bins=4, net=net, weights=blob, precision="fp32")
+    with pytest.raises(RhError):
+        RH(frame_w=64, frame_h=64, max_frames=1, halo=4, bin_size=64, max_bins=4, net=net, weights=blob[:-1], precision="fp32")
+    rh.close()
+
+
+def test_frame_based_run_fp32_matches_oracle():
+    """100 % of the macroblocks through rh_enhance on whole frames + identity placement."""
+    cfg = wl.replace(wl.config(1), n_frames=2)
+    frames = wl.make_frames(cfg)
+    blob = wl.make_weights(cfg.net, 0, "fp32")
+    rh = make_rh(cfg, blob, precision="fp32")
+    d_frames = dev(frames)
+    net = rh.enhance(d_frames)
+    places, n = rh.identity_places(2)
+    hr, sel = rh.unpack(net, places, n, d_frames, want_sel=True)
+    o_net = oracle.sr_forward(cfg.net, blob, frames)
+    o_hr, o_sel = oracle.unpack(frames, 2, o_net, oracle.identity_places(2, cfg.mbh, cfg.mbw))
+    assert rel_l2(net.cpu().numpy(), o_net) <= 1e-5
+    assert rel_l2(sel.cpu().numpy(), o_sel) <= 1e-5
+    assert np.abs(hr.cpu().numpy().astype(int) - o_hr.astype(int)).max() <= 1
+    rh.close()
