@@ -1,3 +1,392 @@
+// SR forward, bf16 path (Sec. 3.3.3): every 3x3 convolution with C input channels is an
+// implicit GEMM on the bf16 matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulate).
+//
+// GEMM view of one conv:  D[cout][pixel] = sum_k A[cout][k] * B[k][pixel],  k = tap*CIN + ci.
+//   A (weights) and B (activations) both come from LDS:
+//   - the workgroup is persistent and keeps one 64-output-channel chunk of the weights in
+//     LDS for all the tiles it processes (repacked at rh_create into MFMA fragment order, so
+//     a fragment load is one conflict-free 16-byte read per lane);
+//   - per tile it stages the (TH+2) x (TW+2) halo'd activation patch, channels last, with
+//     the eight 16-byte channel groups of a pixel XOR-swizzled by the pixel's column so
+//     that 32 lanes reading 32 neighbouring pixels hit distinct banks.
+//   Output channels sit on the M side so that a lane ends up holding 4 consecutive channels
+//   of one pixel (an 8-byte channels-last store).
+// Activations are bf16 channels-last [N][H][W][C]; the network's last conv writes fp32.
+// Pixel shuffle is folded into the output-channel order of the upsampling convs: chunk q of
+// the permuted weights produces all C channels of sub-pixel q, i.e. one whole output pixel.
+#include <string.h>
+
 #include "rh_internal.h"
-rh_status rh_pack_weights_bf16(rh_ctx* ctx, const float*) { RH_FAIL(ctx, RH_E_UNIMPLEMENTED, "bf16 path not built yet"); }
-rh_status rh_launch_enhance_bf16(rh_ctx* ctx, const uint8_t*, int, int, int, float*, const uint32_t*) { RH_FAIL(ctx, RH_E_UNIMPLEMENTED, "bf16 path not built yet"); }
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+
+#define TW 32            // tile width in pixels = N of one MFMA
+#define PW (TW + 2)
+
+struct conv_args {
+    const __bf16* in;        // [N][H][W][CIN]
+    const uint4* wp;         // packed weights of this layer
+    const float* bias;       // packed order
+    void* out;
+    const __bf16* skip;      // same shape as out, or null
+    const uint32_t* n_valid;
+    int N, H, W;
+    int relu, ps, n_chunks;  // bf16 output mode
+    int cout_real, s_final;  // fp32 output mode
+};
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b)
+{
+    typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+    typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2;
+    f32x2 v = {a, b};
+    bf16x2 r = __builtin_convertvector(v, bf16x2);     // round to nearest even
+    return *(uint32_t*)&r;
+}
+
+__device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xFFFF0000u); }
+
+// CIN: input channels (32 or 64).  MT: 32-channel M tiles per output chunk (1 or 2).
+// TH: tile height; each of the 4 waves owns TH/4 rows of 32 pixels.
+// F32OUT: last layer of the network (fp32 output, true channel count cout_real <= 32*MT,
+// optional pixel shuffle s_final in the store address).
+template <int CIN, int MT, int TH, bool F32OUT>
+__global__ __launch_bounds__(256) void k_conv_mfma(conv_args a)
+{
+    constexpr int KS = CIN / 16;             // MFMA k-steps per tap
+    constexpr int NCH = CIN / 8;             // 16-byte channel groups per pixel
+    constexpr int PIXB = CIN * 2;            // bytes per pixel
+    constexpr int PH = TH + 2;
+    constexpr int RW = TH / 4;               // rows per wave
+    constexpr int WBYTES = 9 * KS * MT * 1024;
+    constexpr int SWZ_SH = (NCH == 8) ? 0 : 1;
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    uint8_t* lds_w = lds;
+    uint8_t* lds_p = lds + WBYTES;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lx = lane & 31, hi = lane >> 5;
+    const int n_img = a.n_valid ? min((int)*a.n_valid, a.N) : a.N;
+    const int tiles_x = (a.W + TW - 1) / TW, tiles_y = (a.H + TH - 1) / TH;
+    const int n_tiles = n_img * tiles_x * tiles_y;
+    // consecutive tiles go to workgroups of one XCD (workgroups are dealt round-robin to the 8 XCDs)
+    const int G = gridDim.x;
+    const int wg = (G % 8 == 0) ? (blockIdx.x % 8) * (G / 8) + blockIdx.x / 8 : blockIdx.x;
+
+    for (int chunk = 0; chunk < a.n_chunks; ++chunk) {
+        __syncthreads();
+        {   // this chunk's weights -> LDS, linear copy
+            const uint4* src = a.wp + (size_t)chunk * (WBYTES / 16);
+            for (int i = tid; i < WBYTES / 16; i += 256) ((uint4*)lds_w)[i] = src[i];
+        }
+        const int si = chunk / a.ps, sj = chunk - si * a.ps;
+        for (int tile = wg; tile < n_tiles; tile += G) {
+            const int n = tile / (tiles_x * tiles_y), tr = tile - n * (tiles_x * tiles_y);
+            const int ty = tr / tiles_x, tx = tr - ty * tiles_x;
+            const int y0 = ty * TH, x0 = tx * TW;
+            __syncthreads();                                   // previous tile's LDS reads are done
+            // stage the halo'd patch; out-of-image pixels are zero (the layer's zero padding)
+            for (int idx = tid; idx < PH * PW * NCH; idx += 256) {
+                const int p = idx / NCH, c = idx - p * NCH;
+                const int py = p / PW, px = p - py * PW;
+                const int gy = y0 - 1 + py, gx = x0 - 1 + px;
+                uint4 v = make_uint4(0, 0, 0, 0);
+                if (gy >= 0 && gy < a.H && gx >= 0 && gx < a.W)
+                    v = *(const uint4*)(a.in + (((size_t)n * a.H + gy) * a.W + gx) * CIN + c * 8);
+                const int key = (px >> SWZ_SH) & (NCH - 1);
+                *(uint4*)(lds_p + p * PIXB + ((c ^ key) << 4)) = v;
+            }
+            __syncthreads();
+
+            f32x16 acc[RW][MT];
+#pragma unroll
+            for (int r = 0; r < RW; ++r)
+#pragma unroll
+                for (int m = 0; m < MT; ++m)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) acc[r][m][e] = 0.0f;
+
+#pragma unroll
+            for (int ky = 0; ky < 3; ++ky) {
+#pragma unroll
+                for (int kx = 0; kx < 3; ++kx) {
+                    const int px = lx + kx;
+                    const int key = (px >> SWZ_SH) & (NCH - 1);
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks) {
+                        bf16x8 A[MT], B[RW];
+#pragma unroll
+                        for (int m = 0; m < MT; ++m)
+                            A[m] = *(const bf16x8*)(lds_w + ((((ky * 3 + kx) * KS + ks) * MT + m) << 10) + (lane << 4));
+                        const int c = 2 * ks + hi;
+#pragma unroll
+                        for (int r = 0; r < RW; ++r) {
+                            const int py = wave * RW + r + ky;
+                            B[r] = *(const bf16x8*)(lds_p + (py * PW + px) * PIXB + ((c ^ key) << 4));
+                        }
+#pragma unroll
+                        for (int r = 0; r < RW; ++r)
+#pragma unroll
+                            for (int m = 0; m < MT; ++m)
+                                acc[r][m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[m], B[r], acc[r][m], 0, 0, 0);
+                    }
+                }
+            }
+
+            // epilogue: lane holds, for pixel column lx of each of its rows, channels
+            // m*32 + 8*q + 4*hi + {0,1,2,3} in acc[r][m][4q..4q+3]
+            const int x = x0 + lx;
+#pragma unroll
+            for (int r = 0; r < RW; ++r) {
+                const int y = y0 + wave * RW + r;
+                if (y >= a.H || x >= a.W) continue;
+#pragma unroll
+                for (int m = 0; m < MT; ++m) {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const int cb = m * 32 + q * 8 + hi * 4;
+                        float v0 = acc[r][m][4 * q + 0], v1 = acc[r][m][4 * q + 1];
+                        float v2 = acc[r][m][4 * q + 2], v3 = acc[r][m][4 * q + 3];
+                        if constexpr (F32OUT) {
+                            float v[4] = {v0, v1, v2, v3};
+                            const int s = a.s_final, s2 = s * s;
+                            float* o = (float*)a.out;
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                const int co = cb + e;
+                                if (co >= a.cout_real) continue;
+                                const int ch = co / s2, sub = co - ch * s2, ui = sub / s, uj = sub - ui * s;
+                                o[(((size_t)n * a.H * s + (size_t)y * s + ui) * (a.W * s) + (size_t)x * s + uj) * 3 + ch] =
+                                    v[e] + a.bias[co];
+                            }
+                        } else {
+                            constexpr int CQ = 32 * MT;
+                            const float4 bv = *(const float4*)(a.bias + chunk * CQ + cb);
+                            v0 += bv.x; v1 += bv.y; v2 += bv.z; v3 += bv.w;
+                            if (a.relu) { v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); v2 = fmaxf(v2, 0.f); v3 = fmaxf(v3, 0.f); }
+                            const size_t o = (((size_t)n * a.H * a.ps + (size_t)y * a.ps + si) * (a.W * a.ps) + (size_t)x * a.ps + sj) * CQ + cb;
+                            if (a.skip) {
+                                const uint2 sk = *(const uint2*)(a.skip + o);
+                                v0 += bf16_lo(sk.x); v1 += bf16_hi(sk.x); v2 += bf16_lo(sk.y); v3 += bf16_hi(sk.y);
+                            }
+                            uint2 pk;
+                            pk.x = pack_bf16x2(v0, v1); pk.y = pack_bf16x2(v2, v3);
+                            *(uint2*)((__bf16*)a.out + o) = pk;
+                        }
+                    }
+                }
+            }
+        }
+    }
+}
+
+// First conv of the network: 3 input channels read from the u8 image (x/255 rounded to bf16),
+// C output channels, on the vector ALUs (K = 27 is too short for the matrix cores to matter).
+// Thread = one pixel; the weights are uniform over the workgroup (scalar loads).
+template <int C>
+__global__ __launch_bounds__(256) void k_head_bf16(const uint8_t* __restrict__ in, const float* __restrict__ w /*[C][27] bf16-exact*/,
+                                                   const float* __restrict__ bias, __bf16* __restrict__ out, int N, int H,
+                                                   int W, int relu, const uint32_t* __restrict__ n_valid)
+{
+    const int n_img = n_valid ? min((int)*n_valid, N) : N;
+    const size_t total = (size_t)n_img * H * W;
+    for (size_t p = (size_t)blockIdx.x * 256 + threadIdx.x; p < total; p += (size_t)gridDim.x * 256) {
+        const int x = p % W, y = (p / W) % H;
+        const size_t nb = p - (size_t)y * W - x;       // n*H*W
+        float v[27];
+#pragma unroll
+        for (int ky = 0; ky < 3; ++ky)
+#pragma unroll
+            for (int kx = 0; kx < 3; ++kx) {
+                const int yy = y + ky - 1, xx = x + kx - 1;
+                const bool ok = yy >= 0 && yy < H && xx >= 0 && xx < W;
+#pragma unroll
+                for (int c = 0; c < 3; ++c) {
+                    float f = ok ? __fdiv_rn((float)in[(nb + (size_t)yy * W + xx) * 3 + c], 255.0f) : 0.0f;
+                    uint32_t u = pack_bf16x2(f, 0.0f);
+                    v[(ky * 3 + kx) * 3 + c] = bf16_lo(u);
+                }
+            }
+        uint32_t* o = (uint32_t*)(out + p * C);
+#pragma unroll 1
+        for (int c0 = 0; c0 < C; c0 += 8) {
+            float acc[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                acc[j] = bias[c0 + j];
+#pragma unroll
+                for (int k = 0; k < 27; ++k) acc[j] = fmaf(w[(c0 + j) * 27 + k], v[k], acc[j]);
+                if (relu) acc[j] = fmaxf(acc[j], 0.0f);
+            }
+            uint4 pk;
+            pk.x = pack_bf16x2(acc[0], acc[1]); pk.y = pack_bf16x2(acc[2], acc[3]);
+            pk.z = pack_bf16x2(acc[4], acc[5]); pk.w = pack_bf16x2(acc[6], acc[7]);
+            *(uint4*)(o + c0 / 2) = pk;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// host side
+
+static uint16_t f32_to_bf16_rne(float f)
+{
+    uint32_t u; memcpy(&u, &f, 4);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+// Repack every layer with cin = C into fragment order:
+//   [chunk][tap][ks][m][lane][8]  with  cout' = chunk*CQ + m*32 + lane%32,
+//   ci = ks*16 + 8*(lane/32) + e,   cout' -> original cout through the pixel-shuffle fold.
+rh_status rh_pack_weights_bf16(rh_ctx* ctx, const float* blob)
+{
+    const int C = ctx->cfg.net.channels, s = ctx->cfg.net.scale;
+    if (C != 32 && C != 64) RH_FAIL(ctx, RH_E_UNIMPLEMENTED, "bf16 path supports 32 or 64 channels, got %d", C);
+    std::vector<uint16_t> wp;
+    std::vector<float> bp;
+    const size_t nl = ctx->layers.size();
+    for (size_t li = 0; li < nl; ++li) {
+        rh_layer& L = ctx->layers[li];
+        L.wp_off = wp.size() * 2; L.bp_off = bp.size();
+        const float* w = blob + L.w_off; const float* b = blob + L.b_off;
+        if (L.cin == 3) {                      // head: [C][27] fp32 (values bf16-rounded)
+            L.cout_pad = L.cout; L.ps = 1;
+            // stored in bpack: weights then bias
+            for (int co = 0; co < L.cout; ++co)
+                for (int k = 0; k < 27; ++k) {
+                    uint32_t u = (uint32_t)f32_to_bf16_rne(w[(size_t)co * 27 + k]) << 16; float f; memcpy(&f, &u, 4);
+                    bp.push_back(f);
+                }
+            for (int co = 0; co < L.cout; ++co) bp.push_back(b[co]);
+            continue;
+        }
+        const bool last = (li == nl - 1);
+        int ps = 1;
+        if (!last && L.cout != C) {            // upsampling conv: cout = C * r^2
+            ps = (L.cout == 4 * C) ? 2 : (L.cout == 9 * C ? 3 : 0);
+            if (!ps) RH_FAIL(ctx, RH_E_UNIMPLEMENTED, "unexpected layer shape %d->%d", L.cin, L.cout);
+        }
+        L.ps = ps;
+        const int CQ = last ? ((L.cout + 31) / 32) * 32 : C;     // channels per chunk
+        if (CQ > 64) RH_FAIL(ctx, RH_E_UNIMPLEMENTED, "last conv with %d outputs (scale %d) exceeds 64", L.cout, s);
+        const int n_chunks = last ? 1 : ps * ps, MT = CQ / 32, KS = L.cin / 16;
+        L.cout_pad = CQ * n_chunks;
+        for (int q = 0; q < n_chunks; ++q)
+            for (int tap = 0; tap < 9; ++tap)
+                for (int ks = 0; ks < KS; ++ks)
+                    for (int m = 0; m < MT; ++m)
+                        for (int lane = 0; lane < 64; ++lane)
+                            for (int e = 0; e < 8; ++e) {
+                                const int cp = m * 32 + (lane & 31);             // channel within the chunk
+                                const int co = last ? cp : (ps == 1 ? cp : cp * ps * ps + q);
+                                const int ci = ks * 16 + 8 * (lane >> 5) + e;
+                                float v = (co < L.cout) ? w[((size_t)co * 9 + tap) * L.cin + ci] : 0.0f;
+                                wp.push_back(f32_to_bf16_rne(v));
+                            }
+        for (int q = 0; q < n_chunks; ++q)
+            for (int cp = 0; cp < CQ; ++cp) {
+                const int co = last ? cp : (ps == 1 ? cp : cp * ps * ps + q);
+                bp.push_back(co < L.cout ? b[co] : 0.0f);
+            }
+    }
+    RH_HIP(ctx, hipMalloc(&ctx->wpack, wp.size() * 2 + 16));
+    RH_HIP(ctx, hipMalloc((void**)&ctx->bpack, bp.size() * 4 + 16));
+    RH_HIP(ctx, hipMemcpy(ctx->wpack, wp.data(), wp.size() * 2, hipMemcpyHostToDevice));
+    RH_HIP(ctx, hipMemcpy(ctx->bpack, bp.data(), bp.size() * 4, hipMemcpyHostToDevice));
+    return RH_OK;
+}
+
+template <int CIN, int MT, int TH, bool F32OUT>
+static hipError_t launch_conv(rh_ctx* ctx, const conv_args& a, int grid)
+{
+    constexpr int lds = 9 * (CIN / 16) * MT * 1024 + (TH + 2) * PW * CIN * 2;
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute((const void*)k_conv_mfma<CIN, MT, TH, F32OUT>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    hipLaunchKernelGGL((k_conv_mfma<CIN, MT, TH, F32OUT>), dim3(grid), dim3(256), lds, ctx->stream, a);
+    return hipSuccess;
+}
+
+static rh_status conv(rh_ctx* ctx, const rh_layer& L, const __bf16* in, void* out, const __bf16* skip, int N, int H,
+                      int W, int relu, bool last, int s_final, const uint32_t* n_valid)
+{
+    conv_args a;
+    a.in = in; a.wp = (const uint4*)((const uint8_t*)ctx->wpack + L.wp_off); a.bias = ctx->bpack + L.bp_off;
+    a.out = out; a.skip = skip; a.n_valid = n_valid; a.N = N; a.H = H; a.W = W;
+    a.relu = relu; a.ps = L.ps; a.n_chunks = last ? 1 : L.ps * L.ps; a.cout_real = L.cout; a.s_final = s_final;
+    const int grid = 256;
+    const int MT = last ? L.cout_pad / 32 : L.cin / 32;
+    hipError_t e;
+    if (L.cin == 64) {
+        if (last) e = (MT == 2) ? launch_conv<64, 2, 16, true>(ctx, a, grid) : launch_conv<64, 1, 16, true>(ctx, a, grid);
+        else e = launch_conv<64, 2, 16, false>(ctx, a, grid);
+    } else {
+        if (last) e = (MT == 2) ? launch_conv<32, 2, 16, true>(ctx, a, grid) : launch_conv<32, 1, 16, true>(ctx, a, grid);
+        else e = launch_conv<32, 1, 16, false>(ctx, a, grid);
+    }
+    RH_HIP(ctx, e);
+    return RH_OK;
+}
+
+rh_status rh_launch_enhance_bf16(rh_ctx* ctx, const uint8_t* in, int N, int H, int W, float* out,
+                                 const uint32_t* n_valid)
+{
+    const rh_net_desc& d = ctx->cfg.net;
+    const int C = d.channels, s = d.scale;
+    const size_t lr = (size_t)N * H * W * C;
+    size_t need = 3 * lr, up1 = 0, up2 = 0;
+    if (d.topology == RH_NET_EDSR) {
+        const int r = (s == 4) ? 2 : s;
+        up1 = lr * r * r; need += up1;
+        if (s == 4) { up2 = up1 * 4; need += up2; }
+    }
+    rh_status st = rh_ensure_workspace(ctx, need * 2);
+    if (st != RH_OK) return st;
+    __bf16* a = (__bf16*)ctx->act; __bf16* t = a + lr; __bf16* h = t + lr; __bf16* u1 = h + lr; __bf16* u2 = u1 + up1;
+    const std::vector<rh_layer>& L = ctx->layers;
+    size_t li = 0;
+    const int head_relu = d.topology == RH_NET_PLAIN;
+    {
+        const rh_layer& l0 = L[li++];
+        const float* hw = ctx->bpack + l0.bp_off; const float* hb = hw + (size_t)C * 27;
+        const size_t px = (size_t)N * H * W;
+        const int grid = (int)((px + 255) / 256 < 4096 ? (px + 255) / 256 : 4096);
+        if (C == 64) hipLaunchKernelGGL(k_head_bf16<64>, dim3(grid), dim3(256), 0, ctx->stream, in, hw, hb, h, N, H, W, head_relu, n_valid);
+        else hipLaunchKernelGGL(k_head_bf16<32>, dim3(grid), dim3(256), 0, ctx->stream, in, hw, hb, h, N, H, W, head_relu, n_valid);
+    }
+#define CONV(...) do { st = conv(ctx, __VA_ARGS__); if (st != RH_OK) return st; } while (0)
+    if (d.topology == RH_NET_PLAIN) {
+        const __bf16* x = h;
+        for (int l = 0; l < d.n_blocks - 2; ++l) { __bf16* o = (x == a) ? t : a; CONV(L[li++], x, o, nullptr, N, H, W, 1, false, 1, n_valid); x = o; }
+        CONV(L[li++], x, out, nullptr, N, H, W, 0, true, s, n_valid);
+    } else {
+        const __bf16* x = h;
+        for (int b = 0; b < d.n_blocks; ++b) {
+            CONV(L[li++], x, t, nullptr, N, H, W, 1, false, 1, n_valid);
+            CONV(L[li++], t, a, x, N, H, W, 0, false, 1, n_valid);       // x + conv(t)
+            x = a;
+        }
+        if (d.topology == RH_NET_RES) {
+            CONV(L[li++], x, out, nullptr, N, H, W, 0, true, s, n_valid);
+        } else {
+            CONV(L[li++], x, t, h, N, H, W, 0, false, 1, n_valid);        // body end + long skip
+            const int r = (s == 4) ? 2 : s;
+            CONV(L[li++], t, u1, nullptr, N, H, W, 0, false, 1, n_valid);
+            const __bf16* lastin = u1; int hh = H * r, ww = W * r;
+            if (s == 4) { CONV(L[li++], u1, u2, nullptr, N, hh, ww, 0, false, 1, n_valid); lastin = u2; hh *= 2; ww *= 2; }
+            CONV(L[li++], lastin, out, nullptr, N, hh, ww, 0, true, 1, n_valid);
+        }
+    }
+#undef CONV
+    RH_HIP(ctx, hipGetLastError());
+    return RH_OK;
+}

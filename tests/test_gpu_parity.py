@@ -175,3 +175,42 @@ def test_frame_based_run_fp32_matches_oracle():
     assert rel_l2(sel.cpu().numpy(), o_sel) <= 1e-5
     assert np.abs(hr.cpu().numpy().astype(int) - o_hr.astype(int)).max() <= 1
     rh.close()
+
+
+# ---- bf16 / MFMA path --------------------------------------------------------------------
+
+@pytest.mark.parametrize("net", [wl.Net("res", 32, 1, 2, 0.05), wl.Net("res", 64, 1, 2, 0.05),
+                                 wl.Net("plain", 32, 3, 2, 0.05), wl.Net("plain", 64, 3, 4, 0.05),
+                                 wl.Net("res", 32, 1, 3, 0.05), wl.Net("edsr", 64, 1, 2, 0.03),
+                                 wl.Net("edsr", 64, 1, 3, 0.03), wl.Net("edsr", 64, 2, 4, 0.03),
+                                 wl.Net("edsr", 32, 1, 4, 0.03)])
+def test_small_topologies_bf16(net):
+    """Small nets of every topology/scale/channel count the MFMA kernels serve; bins of 80 px
+    give several 32-wide tiles with a ragged tail in both directions."""
+    cfg = wl.replace(wl.config(1), net=net, n_frames=2, halo=5, frac=0.3, bin_size=80, precision="bf16")
+    full_path_check(cfg)
+
+
+def test_cfg2_two_frames_bf16():
+    full_path_check(wl.config(2), n_frames=2)
+
+
+def test_cfg3_two_frames_bf16():
+    full_path_check(wl.config(3), n_frames=2)
+
+
+def test_frame_based_run_bf16_matches_oracle():
+    cfg = wl.replace(wl.config(3), n_frames=1, width=112, height=80, net=wl.Net("edsr", 64, 3, 4, 0.02))
+    frames = wl.make_frames(cfg)
+    blob = wl.make_weights(cfg.net, 1, "bf16")
+    rh = make_rh(cfg, blob)
+    d_frames = dev(frames)
+    net = rh.enhance(d_frames)
+    places, n = rh.identity_places(1)
+    hr, sel = rh.unpack(net, places, n, d_frames, want_sel=True)
+    o_net = oracle.sr_forward(cfg.net, blob, frames)
+    o_hr, o_sel = oracle.unpack(frames, 4, o_net, oracle.identity_places(1, cfg.mbh, cfg.mbw))
+    assert rel_l2(net.cpu().numpy(), o_net) <= 1e-2
+    assert rel_l2(sel.cpu().numpy(), o_sel) <= 1e-2 and np.abs(sel.cpu().numpy() - o_sel).max() <= 2 / 255
+    assert np.abs(hr.cpu().numpy().astype(int) - o_hr.astype(int)).max() <= 2
+    rh.close()
