@@ -1,0 +1,184 @@
+#!/usr/bin/env python3
+"""Benchmark of the region-aware enhancer hot path on one MI355X.
+
+A step = one pass of the whole path (rh_select_regions -> rh_pack -> rh_enhance -> rh_unpack)
+over one batch of synthetic input already resident in HBM.  Workload: configuration 3 of the
+benchmark list (16 frames 480x272, EDSR-baseline x4, top 20 % macroblocks, halo 10, 128x128
+bins, bf16), the one the headline metric "enhanced macroblocks/s" is quoted on.
+
+Prints ONE JSON line with the metric, the roofline of the dominant kernel (the bf16 MFMA conv,
+timed with HIP events inside the timed region), the CPU oracle timed on a bounded sample
+(cpu_baseline), and the 100 %-macroblock frame-based run on the GPU for comparison.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK = 2.5e15   # dense bf16 MFMA, FLOP/s (MI355X published)
+
+
+def conv_flops_per_lr_pixel(net):
+    """Algorithmic FLOPs of the C-input/bf16-output convs (the profiled kernel class) per
+    packed low-resolution pixel: 18*cin*cout per output pixel at the layer's resolution."""
+    C, s = net.channels, net.scale
+    body = 2 * net.n_blocks + (1 if net.topology == "edsr" else 0)
+    fl = body * 18 * C * C
+    launches = body
+    if net.topology == "edsr":
+        if s == 4:
+            fl += 18 * C * 4 * C + 4 * 18 * C * 4 * C
+            launches += 2
+        else:
+            fl += 18 * C * C * s * s
+            launches += 1
+    return fl, launches
+
+
+def total_flops_per_lr_pixel(net):
+    C, s = net.channels, net.scale
+    fl, _ = conv_flops_per_lr_pixel(net)
+    fl += 18 * 3 * C
+    fl += (s * s * 18 * C * 3) if net.topology == "edsr" else 18 * C * 3 * s * s
+    return fl
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-frame-based", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (--gpus 1); no multi-GPU figure exists", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import workloads as wl
+    from paper_2407_16990_amd import RH
+
+    cfg = wl.config(args.config)
+    F, s = cfg.n_frames, cfg.net.scale
+    frames, imp, segs = wl.make_frames(cfg), wl.make_importance(cfg), wl.make_segments(cfg)
+    blob = wl.make_weights(cfg.net, cfg.weight_seed, cfg.precision)
+    max_bins = 512 if cfg.index == 5 else 256
+    rh = RH(frame_w=cfg.width, frame_h=cfg.height, max_frames=F, halo=cfg.halo, bin_size=cfg.bin_size,
+            max_bins=max_bins, net=cfg.net, weights=blob, precision=cfg.precision)
+    d_frames = torch.from_numpy(frames).cuda()
+    d_imp = torch.from_numpy(imp).cuda()
+    seg_rows = [tuple(r) for r in segs.tolist()]
+    S = cfg.bin_size
+    # all outputs are allocated once, outside the timed region
+    po = None
+    net_out = torch.empty((max_bins, S * s, S * s, 3), dtype=torch.float32, device="cuda")
+    hr = torch.empty((F, cfg.height * s, cfg.width * s, 3), dtype=torch.uint8, device="cuda")
+
+    def step():
+        nonlocal po
+        mask, lst, n_sel = rh.select_regions(d_imp, seg_rows)
+        po = rh.pack(d_frames, d_imp, mask, lst, n_sel, out=po)
+        rh.enhance(po.bins, n=max_bins, n_valid=po.counts[1:2], out=net_out)   # device-side bin count
+        rh.unpack(net_out, po.places, po.counts[3:4], d_frames, out=hr)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    counts = rh.read_counts(po.counts)
+    n_boxes, n_bins, _, k_sel = counts
+    rh.profile_enable(True)
+    rh.profile_read()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = rh.profile_read()
+    rh.profile_enable(False)
+
+    ms_step = dt / args.steps * 1e3
+    mbs_per_s = k_sel * args.steps / dt
+    out_mpix = F * cfg.height * s * cfg.width * s * args.steps / dt / 1e6
+    px_lr = n_bins * S * S
+    conv_fl, conv_launches = conv_flops_per_lr_pixel(cfg.net)
+    conv_ms, conv_n = prof["conv"]
+    avg_launch_s = conv_ms / max(conv_n, 1) * 1e-3
+    flop_per_launch = conv_fl * px_lr / conv_launches
+    achieved = flop_per_launch / avg_launch_s if avg_launch_s > 0 else 0.0
+
+    result = {
+        "metric": "enhanced macroblocks/s",
+        "value": mbs_per_s, "unit": "MB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg.precision == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": cfg.name, "frames": F, "frame": [cfg.width, cfg.height], "scale": s,
+                   "selected_fraction": cfg.frac, "halo": cfg.halo, "bin_size": S,
+                   "n_selected": k_sel, "n_boxes": n_boxes, "n_bins": n_bins,
+                   "occupy_ratio": 256.0 * k_sel / (n_bins * S * S) if n_bins else 0.0},
+        "output_mpixel_per_s": out_mpix,
+        "kernel_ms_per_step": {k: v[0] / args.steps for k, v in prof.items()},
+        "roofline": {"bound": "mfma", "kernel": "k_conv_mfma<64,2,16,false>", "achieved": achieved / 1e12,
+                     "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK,
+                     "traffic": None, "avg_launch_us": avg_launch_s * 1e6, "launches_per_step": conv_n / args.steps,
+                     "flop_per_launch": flop_per_launch},
+        "enhance_tflops_all_layers": total_flops_per_lr_pixel(cfg.net) * px_lr /
+                                     (sum(prof[k][0] for k in ("head", "conv", "conv_last")) / args.steps * 1e-3) / 1e12,
+    }
+
+    if not args.no_frame_based:
+        # 100 % of the macroblocks: rh_enhance on whole frames + identity placement
+        places, n_pl = rh.identity_places(F)
+        fb_net = torch.empty((F, cfg.height * s, cfg.width * s, 3), dtype=torch.float32, device="cuda")
+
+        def fb_step():
+            rh.enhance(d_frames, out=fb_net)
+            rh.unpack(fb_net, places, n_pl, d_frames, out=hr)
+        fb_step()
+        torch.cuda.synchronize()
+        n_fb = max(2, args.steps // 4)
+        t0 = time.perf_counter()
+        for _ in range(n_fb):
+            fb_step()
+        torch.cuda.synchronize()
+        fdt = (time.perf_counter() - t0) / n_fb
+        result["frame_based"] = {"ms_per_step": fdt * 1e3, "macroblocks_per_s": F * cfg.mbw * cfg.mbh / fdt,
+                                 "region_speedup": fdt * 1e3 / ms_step,
+                                 "pixel_ratio": F * cfg.width * cfg.height / max(px_lr, 1)}
+
+    if not args.no_cpu_baseline:
+        import oracle
+        cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+        t = time.perf_counter()
+        o_mask, o_list = oracle.select(imp, segs)
+        pl = oracle.plan(o_mask, imp, cfg.halo, S)
+        o_bins = oracle.gather(frames, pl.boxes, cfg.halo, S, pl.n_bins)
+        t_meta = time.perf_counter() - t
+        nb_s = min(pl.n_bins, cores)
+        t = time.perf_counter()
+        o_net = oracle.sr_forward(cfg.net, blob, o_bins[:nb_s])
+        t_sr = time.perf_counter() - t
+        # paste on one frame's worth of the batch, scaled to all frames
+        t = time.perf_counter()
+        oracle.unpack(frames[:1], s, o_net, pl.places[:0])
+        t_un = (time.perf_counter() - t) * F
+        est = t_meta + t_sr * pl.n_bins / nb_s + t_un
+        result["cpu_baseline"] = {"value": len(o_list) / est, "unit": "MB/s", "cores": cores, "kind": "oracle",
+                                  "sample": f"select+plan+gather in full ({t_meta:.3f} s); SR on {nb_s} of {pl.n_bins} bins "
+                                            f"({t_sr:.1f} s, one bin per core), scaled by bin count; bilinear base on 1 of {F} "
+                                            f"frames scaled ({t_un:.2f} s)"}
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -172,6 +172,19 @@ rh_status rh_identity_places(rh_ctx* ctx, int32_t F, rh_mbplace* places, uint32_
  * Returns RH_E_CAPACITY if the overflow flag is set. */
 rh_status rh_read_counts(rh_ctx* ctx, const uint32_t* counts, uint32_t out[4]);
 
+/*
+ * Measurement aid (not part of the method): when enabled, every kernel launch of the four
+ * calls is bracketed by HIP events on the context's stream, grouped in the classes below.
+ * rh_profile_read synchronises, adds up the elapsed times and launch counts since the last
+ * read into ms[RH_PROF_N] / launches[RH_PROF_N] (host arrays) and resets them.
+ * RH_PROF_CONV is the bf16 MFMA conv with C input and bf16 output channels (the body and the
+ * upsampling convs), the kernel that dominates the path.
+ */
+enum { RH_PROF_SELECT = 0, RH_PROF_PLAN = 1, RH_PROF_GATHER = 2, RH_PROF_HEAD = 3, RH_PROF_CONV = 4,
+       RH_PROF_CONV_LAST = 5, RH_PROF_UNPACK = 6, RH_PROF_N = 7 };
+rh_status rh_profile_enable(rh_ctx* ctx, int32_t on);
+rh_status rh_profile_read(rh_ctx* ctx, double* ms, uint32_t* launches);
+
 #ifdef __cplusplus
 }
 #endif

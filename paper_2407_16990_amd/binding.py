@@ -18,6 +18,9 @@ MODE = {"topk": 0, "threshold": 1}
 STATUS = ["RH_OK", "RH_E_INVALID", "RH_E_SHAPE", "RH_E_CAPACITY", "RH_E_DEVICE", "RH_E_NOMEM", "RH_E_STATE",
           "RH_E_UNIMPLEMENTED"]
 
+PROF_CLASSES = ["select", "plan", "gather", "head", "conv", "conv_last", "unpack"]
+PROF_N = len(PROF_CLASSES)
+
 BOX_DTYPE = np.dtype([("frame", "<u4"), ("mbx0", "<u2"), ("mby0", "<u2"), ("wmb", "u1"), ("hmb", "u1"),
                       ("rot", "u1"), ("pad0", "u1"), ("bin", "<u2"), ("bx", "<u2"), ("by", "<u2"),
                       ("pad1", "<u2"), ("id", "<u4")])
@@ -78,6 +81,8 @@ def load_library():
     L.rh_unpack.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, i32, vp, vp]
     L.rh_identity_places.argtypes = [vp, i32, vp, vp]
     L.rh_read_counts.argtypes = [vp, vp, C.POINTER(C.c_uint32 * 4)]
+    L.rh_profile_enable.argtypes = [vp, i32]
+    L.rh_profile_read.argtypes = [vp, C.POINTER(C.c_double * PROF_N), C.POINTER(C.c_uint32 * PROF_N)]
     _lib = L
     return L
 
@@ -198,6 +203,15 @@ class RH:
         out = (C.c_uint32 * 4)()
         self._check(self.lib.rh_read_counts(self.h, _ptr(counts), C.byref(out)))
         return list(out)
+
+    def profile_enable(self, on: bool):
+        self._check(self.lib.rh_profile_enable(self.h, int(on)))
+
+    def profile_read(self):
+        """-> {class: (total ms, launches)} since the last read (synchronises)."""
+        ms, n = (C.c_double * PROF_N)(), (C.c_uint32 * PROF_N)()
+        self._check(self.lib.rh_profile_read(self.h, C.byref(ms), C.byref(n)))
+        return {k: (ms[i], n[i]) for i, k in enumerate(PROF_CLASSES)}
 
     # host-side views of the metadata
     @staticmethod

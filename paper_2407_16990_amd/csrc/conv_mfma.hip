@@ -325,6 +325,7 @@ static rh_status conv(rh_ctx* ctx, const rh_layer& L, const __bf16* in, void* ou
     a.relu = relu; a.ps = L.ps; a.n_chunks = last ? 1 : L.ps * L.ps; a.cout_real = L.cout; a.s_final = s_final;
     const int grid = 256;
     const int MT = last ? L.cout_pad / 32 : L.cin / 32;
+    rh_prof_scope ps(ctx, last ? RH_PROF_CONV_LAST : RH_PROF_CONV);
     hipError_t e;
     if (L.cin == 64) {
         if (last) e = (MT == 2) ? launch_conv<64, 2, 16, true>(ctx, a, grid) : launch_conv<64, 1, 16, true>(ctx, a, grid);
@@ -360,6 +361,7 @@ rh_status rh_launch_enhance_bf16(rh_ctx* ctx, const uint8_t* in, int N, int H, i
         const float* hw = ctx->bpack + l0.bp_off; const float* hb = hw + (size_t)C * 27;
         const size_t px = (size_t)N * H * W;
         const int grid = (int)((px + 255) / 256 < 4096 ? (px + 255) / 256 : 4096);
+        rh_prof_scope ps(ctx, RH_PROF_HEAD);
         if (C == 64) hipLaunchKernelGGL(k_head_bf16<64>, dim3(grid), dim3(256), 0, ctx->stream, in, hw, hb, h, N, H, W, head_relu, n_valid);
         else hipLaunchKernelGGL(k_head_bf16<32>, dim3(grid), dim3(256), 0, ctx->stream, in, hw, hb, h, N, H, W, head_relu, n_valid);
     }

@@ -42,6 +42,7 @@ rh_status rh_launch_gather(rh_ctx* ctx, const uint8_t* frames, int F, const rh_b
     (void)F;
     const int S = ctx->cfg.bin_size;
     const size_t bin_vec = (size_t)S * S * 3 / 16;
+    rh_prof_scope ps(ctx, RH_PROF_GATHER, 2);
     hipLaunchKernelGGL(k_bins_zero, dim3(1024), dim3(256), 0, ctx->stream, (uint4*)bins, counts, bin_vec);
     hipLaunchKernelGGL(k_gather, dim3(2048), dim3(256), 0, ctx->stream, frames, boxes, counts, ctx->cfg.frame_h,
                        ctx->cfg.frame_w, ctx->cfg.halo, S, bins);

@@ -275,6 +275,7 @@ rh_status rh_launch_plan(rh_ctx* ctx, int F, const float* imp, const uint8_t* ma
 {
     const int per = ctx->per, total = per * F;
     uint32_t* box_pos = ctx->pcount + 8;
+    rh_prof_scope ps(ctx, RH_PROF_PLAN, 5);
     hipLaunchKernelGGL(k_plan_zero, dim3(1), dim3(64), 0, ctx->stream, ctx->pcount);
     hipLaunchKernelGGL(k_plan_label, dim3(F), dim3(256), (size_t)per * 16, ctx->stream, mask, imp, ctx->mbw,
                        ctx->mbh, ctx->cfg.connectivity, ctx->T, ctx->owner_id, ctx->raw, ctx->pcount);

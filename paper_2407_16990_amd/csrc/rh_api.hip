@@ -52,11 +52,13 @@ template <typename T> static hipError_t dalloc(T** p, size_t n) { return hipMall
 extern "C" void rh_destroy(rh_ctx* ctx)
 {
     if (!ctx) return;
-    hipStreamSynchronize(ctx->stream);
+    (void)hipStreamSynchronize(ctx->stream);
+    for (rh_prof_rec& r : ctx->prof_pending) { if (r.t0) (void)hipEventDestroy(r.t0); if (r.t1) (void)hipEventDestroy(r.t1); }
+    for (hipEvent_t e : ctx->prof_pool) (void)hipEventDestroy(e);
     void* ptrs[] = {ctx->w_f32, ctx->wpack, ctx->bpack, ctx->frame_seg, ctx->seg_par, ctx->seg_T, ctx->seg_budget,
                     ctx->frame_nsel, ctx->frame_ties, ctx->owner_id, ctx->rank_of_id, ctx->raw, ctx->sorted,
                     ctx->pcount, ctx->slot_of_mb, ctx->act};
-    for (void* p : ptrs) if (p) hipFree(p);
+    for (void* p : ptrs) if (p) (void)hipFree(p);
     delete ctx;
 }
 
@@ -111,6 +113,55 @@ extern "C" rh_status rh_create(const rh_config* cfg, const float* weights, size_
     return RH_OK;
 }
 
+static hipEvent_t prof_event(rh_ctx* ctx)
+{
+    hipEvent_t e = nullptr;
+    if (!ctx->prof_pool.empty()) { e = ctx->prof_pool.back(); ctx->prof_pool.pop_back(); }
+    else if (hipEventCreate(&e) != hipSuccess) e = nullptr;
+    return e;
+}
+
+void rh_prof_begin(rh_ctx* ctx, int cls)
+{
+    if (!ctx->prof_on) return;
+    rh_prof_rec r{cls, 0, prof_event(ctx), prof_event(ctx)};
+    if (r.t0) (void)hipEventRecord(r.t0, ctx->stream);
+    ctx->prof_pending.push_back(r);
+}
+
+void rh_prof_end(rh_ctx* ctx, uint32_t launches)
+{
+    if (!ctx->prof_on || ctx->prof_pending.empty()) return;
+    rh_prof_rec& r = ctx->prof_pending.back();
+    r.launches = launches;
+    if (r.t1) (void)hipEventRecord(r.t1, ctx->stream);
+}
+
+extern "C" rh_status rh_profile_enable(rh_ctx* ctx, int32_t on)
+{
+    if (!ctx) return RH_E_INVALID;
+    ctx->prof_on = on != 0;
+    return RH_OK;
+}
+
+extern "C" rh_status rh_profile_read(rh_ctx* ctx, double* ms, uint32_t* launches)
+{
+    if (!ctx) return RH_E_INVALID;
+    if (!ms || !launches) RH_FAIL(ctx, RH_E_INVALID, "rh_profile_read: null argument");
+    RH_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    for (rh_prof_rec& r : ctx->prof_pending) {
+        float t = 0.f;
+        if (r.t0 && r.t1 && hipEventElapsedTime(&t, r.t0, r.t1) == hipSuccess) {
+            ctx->prof_ms[r.cls] += t; ctx->prof_launches[r.cls] += r.launches;
+        }
+        if (r.t0) ctx->prof_pool.push_back(r.t0);
+        if (r.t1) ctx->prof_pool.push_back(r.t1);
+    }
+    ctx->prof_pending.clear();
+    for (int i = 0; i < RH_PROF_N; ++i) { ms[i] = ctx->prof_ms[i]; launches[i] = ctx->prof_launches[i]; ctx->prof_ms[i] = 0; ctx->prof_launches[i] = 0; }
+    return RH_OK;
+}
+
 extern "C" rh_status rh_set_stream(rh_ctx* ctx, void* hip_stream)
 {
     if (!ctx) return RH_E_INVALID;
@@ -122,7 +173,7 @@ rh_status rh_ensure_workspace(rh_ctx* ctx, size_t bytes)
 {
     if (bytes <= ctx->act_bytes) return RH_OK;
     RH_HIP(ctx, hipStreamSynchronize(ctx->stream));
-    if (ctx->act) { hipFree(ctx->act); ctx->act = nullptr; ctx->act_bytes = 0; }
+    if (ctx->act) { (void)hipFree(ctx->act); ctx->act = nullptr; ctx->act_bytes = 0; }
     hipError_t e = hipMalloc(&ctx->act, bytes);
     if (e != hipSuccess) RH_FAIL(ctx, RH_E_NOMEM, "workspace of %zu bytes: %s", bytes, hipGetErrorString(e));
     ctx->act_bytes = bytes;

@@ -30,8 +30,16 @@ struct rh_rawbox {
     double key;
 };
 
+struct rh_prof_rec { int cls; uint32_t launches; hipEvent_t t0, t1; };
+
 struct rh_ctx {
     rh_config cfg;
+    // optional per-kernel-class event timing
+    bool prof_on;
+    std::vector<rh_prof_rec> prof_pending;
+    std::vector<hipEvent_t> prof_pool;
+    double prof_ms[RH_PROF_N];
+    uint32_t prof_launches[RH_PROF_N];
     hipStream_t stream;
     int device;
     int mbw, mbh, per;      // macroblock grid of one frame
@@ -98,3 +106,12 @@ rh_status rh_upload_segments(rh_ctx*, const rh_segment* segs, int nseg, int F);
 rh_status rh_plan_init(rh_ctx*);
 void rh_fill_i32(rh_ctx*, int32_t* p, int32_t v, size_t n);
 rh_status rh_ensure_workspace(rh_ctx*, size_t bytes);
+
+// Event bracket around the launches of one kernel class (no-ops unless profiling is on).
+void rh_prof_begin(rh_ctx*, int cls);
+void rh_prof_end(rh_ctx*, uint32_t launches);
+struct rh_prof_scope {
+    rh_ctx* c; uint32_t n;
+    rh_prof_scope(rh_ctx* ctx, int cls, uint32_t launches = 1) : c(ctx), n(launches) { rh_prof_begin(c, cls); }
+    ~rh_prof_scope() { rh_prof_end(c, n); }
+};

@@ -185,6 +185,7 @@ rh_status rh_upload_segments(rh_ctx* ctx, const rh_segment* segs, int nseg, int 
 rh_status rh_launch_select(rh_ctx* ctx, const float* imp, int F, int nseg, int mode,
                            uint8_t* mask, uint32_t* list, uint32_t* n_sel)
 {
+    rh_prof_scope ps(ctx, RH_PROF_SELECT, nseg > 0 ? 2 : 1);
     if (nseg > 0)
         hipLaunchKernelGGL(k_select_kth, dim3(nseg), dim3(1024), 0, ctx->stream, imp, ctx->seg_par, mode,
                            ctx->per, ctx->seg_T, ctx->frame_nsel, ctx->frame_ties);

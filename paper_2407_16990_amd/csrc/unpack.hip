@@ -104,6 +104,7 @@ rh_status rh_launch_unpack(rh_ctx* ctx, const float* enh, int n_img, int ih, int
 {
     const uint32_t total = (uint32_t)ctx->per * F;
     const int nb = (int)min((total + 255u) / 256u, 1024u);
+    rh_prof_scope ps(ctx, RH_PROF_UNPACK, 3);
     rh_fill_i32(ctx, ctx->slot_of_mb, -1, (size_t)total);
     hipLaunchKernelGGL(k_slot_scatter, dim3(nb), dim3(256), 0, ctx->stream, places, n_places, total, ctx->slot_of_mb);
     hipLaunchKernelGGL(k_unpack, dim3(ctx->mbw, ctx->mbh, F), dim3(256), 0, ctx->stream, lr, ctx->cfg.frame_h,
