@@ -51,56 +51,119 @@ __device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u 
 __device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xFFFF0000u); }
 
 // CIN: input channels (32 or 64).  MT: 32-channel M tiles per output chunk (1 or 2).
-// TH: tile height; each of the 4 waves owns TH/4 rows of 32 pixels.
+// TH: tile height; each of the 4 waves owns RW = TH/4 rows of 32 pixels.
 // F32OUT: last layer of the network (fp32 output, true channel count cout_real <= 32*MT,
 // optional pixel shuffle s_final in the store address).
-template <int CIN, int MT, int TH, bool F32OUT>
+//
+// Per tile:   (A) barrier, prefetched patch registers -> LDS, (B) barrier,
+//             issue the global loads of the NEXT tile's patch into registers (they complete
+//             under the MFMA loop), MFMA loop, (C) barrier, epilogue through LDS.
+// MFMA loop:  12 (CIN=64) steps = (kx, k-step) pairs.  In a step the 3 x MT weight fragments
+//             of the three ky taps stay in registers while the wave walks down its RW+2 input
+//             rows: every activation fragment is read from LDS once and feeds the (up to) 3
+//             output rows it belongs to.  The fragments of step s+1 are loaded while the
+//             MFMAs of step s run (two register sets).
+// Epilogue:   accumulators (+bias, ReLU) are rounded to bf16 into the wave's own slice of the
+//             (now free) patch area and read back as 16-byte channel groups, so that the skip
+//             read and the store are whole pixels, 1 KB contiguous per wave access.
+template <int CIN, int MT, int TH, bool F32OUT, bool SKIP>
 __global__ __launch_bounds__(256) void k_conv_mfma(conv_args a)
 {
     constexpr int KS = CIN / 16;             // MFMA k-steps per tap
-    constexpr int NCH = CIN / 8;             // 16-byte channel groups per pixel
-    constexpr int PIXB = CIN * 2;            // bytes per pixel
+    constexpr int NCH = CIN / 8;             // 16-byte channel groups per input pixel
+    constexpr int PIXB = CIN * 2;            // bytes per input pixel
     constexpr int PH = TH + 2;
     constexpr int RW = TH / 4;               // rows per wave
+    constexpr int NR = RW + 2;               // input rows per wave
     constexpr int WBYTES = 9 * KS * MT * 1024;
     constexpr int SWZ_SH = (NCH == 8) ? 0 : 1;
+    constexpr int NSTEP = 3 * KS;
+    constexpr int CQ = 32 * MT;              // channels of one output pixel (bf16 mode)
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     uint8_t* lds_w = lds;
     uint8_t* lds_p = lds + WBYTES;
+    float* lds_b = (float*)(lds + WBYTES + PH * PW * PIXB);      // CQ biases of the chunk
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int lx = lane & 31, hi = lane >> 5;
     const int n_img = a.n_valid ? min((int)*a.n_valid, a.N) : a.N;
     const int tiles_x = (a.W + TW - 1) / TW, tiles_y = (a.H + TH - 1) / TH;
-    const int n_tiles = n_img * tiles_x * tiles_y;
+    const int tiles_img = tiles_x * tiles_y;
+    const int n_tiles = n_img * tiles_img;
     // consecutive tiles go to workgroups of one XCD (workgroups are dealt round-robin to the 8 XCDs)
     const int G = gridDim.x;
     const int wg = (G % 8 == 0) ? (blockIdx.x % 8) * (G / 8) + blockIdx.x / 8 : blockIdx.x;
 
+    // Patch staging.  The 32 inner columns of a patch row are PPR contiguous 16-byte pieces in
+    // global memory: piece j of a thread is (row RPJ*j + tid/PPR, column 1 + (tid%PPR)/NCH),
+    // i.e. a uniform row base plus a per-thread constant.  The two halo columns (0 and 33) are
+    // the NHALO extra pieces.  Loads always use an in-image (clamped) address; pieces outside
+    // the image are zeroed when they are written to LDS (the layer's zero padding).
+    constexpr int PPR = 32 * NCH, RPJ = 256 / PPR, NMAIN = PH / RPJ;
+    constexpr int NHP = PH * 2 * NCH, NHALO = (NHP + 255) / 256;
+    static_assert(PH % RPJ == 0, "patch rows must split evenly over the threads");
+    uint4 pre[NMAIN + NHALO];
+    const int m_row = tid / PPR, m_col = (tid % PPR) / NCH, m_c = tid % NCH;       // main piece
+    const uint32_t m_lds = (uint32_t)((1 + m_col) * PIXB + ((m_c ^ (((1 + m_col) >> SWZ_SH) & (NCH - 1))) << 4));
+    auto load_patch = [&](int tile) __attribute__((always_inline)) {
+        const int n = tile / tiles_img, tr = tile - n * tiles_img;
+        const int ty = tr / tiles_x, tx = tr - ty * tiles_x;
+        const int y0 = ty * TH, x0 = tx * TW;
+        const uint8_t* img = (const uint8_t*)(a.in + (size_t)n * a.H * a.W * CIN);
+        const int gx = min(x0 + m_col, a.W - 1);
+#pragma unroll
+        for (int j = 0; j < NMAIN; ++j) {
+            const int gy = min(max(y0 - 1 + RPJ * j + m_row, 0), a.H - 1);
+            pre[j] = *(const uint4*)(img + ((size_t)gy * a.W + gx) * PIXB + m_c * 16);
+        }
+#pragma unroll
+        for (int j = 0; j < NHALO; ++j) {
+            const int idx = tid + 256 * j, row = min(idx / (2 * NCH), PH - 1), side = (idx / NCH) & 1, c = idx % NCH;
+            const int gy = min(max(y0 - 1 + row, 0), a.H - 1), hx = min(max(side ? x0 + TW : x0 - 1, 0), a.W - 1);
+            pre[NMAIN + j] = *(const uint4*)(img + ((size_t)gy * a.W + hx) * PIXB + c * 16);
+        }
+    };
+    auto store_patch = [&](int y0, int x0) __attribute__((always_inline)) {
+        const bool col_ok = x0 + m_col < a.W;
+#pragma unroll
+        for (int j = 0; j < NMAIN; ++j) {
+            const int row = RPJ * j + m_row, gy = y0 - 1 + row;
+            const bool ok = col_ok && gy >= 0 && gy < a.H;
+            const uint32_t keep = ok ? 0xFFFFFFFFu : 0u;
+            uint4 v = pre[j];
+            v.x &= keep; v.y &= keep; v.z &= keep; v.w &= keep;
+            *(uint4*)(lds_p + row * (PW * PIXB) + m_lds) = v;
+        }
+#pragma unroll
+        for (int j = 0; j < NHALO; ++j) {
+            const int idx = tid + 256 * j, row = idx / (2 * NCH), side = (idx / NCH) & 1, c = idx % NCH;
+            const int gy = y0 - 1 + row, hx = side ? x0 + TW : x0 - 1, px = side ? PW - 1 : 0;
+            const bool ok = gy >= 0 && gy < a.H && hx >= 0 && hx < a.W;
+            const uint32_t keep = ok ? 0xFFFFFFFFu : 0u;
+            uint4 v = pre[NMAIN + j];
+            v.x &= keep; v.y &= keep; v.z &= keep; v.w &= keep;
+            if (idx < NHP) *(uint4*)(lds_p + (row * PW + px) * PIXB + ((c ^ ((px >> SWZ_SH) & (NCH - 1))) << 4)) = v;
+        }
+    };
+
     for (int chunk = 0; chunk < a.n_chunks; ++chunk) {
         __syncthreads();
-        {   // this chunk's weights -> LDS, linear copy
+        {   // this chunk's weights and biases -> LDS
             const uint4* src = a.wp + (size_t)chunk * (WBYTES / 16);
             for (int i = tid; i < WBYTES / 16; i += 256) ((uint4*)lds_w)[i] = src[i];
+            if (!F32OUT && tid < CQ) lds_b[tid] = a.bias[chunk * CQ + tid];
         }
         const int si = chunk / a.ps, sj = chunk - si * a.ps;
-        for (int tile = wg; tile < n_tiles; tile += G) {
-            const int n = tile / (tiles_x * tiles_y), tr = tile - n * (tiles_x * tiles_y);
+        int tile = wg;
+        if (tile < n_tiles) load_patch(tile);
+        for (; tile < n_tiles; tile += G) {
+            const int n = tile / tiles_img, tr = tile - n * tiles_img;
             const int ty = tr / tiles_x, tx = tr - ty * tiles_x;
             const int y0 = ty * TH, x0 = tx * TW;
-            __syncthreads();                                   // previous tile's LDS reads are done
-            // stage the halo'd patch; out-of-image pixels are zero (the layer's zero padding)
-            for (int idx = tid; idx < PH * PW * NCH; idx += 256) {
-                const int p = idx / NCH, c = idx - p * NCH;
-                const int py = p / PW, px = p - py * PW;
-                const int gy = y0 - 1 + py, gx = x0 - 1 + px;
-                uint4 v = make_uint4(0, 0, 0, 0);
-                if (gy >= 0 && gy < a.H && gx >= 0 && gx < a.W)
-                    v = *(const uint4*)(a.in + (((size_t)n * a.H + gy) * a.W + gx) * CIN + c * 8);
-                const int key = (px >> SWZ_SH) & (NCH - 1);
-                *(uint4*)(lds_p + p * PIXB + ((c ^ key) << 4)) = v;
-            }
-            __syncthreads();
+            __syncthreads();                                   // (A) LDS reads of the previous tile are done
+            store_patch(y0, x0);
+            __syncthreads();                                   // (B)
+            if (tile + G < n_tiles) load_patch(tile + G);
 
             f32x16 acc[RW][MT];
 #pragma unroll
@@ -110,74 +173,137 @@ __global__ __launch_bounds__(256) void k_conv_mfma(conv_args a)
 #pragma unroll
                     for (int e = 0; e < 16; ++e) acc[r][m][e] = 0.0f;
 
+            // fragment addresses of step st = kx*KS + ks
+            const uint8_t* wlane = lds_w + (lane << 4);
+            const uint8_t* prow = lds_p + (wave * RW) * (PW * PIXB);
+            auto load_A = [&](int st, bf16x8 (&A)[3][MT]) __attribute__((always_inline)) {
+                const int kx = st / KS, ks = st - kx * KS;
 #pragma unroll
-            for (int ky = 0; ky < 3; ++ky) {
+                for (int ky = 0; ky < 3; ++ky)
 #pragma unroll
-                for (int kx = 0; kx < 3; ++kx) {
-                    const int px = lx + kx;
-                    const int key = (px >> SWZ_SH) & (NCH - 1);
+                    for (int m = 0; m < MT; ++m)
+                        A[ky][m] = *(const bf16x8*)(wlane + ((((ky * 3 + kx) * KS + ks) * MT + m) << 10));
+            };
+            auto load_B = [&](int st, bf16x8 (&B)[NR]) __attribute__((always_inline)) {
+                const int kx = st / KS, ks = st - kx * KS;
+                const int px = lx + kx;
+                const int key = (px >> SWZ_SH) & (NCH - 1);
+                const uint8_t* b0 = prow + px * PIXB + (((2 * ks + hi) ^ key) << 4);
 #pragma unroll
-                    for (int ks = 0; ks < KS; ++ks) {
-                        bf16x8 A[MT], B[RW];
+                for (int py = 0; py < NR; ++py) B[py] = *(const bf16x8*)(b0 + py * (PW * PIXB));
+            };
+            bf16x8 A0[3][MT], A1[3][MT], B0[NR], B1[NR];
+            load_A(0, A0); load_B(0, B0);
+#pragma unroll
+            for (int st = 0; st < NSTEP; ++st) {
+                bf16x8 (&Ac)[3][MT] = (st & 1) ? A1 : A0;
+                bf16x8 (&Bc)[NR] = (st & 1) ? B1 : B0;
+                if (st + 1 < NSTEP) {
+                    load_A(st + 1, (st & 1) ? A0 : A1);
+                    load_B(st + 1, (st & 1) ? B0 : B1);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int py = 0; py < NR; ++py)
+#pragma unroll
+                    for (int ky = 0; ky < 3; ++ky) {
+                        const int r = py - ky;
+                        if (r < 0 || r >= RW) continue;
 #pragma unroll
                         for (int m = 0; m < MT; ++m)
-                            A[m] = *(const bf16x8*)(lds_w + ((((ky * 3 + kx) * KS + ks) * MT + m) << 10) + (lane << 4));
-                        const int c = 2 * ks + hi;
-#pragma unroll
-                        for (int r = 0; r < RW; ++r) {
-                            const int py = wave * RW + r + ky;
-                            B[r] = *(const bf16x8*)(lds_p + (py * PW + px) * PIXB + ((c ^ key) << 4));
-                        }
-#pragma unroll
-                        for (int r = 0; r < RW; ++r)
-#pragma unroll
-                            for (int m = 0; m < MT; ++m)
-                                acc[r][m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[m], B[r], acc[r][m], 0, 0, 0);
+                            acc[r][m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Ac[ky][m], Bc[py], acc[r][m], 0, 0, 0);
                     }
-                }
+                __builtin_amdgcn_sched_barrier(0);
             }
 
-            // epilogue: lane holds, for pixel column lx of each of its rows, channels
+            // lane holds, for pixel column lx of each of its rows, channels
             // m*32 + 8*q + 4*hi + {0,1,2,3} in acc[r][m][4q..4q+3]
-            const int x = x0 + lx;
+            if constexpr (F32OUT) {
+                const int x = x0 + lx;
+                const int s = a.s_final, s2 = s * s;
+                float* o = (float*)a.out;
 #pragma unroll
-            for (int r = 0; r < RW; ++r) {
-                const int y = y0 + wave * RW + r;
-                if (y >= a.H || x >= a.W) continue;
+                for (int r = 0; r < RW; ++r) {
+                    const int y = y0 + wave * RW + r;
+                    if (y >= a.H || x >= a.W) continue;
 #pragma unroll
-                for (int m = 0; m < MT; ++m) {
+                    for (int m = 0; m < MT; ++m)
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const int cb = m * 32 + q * 8 + hi * 4;
-                        float v0 = acc[r][m][4 * q + 0], v1 = acc[r][m][4 * q + 1];
-                        float v2 = acc[r][m][4 * q + 2], v3 = acc[r][m][4 * q + 3];
-                        if constexpr (F32OUT) {
-                            float v[4] = {v0, v1, v2, v3};
-                            const int s = a.s_final, s2 = s * s;
-                            float* o = (float*)a.out;
+                        for (int q = 0; q < 4; ++q) {
+                            const int cb = m * 32 + q * 8 + hi * 4;
 #pragma unroll
                             for (int e = 0; e < 4; ++e) {
                                 const int co = cb + e;
                                 if (co >= a.cout_real) continue;
                                 const int ch = co / s2, sub = co - ch * s2, ui = sub / s, uj = sub - ui * s;
                                 o[(((size_t)n * a.H * s + (size_t)y * s + ui) * (a.W * s) + (size_t)x * s + uj) * 3 + ch] =
-                                    v[e] + a.bias[co];
+                                    acc[r][m][4 * q + e] + a.bias[co];
                             }
-                        } else {
-                            constexpr int CQ = 32 * MT;
-                            const float4 bv = *(const float4*)(a.bias + chunk * CQ + cb);
-                            v0 += bv.x; v1 += bv.y; v2 += bv.z; v3 += bv.w;
-                            if (a.relu) { v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); v2 = fmaxf(v2, 0.f); v3 = fmaxf(v3, 0.f); }
-                            const size_t o = (((size_t)n * a.H * a.ps + (size_t)y * a.ps + si) * (a.W * a.ps) + (size_t)x * a.ps + sj) * CQ + cb;
-                            if (a.skip) {
-                                const uint2 sk = *(const uint2*)(a.skip + o);
-                                v0 += bf16_lo(sk.x); v1 += bf16_hi(sk.x); v2 += bf16_lo(sk.y); v3 += bf16_hi(sk.y);
-                            }
+                        }
+                }
+            } else {
+                constexpr int NCHO = CQ / 8;             // 16-byte groups per output pixel
+                constexpr int OPIXB = CQ * 2;
+                constexpr int OSH = (NCHO == 8) ? 0 : 1;
+                constexpr int NOUT = RW * 32 * NCHO / 64; // 16-byte pieces per lane
+                __syncthreads();                           // (C) every wave is done with the patch
+                uint8_t* stg = lds_p + wave * (RW * 32 * OPIXB);
+                const int okey = (lx >> OSH) & (NCHO - 1);
+                const float lo = a.relu ? 0.0f : -__builtin_inff();        // ReLU as a max with 0 or -inf
+#pragma unroll
+                for (int m = 0; m < MT; ++m)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const float4 bv = *(const float4*)(lds_b + m * 32 + q * 8 + hi * 4);
+#pragma unroll
+                        for (int r = 0; r < RW; ++r) {
+                            float v0 = acc[r][m][4 * q + 0] + bv.x, v1 = acc[r][m][4 * q + 1] + bv.y;
+                            float v2 = acc[r][m][4 * q + 2] + bv.z, v3 = acc[r][m][4 * q + 3] + bv.w;
+                            v0 = fmaxf(v0, lo); v1 = fmaxf(v1, lo); v2 = fmaxf(v2, lo); v3 = fmaxf(v3, lo);
                             uint2 pk;
                             pk.x = pack_bf16x2(v0, v1); pk.y = pack_bf16x2(v2, v3);
-                            *(uint2*)((__bf16*)a.out + o) = pk;
+                            *(uint2*)(stg + (r * 32 + lx) * OPIXB + (((m * 4 + q) ^ okey) << 4) + hi * 8) = pk;
                         }
                     }
+                // piece j of this lane: pixel (j*64 + lane) / NCHO of the wave's RW x 32 pixels =
+                // row j / JPR, column (j % JPR) * PPJ + lane / NCHO, channel group lane % NCHO
+                constexpr int PPJ = 64 / NCHO, JPR = 32 / PPJ;
+                const int ps = a.ps;
+                const int lcol = lane / NCHO, lc = lane % NCHO;
+                const uint32_t lane_off = (uint32_t)(lcol * ps) * OPIXB + lc * 16;      // bytes, within an output row
+                const uint32_t lane_lds = (uint32_t)lcol * OPIXB;
+                const size_t orow_pitch = (size_t)a.W * ps * OPIXB;
+                const uint8_t* skp = (const uint8_t*)a.skip;
+                uint8_t* outp = (uint8_t*)a.out;
+                uint4 sk[NOUT];
+                if constexpr (SKIP) {
+#pragma unroll
+                    for (int j = 0; j < NOUT; ++j) {       // all skip reads in flight together
+                        const int y = min(y0 + wave * RW + j / JPR, a.H - 1), xb = x0 + (j % JPR) * PPJ;
+                        const size_t rb = ((size_t)n * a.H * ps + (size_t)y * ps + si) * orow_pitch + (size_t)(xb * ps + sj) * OPIXB;
+                        sk[j] = *(const uint4*)(skp + rb + (xb + lcol < a.W ? lane_off : 0));
+                    }
+                }
+                __syncthreads();                           // staged values visible
+                uint4 v[NOUT];
+#pragma unroll
+                for (int j = 0; j < NOUT; ++j) {
+                    const int r = j / JPR, px = (j % JPR) * PPJ + lcol;
+                    v[j] = *(const uint4*)(stg + (r * 32 + (j % JPR) * PPJ) * OPIXB + lane_lds + ((lc ^ ((px >> OSH) & (NCHO - 1))) << 4));
+                }
+                const bool full = y0 + TH <= a.H && x0 + TW <= a.W;       // uniform: no ragged edge in this tile
+#pragma unroll
+                for (int j = 0; j < NOUT; ++j) {
+                    const int y = y0 + wave * RW + j / JPR, xb = x0 + (j % JPR) * PPJ;
+                    uint4 o = v[j];
+                    if constexpr (SKIP) {
+                        o.x = pack_bf16x2(bf16_lo(o.x) + bf16_lo(sk[j].x), bf16_hi(o.x) + bf16_hi(sk[j].x));
+                        o.y = pack_bf16x2(bf16_lo(o.y) + bf16_lo(sk[j].y), bf16_hi(o.y) + bf16_hi(sk[j].y));
+                        o.z = pack_bf16x2(bf16_lo(o.z) + bf16_lo(sk[j].z), bf16_hi(o.z) + bf16_hi(sk[j].z));
+                        o.w = pack_bf16x2(bf16_lo(o.w) + bf16_lo(sk[j].w), bf16_hi(o.w) + bf16_hi(sk[j].w));
+                    }
+                    const size_t rb = ((size_t)n * a.H * ps + (size_t)y * ps + si) * orow_pitch + (size_t)(xb * ps + sj) * OPIXB;
+                    if (full || (y < a.H && xb + lcol < a.W)) *(uint4*)(outp + rb + lane_off) = o;
                 }
             }
         }
@@ -301,18 +427,18 @@ rh_status rh_pack_weights_bf16(rh_ctx* ctx, const float* blob)
     return RH_OK;
 }
 
-template <int CIN, int MT, int TH, bool F32OUT>
+template <int CIN, int MT, int TH, bool F32OUT, bool SKIP>
 static hipError_t launch_conv(rh_ctx* ctx, const conv_args& a, int grid)
 {
-    constexpr int lds = 9 * (CIN / 16) * MT * 1024 + (TH + 2) * PW * CIN * 2;
+    constexpr int lds = 9 * (CIN / 16) * MT * 1024 + (TH + 2) * PW * CIN * 2 + 256;
     static bool attr_done = false;
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute((const void*)k_conv_mfma<CIN, MT, TH, F32OUT>,
+        hipError_t e = hipFuncSetAttribute((const void*)k_conv_mfma<CIN, MT, TH, F32OUT, SKIP>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    hipLaunchKernelGGL((k_conv_mfma<CIN, MT, TH, F32OUT>), dim3(grid), dim3(256), lds, ctx->stream, a);
+    hipLaunchKernelGGL((k_conv_mfma<CIN, MT, TH, F32OUT, SKIP>), dim3(grid), dim3(256), lds, ctx->stream, a);
     return hipSuccess;
 }
 
@@ -328,11 +454,11 @@ static rh_status conv(rh_ctx* ctx, const rh_layer& L, const __bf16* in, void* ou
     rh_prof_scope ps(ctx, last ? RH_PROF_CONV_LAST : RH_PROF_CONV);
     hipError_t e;
     if (L.cin == 64) {
-        if (last) e = (MT == 2) ? launch_conv<64, 2, 16, true>(ctx, a, grid) : launch_conv<64, 1, 16, true>(ctx, a, grid);
-        else e = launch_conv<64, 2, 16, false>(ctx, a, grid);
+        if (last) e = (MT == 2) ? launch_conv<64, 2, 16, true, false>(ctx, a, grid) : launch_conv<64, 1, 16, true, false>(ctx, a, grid);
+        else e = skip ? launch_conv<64, 2, 16, false, true>(ctx, a, grid) : launch_conv<64, 2, 16, false, false>(ctx, a, grid);
     } else {
-        if (last) e = (MT == 2) ? launch_conv<32, 2, 16, true>(ctx, a, grid) : launch_conv<32, 1, 16, true>(ctx, a, grid);
-        else e = launch_conv<32, 1, 16, false>(ctx, a, grid);
+        if (last) e = (MT == 2) ? launch_conv<32, 2, 16, true, false>(ctx, a, grid) : launch_conv<32, 1, 16, true, false>(ctx, a, grid);
+        else e = skip ? launch_conv<32, 1, 16, false, true>(ctx, a, grid) : launch_conv<32, 1, 16, false, false>(ctx, a, grid);
     }
     RH_HIP(ctx, e);
     return RH_OK;
