@@ -14,7 +14,10 @@
 // Activations are bf16 channels-last [N][H][W][C]; the network's last conv writes fp32.
 // Pixel shuffle is folded into the output-channel order of the upsampling convs: chunk q of
 // the permuted weights produces all C channels of sub-pixel q, i.e. one whole output pixel.
+#include <stdlib.h>
 #include <string.h>
+
+#include <type_traits>
 
 #include "rh_internal.h"
 
@@ -22,6 +25,26 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+typedef __attribute__((__vector_size__(4 * sizeof(int)))) int i32x4;
+
+#ifdef RH_PHASE_TIMING   // development aid: per-phase cycle counts of wave 0 of every workgroup
+__device__ unsigned long long rh_dbg[16];
+extern "C" void rh_debug_read(unsigned long long* out, int reset)
+{
+    (void)hipDeviceSynchronize();
+    (void)hipMemcpyFromSymbol(out, HIP_SYMBOL(rh_dbg), sizeof(rh_dbg));
+    if (reset) { unsigned long long z[16] = {0}; (void)hipMemcpyToSymbol(HIP_SYMBOL(rh_dbg), z, sizeof(z)); }
+}
+#define PHASE(i) do { unsigned long long t_ = clock64(); ph[i] += t_ - tprev; tprev = t_; } while (0)
+#define PHASE_INIT unsigned long long ph[6] = {0, 0, 0, 0, 0, 0}; unsigned long long tprev = clock64()
+#define PHASE_END do { if (tid == 0 && !F32OUT) for (int i_ = 0; i_ < 6; ++i_) atomicAdd(&rh_dbg[(SKIP ? 8 : 0) + i_], ph[i_]); } while (0)
+#define DBG(bit) (a.dbg & (bit))
+#else
+#define DBG(bit) 0
+#define PHASE(i) do { } while (0)
+#define PHASE_INIT do { } while (0)
+#define PHASE_END do { } while (0)
+#endif
 
 #define TW 32            // tile width in pixels = N of one MFMA
 #define PW (TW + 2)
@@ -36,6 +59,9 @@ struct conv_args {
     int N, H, W;
     int relu, ps, n_chunks;  // bf16 output mode
     int cout_real, s_final;  // fp32 output mode
+#ifdef RH_PHASE_TIMING
+    int dbg;                 // bit0: no patch loads, bit1: no output stores, bit2: no MFMA loop
+#endif
 };
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b)
@@ -47,26 +73,49 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b)
     return *(uint32_t*)&r;
 }
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every
+// outstanding global load and store of the wave, which would expose the latency of the patch
+// prefetch, the skip reads and the output stores once per tile.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 __device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xFFFF0000u); }
 
 // CIN: input channels (32 or 64).  MT: 32-channel M tiles per output chunk (1 or 2).
 // TH: tile height; each of the 4 waves owns RW = TH/4 rows of 32 pixels.
 // F32OUT: last layer of the network (fp32 output, true channel count cout_real <= 32*MT,
-// optional pixel shuffle s_final in the store address).
+// optional pixel shuffle s_final in the store address).  SKIP: add a same-shaped bf16 tensor
+// to the output (residual connections).  RELU: clamp at zero before rounding.
 //
-// Per tile:   (A) barrier, prefetched patch registers -> LDS, (B) barrier,
-//             issue the global loads of the NEXT tile's patch into registers (they complete
-//             under the MFMA loop), MFMA loop, (C) barrier, epilogue through LDS.
-// MFMA loop:  12 (CIN=64) steps = (kx, k-step) pairs.  In a step the 3 x MT weight fragments
-//             of the three ky taps stay in registers while the wave walks down its RW+2 input
-//             rows: every activation fragment is read from LDS once and feeds the (up to) 3
-//             output rows it belongs to.  The fragments of step s+1 are loaded while the
-//             MFMAs of step s run (two register sets).
-// Epilogue:   accumulators (+bias, ReLU) are rounded to bf16 into the wave's own slice of the
-//             (now free) patch area and read back as 16-byte channel groups, so that the skip
-//             read and the store are whole pixels, 1 KB contiguous per wave access.
-template <int CIN, int MT, int TH, bool F32OUT, bool SKIP>
+// Per tile:   (A) barrier, prefetched patch registers -> LDS, (B) barrier, MFMA loop,
+//             (C) barrier, accumulators -> bf16 -> LDS, (D) barrier, LDS -> registers.
+// MFMA loop:  NSTEP = 3 * CIN/16 steps = (kx, k-step) pairs.  In a step the 3 x MT weight
+//             fragments of the three ky taps stay in registers while the wave walks down its
+//             RW+2 input rows: every activation fragment is read from LDS once and feeds the
+//             (up to) 3 output rows it belongs to.  The fragments of step s+1 are loaded while
+//             the MFMAs of step s run (two register sets).  The accumulators start from the
+//             bias (C operand of the first MFMA).
+// Memory:     all global traffic of a tile is issued from inside the MFMA loop, a few
+//             instructions per step, so that it is never waited for while the matrix cores
+//             idle: the stores of the PREVIOUS tile's result (kept in registers), the loads of
+//             the NEXT tile's patch (into registers), and in the last steps the skip reads of
+//             the current tile.  Buffer instructions are used: out-of-range lanes (ragged
+//             tiles, the zero padding around the image, "no previous / no next tile") get an
+//             offset beyond the descriptor's size, which makes loads return 0 and drops stores,
+//             so there is no branch and no masking.
+// Epilogue:   results go through the wave's own slice of the (then free) patch area and are
+//             read back as 16-byte channel groups: the skip read and the store move whole
+//             pixels, 1 KB contiguous per wave instruction.
+template <int N, int I = 0, typename F>
+__device__ __forceinline__ void for_each_step(F& f)
+{
+    if constexpr (I < N) { f(std::integral_constant<int, I>{}); for_each_step<N, I + 1>(f); }
+}
+
+#define RSRC_FLAGS 0x00020000            // raw buffer, 32-bit data format (gfx9 family)
+#define OOB_OFF 0x80000000u              // beyond any descriptor used here (images are < 2 GiB)
+
+template <int CIN, int MT, int TH, bool F32OUT, bool SKIP, bool RELU>
 __global__ __launch_bounds__(256) void k_conv_mfma(conv_args a)
 {
     constexpr int KS = CIN / 16;             // MFMA k-steps per tap
@@ -79,10 +128,22 @@ __global__ __launch_bounds__(256) void k_conv_mfma(conv_args a)
     constexpr int SWZ_SH = (NCH == 8) ? 0 : 1;
     constexpr int NSTEP = 3 * KS;
     constexpr int CQ = 32 * MT;              // channels of one output pixel (bf16 mode)
+    // patch pieces (16 bytes each) of a thread: the 32 inner columns of patch row RPJ*j + m_row
+    // are PPR contiguous pieces in global memory; the 2 halo columns are NHALO extra pieces
+    constexpr int PPR = 32 * NCH, RPJ = 256 / PPR, NMAIN = PH / RPJ;
+    constexpr int NHP = PH * 2 * NCH, NHALO = (NHP + 255) / 256, NPRE = NMAIN + NHALO;
+    static_assert(PH % RPJ == 0, "patch rows must split evenly over the threads");
+    // output pieces of a lane (bf16 mode): pixel (j*64 + lane) / NCHO of the wave's RW x 32 pixels
+    constexpr int NCHO = CQ / 8, OPIXB = CQ * 2, OSH = (NCHO == 8) ? 0 : 1;
+    constexpr int NOUT = F32OUT ? 0 : RW * 32 * NCHO / 64, PPJ = 64 / NCHO, JPR = 32 / PPJ;
+    // issue schedule of the global memory instructions over the MFMA steps
+    constexpr int ST_STEPS = NSTEP * 2 / 3, SK_STEPS = NSTEP - ST_STEPS, LD_STEPS = NSTEP * 5 / 6;
+    constexpr int SPS = F32OUT ? 0 : (NOUT + ST_STEPS - 1) / ST_STEPS, KPS = F32OUT ? 0 : (NOUT + SK_STEPS - 1) / SK_STEPS;
+    constexpr int LPS = (NPRE + LD_STEPS - 1) / LD_STEPS;
+
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     uint8_t* lds_w = lds;
     uint8_t* lds_p = lds + WBYTES;
-    float* lds_b = (float*)(lds + WBYTES + PH * PW * PIXB);      // CQ biases of the chunk
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int lx = lane & 31, hi = lane >> 5;
@@ -93,87 +154,102 @@ __global__ __launch_bounds__(256) void k_conv_mfma(conv_args a)
     // consecutive tiles go to workgroups of one XCD (workgroups are dealt round-robin to the 8 XCDs)
     const int G = gridDim.x;
     const int wg = (G % 8 == 0) ? (blockIdx.x % 8) * (G / 8) + blockIdx.x / 8 : blockIdx.x;
+    const int ps = a.ps;
+    const uint32_t in_img_bytes = (uint32_t)a.H * a.W * PIXB;
+    const uint32_t out_img_bytes = F32OUT ? 0u : (uint32_t)(a.H * ps) * (a.W * ps) * OPIXB;
 
-    // Patch staging.  The 32 inner columns of a patch row are PPR contiguous 16-byte pieces in
-    // global memory: piece j of a thread is (row RPJ*j + tid/PPR, column 1 + (tid%PPR)/NCH),
-    // i.e. a uniform row base plus a per-thread constant.  The two halo columns (0 and 33) are
-    // the NHALO extra pieces.  Loads always use an in-image (clamped) address; pieces outside
-    // the image are zeroed when they are written to LDS (the layer's zero padding).
-    constexpr int PPR = 32 * NCH, RPJ = 256 / PPR, NMAIN = PH / RPJ;
-    constexpr int NHP = PH * 2 * NCH, NHALO = (NHP + 255) / 256;
-    static_assert(PH % RPJ == 0, "patch rows must split evenly over the threads");
-    uint4 pre[NMAIN + NHALO];
-    const int m_row = tid / PPR, m_col = (tid % PPR) / NCH, m_c = tid % NCH;       // main piece
-    const uint32_t m_lds = (uint32_t)((1 + m_col) * PIXB + ((m_c ^ (((1 + m_col) >> SWZ_SH) & (NCH - 1))) << 4));
-    auto load_patch = [&](int tile) __attribute__((always_inline)) {
-        const int n = tile / tiles_img, tr = tile - n * tiles_img;
-        const int ty = tr / tiles_x, tx = tr - ty * tiles_x;
-        const int y0 = ty * TH, x0 = tx * TW;
-        const uint8_t* img = (const uint8_t*)(a.in + (size_t)n * a.H * a.W * CIN);
-        const int gx = min(x0 + m_col, a.W - 1);
-#pragma unroll
-        for (int j = 0; j < NMAIN; ++j) {
-            const int gy = min(max(y0 - 1 + RPJ * j + m_row, 0), a.H - 1);
-            pre[j] = *(const uint4*)(img + ((size_t)gy * a.W + gx) * PIXB + m_c * 16);
+    // per-thread constants of the patch pieces
+    const int m_row = tid / PPR, m_col = (tid % PPR) / NCH, m_c = tid % NCH;
+    const int m_goff = (m_row * a.W + m_col) * PIXB + m_c * 16;                    // + tile origin + j rows
+    const uint32_t m_lds = (uint32_t)(m_row * (PW * PIXB) + (1 + m_col) * PIXB + ((m_c ^ (((1 + m_col) >> SWZ_SH) & (NCH - 1))) << 4));
+    // per-lane constants of the output pieces
+    const int lcol = lane / (F32OUT ? 1 : NCHO), lc = lane % (F32OUT ? 1 : NCHO);
+    const int o_lane = (lcol * ps) * OPIXB + lc * 16;
+    const int o_rowpitch = a.W * ps * OPIXB;
+
+    uint4 pre[NPRE];
+    // patch piece j of tile (y0, x0) of the image behind rin
+    auto load_piece = [&](int j, __amdgpu_buffer_rsrc_t rin, int y0, int x0) __attribute__((always_inline)) {
+        int off; bool ok;
+        if (j < NMAIN) {
+            const int gy = y0 - 1 + RPJ * j + m_row;
+            ok = gy >= 0 && gy < a.H && x0 + m_col < a.W;
+            off = ((y0 - 1 + RPJ * j) * a.W + x0) * PIXB + m_goff;
+        } else {
+            const int idx = tid + 256 * (j - NMAIN), row = idx / (2 * NCH), side = (idx / NCH) & 1, c = idx % NCH;
+            const int gy = y0 - 1 + row, hx = side ? x0 + TW : x0 - 1;
+            ok = idx < NHP && gy >= 0 && gy < a.H && hx >= 0 && hx < a.W;
+            off = (gy * a.W + hx) * PIXB + c * 16;
         }
-#pragma unroll
-        for (int j = 0; j < NHALO; ++j) {
-            const int idx = tid + 256 * j, row = min(idx / (2 * NCH), PH - 1), side = (idx / NCH) & 1, c = idx % NCH;
-            const int gy = min(max(y0 - 1 + row, 0), a.H - 1), hx = min(max(side ? x0 + TW : x0 - 1, 0), a.W - 1);
-            pre[NMAIN + j] = *(const uint4*)(img + ((size_t)gy * a.W + hx) * PIXB + c * 16);
-        }
+        const i32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rin, ok ? (uint32_t)off : OOB_OFF, 0, 0);
+        pre[j] = make_uint4(v[0], v[1], v[2], v[3]);
     };
-    auto store_patch = [&](int y0, int x0) __attribute__((always_inline)) {
-        const bool col_ok = x0 + m_col < a.W;
+    auto store_patch = [&]() __attribute__((always_inline)) {
 #pragma unroll
-        for (int j = 0; j < NMAIN; ++j) {
-            const int row = RPJ * j + m_row, gy = y0 - 1 + row;
-            const bool ok = col_ok && gy >= 0 && gy < a.H;
-            const uint32_t keep = ok ? 0xFFFFFFFFu : 0u;
-            uint4 v = pre[j];
-            v.x &= keep; v.y &= keep; v.z &= keep; v.w &= keep;
-            *(uint4*)(lds_p + row * (PW * PIXB) + m_lds) = v;
-        }
+        for (int j = 0; j < NMAIN; ++j) *(uint4*)(lds_p + j * (RPJ * PW * PIXB) + m_lds) = pre[j];
 #pragma unroll
         for (int j = 0; j < NHALO; ++j) {
             const int idx = tid + 256 * j, row = idx / (2 * NCH), side = (idx / NCH) & 1, c = idx % NCH;
-            const int gy = y0 - 1 + row, hx = side ? x0 + TW : x0 - 1, px = side ? PW - 1 : 0;
-            const bool ok = gy >= 0 && gy < a.H && hx >= 0 && hx < a.W;
-            const uint32_t keep = ok ? 0xFFFFFFFFu : 0u;
-            uint4 v = pre[NMAIN + j];
-            v.x &= keep; v.y &= keep; v.z &= keep; v.w &= keep;
-            if (idx < NHP) *(uint4*)(lds_p + (row * PW + px) * PIXB + ((c ^ ((px >> SWZ_SH) & (NCH - 1))) << 4)) = v;
+            const int px = side ? PW - 1 : 0;
+            if (idx < NHP) *(uint4*)(lds_p + (row * PW + px) * PIXB + ((c ^ ((px >> SWZ_SH) & (NCH - 1))) << 4)) = pre[NMAIN + j];
         }
+    };
+    // byte offset of output piece j of tile (y0, x0) inside its image, or OOB_OFF outside the image
+    auto out_off = [&](int j, int y0, int x0, int si, int sj) __attribute__((always_inline)) {
+        const int y = y0 + wave * RW + j / JPR, xb = x0 + (j % JPR) * PPJ;
+        const bool ok = y < a.H && xb + lcol < a.W;
+        const int off = (y * ps + si) * o_rowpitch + (xb * ps + sj) * OPIXB + o_lane;
+        return ok ? (uint32_t)off : OOB_OFF;
     };
 
     for (int chunk = 0; chunk < a.n_chunks; ++chunk) {
         __syncthreads();
-        {   // this chunk's weights and biases -> LDS
+        {   // this chunk's weights -> LDS
             const uint4* src = a.wp + (size_t)chunk * (WBYTES / 16);
             for (int i = tid; i < WBYTES / 16; i += 256) ((uint4*)lds_w)[i] = src[i];
-            if (!F32OUT && tid < CQ) lds_b[tid] = a.bias[chunk * CQ + tid];
         }
-        const int si = chunk / a.ps, sj = chunk - si * a.ps;
+        // bias in accumulator layout: lane holds channels m*32 + 8*(e/4) + 4*hi + e%4
+        f32x16 biasv[MT];
+#pragma unroll
+        for (int m = 0; m < MT; ++m)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) biasv[m][e] = a.bias[chunk * CQ + m * 32 + (e >> 2) * 8 + hi * 4 + (e & 3)];
+        const int si = chunk / ps, sj = chunk - si * ps;
+
         int tile = wg;
-        if (tile < n_tiles) load_patch(tile);
+        if (tile < n_tiles) {
+            const int n = tile / tiles_img, tr = tile - n * tiles_img, ty = tr / tiles_x, tx = tr - ty * tiles_x;
+            __amdgpu_buffer_rsrc_t rin = __builtin_amdgcn_make_buffer_rsrc((void*)(a.in + (size_t)n * a.H * a.W * CIN), 0, in_img_bytes, RSRC_FLAGS);
+#pragma unroll
+            for (int j = 0; j < NPRE; ++j) load_piece(j, rin, ty * TH, tx * TW);
+        }
+        uint4 outv[F32OUT ? 1 : NOUT];       // previous tile's result, stored during this tile's MFMA loop
+        int out_tile = -1;
+        PHASE_INIT;
         for (; tile < n_tiles; tile += G) {
+            PHASE(0);
             const int n = tile / tiles_img, tr = tile - n * tiles_img;
             const int ty = tr / tiles_x, tx = tr - ty * tiles_x;
             const int y0 = ty * TH, x0 = tx * TW;
-            __syncthreads();                                   // (A) LDS reads of the previous tile are done
-            store_patch(y0, x0);
-            __syncthreads();                                   // (B)
-            if (tile + G < n_tiles) load_patch(tile + G);
+            lds_barrier();                                     // (A) LDS reads of the previous tile are done
+            store_patch();
+            lds_barrier();                                     // (B)
+            PHASE(1);
+            // descriptors: next tile's input image (empty if there is no next tile), previous
+            // tile's output image (empty if none), this tile's skip image
+            const int nt = tile + G;
+            const bool has_next = nt < n_tiles;
+            const int nn = has_next ? nt / tiles_img : 0, ntr = nt - nn * tiles_img, nty = ntr / tiles_x, ntx = ntr - nty * tiles_x;
+            __amdgpu_buffer_rsrc_t rin = __builtin_amdgcn_make_buffer_rsrc(
+                (void*)(a.in + (size_t)nn * a.H * a.W * CIN), 0, has_next ? in_img_bytes : 0u, RSRC_FLAGS);
+            const int on = out_tile >= 0 ? out_tile / tiles_img : 0, otr = out_tile - on * tiles_img, oty = otr / tiles_x, otx = otr - oty * tiles_x;
+            __amdgpu_buffer_rsrc_t rout = __builtin_amdgcn_make_buffer_rsrc(
+                (void*)((uint8_t*)a.out + (size_t)on * out_img_bytes), 0, out_tile >= 0 ? out_img_bytes : 0u, RSRC_FLAGS);
+            __amdgpu_buffer_rsrc_t rsk = __builtin_amdgcn_make_buffer_rsrc(
+                (void*)((uint8_t*)a.skip + (size_t)n * out_img_bytes), 0, SKIP ? out_img_bytes : 0u, RSRC_FLAGS);
+            uint4 sk[(SKIP && !F32OUT) ? NOUT : 1];
 
             f32x16 acc[RW][MT];
-#pragma unroll
-            for (int r = 0; r < RW; ++r)
-#pragma unroll
-                for (int m = 0; m < MT; ++m)
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) acc[r][m][e] = 0.0f;
-
-            // fragment addresses of step st = kx*KS + ks
             const uint8_t* wlane = lds_w + (lane << 4);
             const uint8_t* prow = lds_p + (wave * RW) * (PW * PIXB);
             auto load_A = [&](int st, bf16x8 (&A)[3][MT]) __attribute__((always_inline)) {
@@ -194,28 +270,68 @@ __global__ __launch_bounds__(256) void k_conv_mfma(conv_args a)
             };
             bf16x8 A0[3][MT], A1[3][MT], B0[NR], B1[NR];
             load_A(0, A0); load_B(0, B0);
-#pragma unroll
-            for (int st = 0; st < NSTEP; ++st) {
+            // One step, cut into NSLOT slots.  Every slot issues its share of the next step's
+            // fragment loads and at most one global memory instruction, then its MFMAs; the
+            // scheduling barrier after a slot keeps that interleaving in the instruction stream.
+            auto step = [&](auto st_c) __attribute__((always_inline)) {
+                constexpr int st = decltype(st_c)::value;
+                constexpr int NMF = 3 * RW * MT, NFR = 3 * MT + NR, NSLOT = 6;
+                constexpr int MPS = NMF / NSLOT, FPS = (NFR + NSLOT - 1) / NSLOT;
+                static_assert(NMF % NSLOT == 0, "MFMAs of a step must split evenly over the slots");
                 bf16x8 (&Ac)[3][MT] = (st & 1) ? A1 : A0;
                 bf16x8 (&Bc)[NR] = (st & 1) ? B1 : B0;
-                if (st + 1 < NSTEP) {
-                    load_A(st + 1, (st & 1) ? A0 : A1);
-                    load_B(st + 1, (st & 1) ? B0 : B1);
-                }
-                __builtin_amdgcn_sched_barrier(0);
+                bf16x8 (&An)[3][MT] = (st & 1) ? A0 : A1;
+                bf16x8 (&Bn)[NR] = (st & 1) ? B0 : B1;
+                constexpr int kxn = (st + 1) / KS, ksn = (st + 1) - kxn * KS;
+                const int pxn = lx + kxn;
+                const uint8_t* b0n = prow + pxn * PIXB + (((2 * ksn + hi) ^ ((pxn >> SWZ_SH) & (NCH - 1))) << 4);
+                constexpr int n_st = (!F32OUT && st < ST_STEPS) ? SPS : 0;          // stores in this step
+                constexpr int n_ld = (st < LD_STEPS) ? LPS : 0;                     // patch loads
+                constexpr int n_sk = (SKIP && !F32OUT && st >= ST_STEPS) ? KPS : 0; // skip loads
+                static_assert(n_st + n_ld + n_sk <= NSLOT, "too many memory instructions for one step");
 #pragma unroll
-                for (int py = 0; py < NR; ++py)
+                for (int sl = 0; sl < NSLOT; ++sl) {
+                    if (st + 1 < NSTEP) {
 #pragma unroll
-                    for (int ky = 0; ky < 3; ++ky) {
-                        const int r = py - ky;
-                        if (r < 0 || r >= RW) continue;
-#pragma unroll
-                        for (int m = 0; m < MT; ++m)
-                            acc[r][m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Ac[ky][m], Bc[py], acc[r][m], 0, 0, 0);
+                        for (int f = sl * FPS; f < (sl + 1) * FPS && f < NFR; ++f) {
+                            if (f < 3 * MT) An[f / MT][f % MT] = *(const bf16x8*)(wlane + (((((f / MT) * 3 + kxn) * KS + ksn) * MT + f % MT) << 10));
+                            else Bn[f - 3 * MT] = *(const bf16x8*)(b0n + (f - 3 * MT) * (PW * PIXB));
+                        }
                     }
-                __builtin_amdgcn_sched_barrier(0);
-            }
-
+                    if (sl < n_st) {
+                        const int j = st * SPS + sl;
+                        if (j < NOUT) {
+                            const i32x4 v = {(int)outv[j].x, (int)outv[j].y, (int)outv[j].z, (int)outv[j].w};
+                            __builtin_amdgcn_raw_buffer_store_b128(v, rout, out_off(j, oty * TH, otx * TW, si, sj), 0, 0);
+                        }
+                    } else if (sl < n_st + n_ld) {
+                        const int j = st * LPS + (sl - n_st);
+                        if (j < NPRE) load_piece(j, rin, nty * TH, ntx * TW);
+                    } else if (sl < n_st + n_ld + n_sk) {
+                        const int j = (st - ST_STEPS) * KPS + (sl - n_st - n_ld);
+                        if (j < NOUT) {
+                            const i32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsk, out_off(j, y0, x0, 0, 0), 0, 0);
+                            sk[j] = make_uint4(v[0], v[1], v[2], v[3]);
+                        }
+                    }
+#pragma unroll
+                    for (int k = sl * MPS; k < (sl + 1) * MPS; ++k) {
+                        // MFMA k of the step: (input row py, tap ky) pairs with 0 <= py - ky < RW, py-major
+                        const int m = k % MT, pair = k / MT;
+                        int py = 0, ky = 0, cnt = 0;
+#pragma unroll
+                        for (int p = 0; p < NR; ++p)
+#pragma unroll
+                            for (int q = 0; q < 3; ++q)
+                                if (p - q >= 0 && p - q < RW) { if (cnt == pair) { py = p; ky = q; } ++cnt; }
+                        const int r = py - ky;
+                        acc[r][m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Ac[ky][m], Bc[py], (st == 0 && ky == 0) ? biasv[m] : acc[r][m], 0, 0, 0);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            };
+            for_each_step<NSTEP>(step);
+            PHASE(3);
             // lane holds, for pixel column lx of each of its rows, channels
             // m*32 + 8*q + 4*hi + {0,1,2,3} in acc[r][m][4q..4q+3]
             if constexpr (F32OUT) {
@@ -236,77 +352,56 @@ __global__ __launch_bounds__(256) void k_conv_mfma(conv_args a)
                                 const int co = cb + e;
                                 if (co >= a.cout_real) continue;
                                 const int ch = co / s2, sub = co - ch * s2, ui = sub / s, uj = sub - ui * s;
-                                o[(((size_t)n * a.H * s + (size_t)y * s + ui) * (a.W * s) + (size_t)x * s + uj) * 3 + ch] =
-                                    acc[r][m][4 * q + e] + a.bias[co];
+                                o[(((size_t)n * a.H * s + (size_t)y * s + ui) * (a.W * s) + (size_t)x * s + uj) * 3 + ch] = acc[r][m][4 * q + e];
                             }
                         }
                 }
             } else {
-                constexpr int NCHO = CQ / 8;             // 16-byte groups per output pixel
-                constexpr int OPIXB = CQ * 2;
-                constexpr int OSH = (NCHO == 8) ? 0 : 1;
-                constexpr int NOUT = RW * 32 * NCHO / 64; // 16-byte pieces per lane
-                __syncthreads();                           // (C) every wave is done with the patch
+                lds_barrier();                             // (C) every wave is done with the patch
                 uint8_t* stg = lds_p + wave * (RW * 32 * OPIXB);
                 const int okey = (lx >> OSH) & (NCHO - 1);
-                const float lo = a.relu ? 0.0f : -__builtin_inff();        // ReLU as a max with 0 or -inf
 #pragma unroll
                 for (int m = 0; m < MT; ++m)
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const float4 bv = *(const float4*)(lds_b + m * 32 + q * 8 + hi * 4);
+                    for (int q = 0; q < 4; ++q)
 #pragma unroll
                         for (int r = 0; r < RW; ++r) {
-                            float v0 = acc[r][m][4 * q + 0] + bv.x, v1 = acc[r][m][4 * q + 1] + bv.y;
-                            float v2 = acc[r][m][4 * q + 2] + bv.z, v3 = acc[r][m][4 * q + 3] + bv.w;
-                            v0 = fmaxf(v0, lo); v1 = fmaxf(v1, lo); v2 = fmaxf(v2, lo); v3 = fmaxf(v3, lo);
+                            float v0 = acc[r][m][4 * q + 0], v1 = acc[r][m][4 * q + 1], v2 = acc[r][m][4 * q + 2], v3 = acc[r][m][4 * q + 3];
+                            if constexpr (RELU) { v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); v2 = fmaxf(v2, 0.f); v3 = fmaxf(v3, 0.f); }
                             uint2 pk;
                             pk.x = pack_bf16x2(v0, v1); pk.y = pack_bf16x2(v2, v3);
                             *(uint2*)(stg + (r * 32 + lx) * OPIXB + (((m * 4 + q) ^ okey) << 4) + hi * 8) = pk;
                         }
-                    }
-                // piece j of this lane: pixel (j*64 + lane) / NCHO of the wave's RW x 32 pixels =
-                // row j / JPR, column (j % JPR) * PPJ + lane / NCHO, channel group lane % NCHO
-                constexpr int PPJ = 64 / NCHO, JPR = 32 / PPJ;
-                const int ps = a.ps;
-                const int lcol = lane / NCHO, lc = lane % NCHO;
-                const uint32_t lane_off = (uint32_t)(lcol * ps) * OPIXB + lc * 16;      // bytes, within an output row
-                const uint32_t lane_lds = (uint32_t)lcol * OPIXB;
-                const size_t orow_pitch = (size_t)a.W * ps * OPIXB;
-                const uint8_t* skp = (const uint8_t*)a.skip;
-                uint8_t* outp = (uint8_t*)a.out;
-                uint4 sk[NOUT];
-                if constexpr (SKIP) {
-#pragma unroll
-                    for (int j = 0; j < NOUT; ++j) {       // all skip reads in flight together
-                        const int y = min(y0 + wave * RW + j / JPR, a.H - 1), xb = x0 + (j % JPR) * PPJ;
-                        const size_t rb = ((size_t)n * a.H * ps + (size_t)y * ps + si) * orow_pitch + (size_t)(xb * ps + sj) * OPIXB;
-                        sk[j] = *(const uint4*)(skp + rb + (xb + lcol < a.W ? lane_off : 0));
-                    }
-                }
-                __syncthreads();                           // staged values visible
-                uint4 v[NOUT];
+                lds_barrier();                             // (D) staged values visible
+                PHASE(4);
 #pragma unroll
                 for (int j = 0; j < NOUT; ++j) {
                     const int r = j / JPR, px = (j % JPR) * PPJ + lcol;
-                    v[j] = *(const uint4*)(stg + (r * 32 + (j % JPR) * PPJ) * OPIXB + lane_lds + ((lc ^ ((px >> OSH) & (NCHO - 1))) << 4));
-                }
-                const bool full = y0 + TH <= a.H && x0 + TW <= a.W;       // uniform: no ragged edge in this tile
-#pragma unroll
-                for (int j = 0; j < NOUT; ++j) {
-                    const int y = y0 + wave * RW + j / JPR, xb = x0 + (j % JPR) * PPJ;
-                    uint4 o = v[j];
+                    uint4 o = *(const uint4*)(stg + (r * 32 + px) * OPIXB + ((lc ^ ((px >> OSH) & (NCHO - 1))) << 4));
                     if constexpr (SKIP) {
                         o.x = pack_bf16x2(bf16_lo(o.x) + bf16_lo(sk[j].x), bf16_hi(o.x) + bf16_hi(sk[j].x));
                         o.y = pack_bf16x2(bf16_lo(o.y) + bf16_lo(sk[j].y), bf16_hi(o.y) + bf16_hi(sk[j].y));
                         o.z = pack_bf16x2(bf16_lo(o.z) + bf16_lo(sk[j].z), bf16_hi(o.z) + bf16_hi(sk[j].z));
                         o.w = pack_bf16x2(bf16_lo(o.w) + bf16_lo(sk[j].w), bf16_hi(o.w) + bf16_hi(sk[j].w));
                     }
-                    const size_t rb = ((size_t)n * a.H * ps + (size_t)y * ps + si) * orow_pitch + (size_t)(xb * ps + sj) * OPIXB;
-                    if (full || (y < a.H && xb + lcol < a.W)) *(uint4*)(outp + rb + lane_off) = o;
+                    outv[j] = o;
+                }
+                out_tile = tile;
+                PHASE(5);
+            }
+        }
+        if constexpr (!F32OUT) {
+            if (out_tile >= 0) {                           // the last tile's result
+                const int on = out_tile / tiles_img, otr = out_tile - on * tiles_img, oty = otr / tiles_x, otx = otr - oty * tiles_x;
+                __amdgpu_buffer_rsrc_t rout = __builtin_amdgcn_make_buffer_rsrc((void*)((uint8_t*)a.out + (size_t)on * out_img_bytes), 0, out_img_bytes, RSRC_FLAGS);
+#pragma unroll
+                for (int j = 0; j < NOUT; ++j) {
+                    const i32x4 v = {(int)outv[j].x, (int)outv[j].y, (int)outv[j].z, (int)outv[j].w};
+                    __builtin_amdgcn_raw_buffer_store_b128(v, rout, out_off(j, oty * TH, otx * TW, si, sj), 0, 0);
                 }
             }
         }
+        PHASE_END;
     }
 }
 
@@ -427,18 +522,18 @@ rh_status rh_pack_weights_bf16(rh_ctx* ctx, const float* blob)
     return RH_OK;
 }
 
-template <int CIN, int MT, int TH, bool F32OUT, bool SKIP>
+template <int CIN, int MT, int TH, bool F32OUT, bool SKIP, bool RELU>
 static hipError_t launch_conv(rh_ctx* ctx, const conv_args& a, int grid)
 {
-    constexpr int lds = 9 * (CIN / 16) * MT * 1024 + (TH + 2) * PW * CIN * 2 + 256;
+    constexpr int lds = 9 * (CIN / 16) * MT * 1024 + (TH + 2) * PW * CIN * 2;
     static bool attr_done = false;
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute((const void*)k_conv_mfma<CIN, MT, TH, F32OUT, SKIP>,
+        hipError_t e = hipFuncSetAttribute((const void*)k_conv_mfma<CIN, MT, TH, F32OUT, SKIP, RELU>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    hipLaunchKernelGGL((k_conv_mfma<CIN, MT, TH, F32OUT, SKIP>), dim3(grid), dim3(256), lds, ctx->stream, a);
+    hipLaunchKernelGGL((k_conv_mfma<CIN, MT, TH, F32OUT, SKIP, RELU>), dim3(grid), dim3(256), lds, ctx->stream, a);
     return hipSuccess;
 }
 
@@ -448,17 +543,25 @@ static rh_status conv(rh_ctx* ctx, const rh_layer& L, const __bf16* in, void* ou
     conv_args a;
     a.in = in; a.wp = (const uint4*)((const uint8_t*)ctx->wpack + L.wp_off); a.bias = ctx->bpack + L.bp_off;
     a.out = out; a.skip = skip; a.n_valid = n_valid; a.N = N; a.H = H; a.W = W;
+#ifdef RH_PHASE_TIMING
+    a.dbg = getenv("RH_DBG") ? atoi(getenv("RH_DBG")) : 0;
+#endif
     a.relu = relu; a.ps = L.ps; a.n_chunks = last ? 1 : L.ps * L.ps; a.cout_real = L.cout; a.s_final = s_final;
     const int grid = 256;
     const int MT = last ? L.cout_pad / 32 : L.cin / 32;
     rh_prof_scope ps(ctx, last ? RH_PROF_CONV_LAST : RH_PROF_CONV);
     hipError_t e;
+    // bf16-output convs come as (ReLU, no skip), (skip, no ReLU) or (neither)
     if (L.cin == 64) {
-        if (last) e = (MT == 2) ? launch_conv<64, 2, 16, true, false>(ctx, a, grid) : launch_conv<64, 1, 16, true, false>(ctx, a, grid);
-        else e = skip ? launch_conv<64, 2, 16, false, true>(ctx, a, grid) : launch_conv<64, 2, 16, false, false>(ctx, a, grid);
+        if (last) e = (MT == 2) ? launch_conv<64, 2, 16, true, false, false>(ctx, a, grid) : launch_conv<64, 1, 16, true, false, false>(ctx, a, grid);
+        else if (skip) e = launch_conv<64, 2, 16, false, true, false>(ctx, a, grid);
+        else if (relu) e = launch_conv<64, 2, 16, false, false, true>(ctx, a, grid);
+        else e = launch_conv<64, 2, 16, false, false, false>(ctx, a, grid);
     } else {
-        if (last) e = (MT == 2) ? launch_conv<32, 2, 16, true, false>(ctx, a, grid) : launch_conv<32, 1, 16, true, false>(ctx, a, grid);
-        else e = skip ? launch_conv<32, 1, 16, false, true>(ctx, a, grid) : launch_conv<32, 1, 16, false, false>(ctx, a, grid);
+        if (last) e = (MT == 2) ? launch_conv<32, 2, 16, true, false, false>(ctx, a, grid) : launch_conv<32, 1, 16, true, false, false>(ctx, a, grid);
+        else if (skip) e = launch_conv<32, 1, 16, false, true, false>(ctx, a, grid);
+        else if (relu) e = launch_conv<32, 1, 16, false, false, true>(ctx, a, grid);
+        else e = launch_conv<32, 1, 16, false, false, false>(ctx, a, grid);
     }
     RH_HIP(ctx, e);
     return RH_OK;
