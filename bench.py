@@ -59,6 +59,12 @@ def main():
     ap.add_argument("--config", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-frame-based", action="store_true")
+    ap.add_argument("--sync-counts", action="store_true",
+                    help="read the bin count back to the host after rh_pack (one synchronisation per step) and "
+                         "enhance exactly that many bins, instead of passing the device-side count")
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
+                    help="also run one plain device copy of this many MiB (reference for scaling rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (--gpus 1); no multi-GPU figure exists", file=sys.stderr)
@@ -88,9 +94,17 @@ def main():
         nonlocal po
         mask, lst, n_sel = rh.select_regions(d_imp, seg_rows)
         po = rh.pack(d_frames, d_imp, mask, lst, n_sel, out=po)
-        rh.enhance(po.bins, n=max_bins, n_valid=po.counts[1:2], out=net_out)   # device-side bin count
+        if args.sync_counts:
+            rh.enhance(po.bins, n=rh.read_counts(po.counts)[1], out=net_out)
+        else:
+            rh.enhance(po.bins, n=max_bins, n_valid=po.counts[1:2], out=net_out)   # device-side bin count
         rh.unpack(net_out, po.places, po.counts[3:4], d_frames, out=hr)
 
+    if args.calibrate_copy:
+        src = torch.full((args.calibrate_copy << 20,), 7, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -128,7 +142,7 @@ def main():
                    "occupy_ratio": 256.0 * k_sel / (n_bins * S * S) if n_bins else 0.0},
         "output_mpixel_per_s": out_mpix,
         "kernel_ms_per_step": {k: v[0] / args.steps for k, v in prof.items()},
-        "roofline": {"bound": "mfma", "kernel": "k_conv_mfma<64,2,16,false>", "achieved": achieved / 1e12,
+        "roofline": {"bound": "mfma", "kernel": "k_conv_mfma<64,2,16,false,*,*> (bf16-output convs: ReLU, skip and plain variants)", "achieved": achieved / 1e12,
                      "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK,
                      "traffic": None, "avg_launch_us": avg_launch_s * 1e6, "launches_per_step": conv_n / args.steps,
                      "flop_per_launch": flop_per_launch},

@@ -173,8 +173,9 @@ rh_status rh_identity_places(rh_ctx* ctx, int32_t F, rh_mbplace* places, uint32_
 rh_status rh_read_counts(rh_ctx* ctx, const uint32_t* counts, uint32_t out[4]);
 
 /*
- * Measurement aid (not part of the method): when enabled, every kernel launch of the four
- * calls is bracketed by HIP events on the context's stream, grouped in the classes below.
+ * Measurement aid (not part of the method): when enabled, the kernel launches of the four
+ * calls are bracketed by HIP events on the context's stream, one event pair around each run of
+ * consecutive launches of a class (no event is placed between back-to-back launches).
  * rh_profile_read synchronises, adds up the elapsed times and launch counts since the last
  * read into ms[RH_PROF_N] / launches[RH_PROF_N] (host arrays) and resets them.
  * RH_PROF_CONV is the bf16 MFMA conv with C input and bf16 output channels (the body and the

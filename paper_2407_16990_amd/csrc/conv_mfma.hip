@@ -549,7 +549,6 @@ static rh_status conv(rh_ctx* ctx, const rh_layer& L, const __bf16* in, void* ou
     a.relu = relu; a.ps = L.ps; a.n_chunks = last ? 1 : L.ps * L.ps; a.cout_real = L.cout; a.s_final = s_final;
     const int grid = 256;
     const int MT = last ? L.cout_pad / 32 : L.cin / 32;
-    rh_prof_scope ps(ctx, last ? RH_PROF_CONV_LAST : RH_PROF_CONV);
     hipError_t e;
     // bf16-output convs come as (ReLU, no skip), (skip, no ReLU) or (neither)
     if (L.cin == 64) {
@@ -594,11 +593,16 @@ rh_status rh_launch_enhance_bf16(rh_ctx* ctx, const uint8_t* in, int N, int H, i
         if (C == 64) hipLaunchKernelGGL(k_head_bf16<64>, dim3(grid), dim3(256), 0, ctx->stream, in, hw, hb, h, N, H, W, head_relu, n_valid);
         else hipLaunchKernelGGL(k_head_bf16<32>, dim3(grid), dim3(256), 0, ctx->stream, in, hw, hb, h, N, H, W, head_relu, n_valid);
     }
-#define CONV(...) do { st = conv(ctx, __VA_ARGS__); if (st != RH_OK) return st; } while (0)
+    // one event pair around the run of bf16-output convs (they are launched back to back) and
+    // one around the last conv: per-launch events would put a bubble between the launches
+    uint32_t n_conv = 0;
+    rh_prof_begin(ctx, RH_PROF_CONV);
+#define CONV(...) do { st = conv(ctx, __VA_ARGS__); if (st != RH_OK) return st; ++n_conv; } while (0)
+#define LAST_CONV(...) do { rh_prof_end(ctx, n_conv); rh_prof_scope ps_(ctx, RH_PROF_CONV_LAST); st = conv(ctx, __VA_ARGS__); if (st != RH_OK) return st; } while (0)
     if (d.topology == RH_NET_PLAIN) {
         const __bf16* x = h;
         for (int l = 0; l < d.n_blocks - 2; ++l) { __bf16* o = (x == a) ? t : a; CONV(L[li++], x, o, nullptr, N, H, W, 1, false, 1, n_valid); x = o; }
-        CONV(L[li++], x, out, nullptr, N, H, W, 0, true, s, n_valid);
+        LAST_CONV(L[li++], x, out, nullptr, N, H, W, 0, true, s, n_valid);
     } else {
         const __bf16* x = h;
         for (int b = 0; b < d.n_blocks; ++b) {
@@ -607,17 +611,18 @@ rh_status rh_launch_enhance_bf16(rh_ctx* ctx, const uint8_t* in, int N, int H, i
             x = a;
         }
         if (d.topology == RH_NET_RES) {
-            CONV(L[li++], x, out, nullptr, N, H, W, 0, true, s, n_valid);
+            LAST_CONV(L[li++], x, out, nullptr, N, H, W, 0, true, s, n_valid);
         } else {
             CONV(L[li++], x, t, h, N, H, W, 0, false, 1, n_valid);        // body end + long skip
             const int r = (s == 4) ? 2 : s;
             CONV(L[li++], t, u1, nullptr, N, H, W, 0, false, 1, n_valid);
             const __bf16* lastin = u1; int hh = H * r, ww = W * r;
             if (s == 4) { CONV(L[li++], u1, u2, nullptr, N, hh, ww, 0, false, 1, n_valid); lastin = u2; hh *= 2; ww *= 2; }
-            CONV(L[li++], lastin, out, nullptr, N, hh, ww, 0, true, 1, n_valid);
+            LAST_CONV(L[li++], lastin, out, nullptr, N, hh, ww, 0, true, 1, n_valid);
         }
     }
 #undef CONV
+#undef LAST_CONV
     RH_HIP(ctx, hipGetLastError());
     return RH_OK;
 }
