@@ -24,6 +24,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK = 2.5e15   # dense bf16 MFMA, FLOP/s (MI355X published)
+# HBM bytes per launch of the dominant kernel class on the default workload, from the rocprofv3
+# FETCH_SIZE / WRITE_SIZE runs summarised in profiles/conv_mfma_cfg3_hbm_counters.md (scaled by
+# the plain-copy calibration); not measured live, so only reported for that workload.
+MEASURED_TRAFFIC = {"cfg3_16x480x272_edsr64_x4_bf16": 564.4e6}
 
 
 def conv_flops_per_lr_pixel(net):
@@ -144,7 +148,7 @@ def main():
         "kernel_ms_per_step": {k: v[0] / args.steps for k, v in prof.items()},
         "roofline": {"bound": "mfma", "kernel": "k_conv_mfma<64,2,16,false,*,*> (bf16-output convs: ReLU, skip and plain variants)", "achieved": achieved / 1e12,
                      "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK,
-                     "traffic": None, "avg_launch_us": avg_launch_s * 1e6, "launches_per_step": conv_n / args.steps,
+                     "traffic": MEASURED_TRAFFIC.get(cfg.name), "avg_launch_us": avg_launch_s * 1e6, "launches_per_step": conv_n / args.steps,
                      "flop_per_launch": flop_per_launch},
         "enhance_tflops_all_layers": total_flops_per_lr_pixel(cfg.net) * px_lr /
                                      (sum(prof[k][0] for k in ("head", "conv", "conv_last")) / args.steps * 1e-3) / 1e12,
