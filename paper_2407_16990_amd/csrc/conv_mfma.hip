@@ -19,13 +19,7 @@
 
 #include <type_traits>
 
-#include "rh_internal.h"
-
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
-typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
-typedef __attribute__((__vector_size__(4 * sizeof(int)))) int i32x4;
+#include "conv_mfma_common.h"
 
 #ifdef RH_PHASE_TIMING   // development aid: per-phase cycle counts of wave 0 of every workgroup
 __device__ unsigned long long rh_dbg[16];
@@ -49,43 +43,14 @@ extern "C" void rh_debug_read(unsigned long long* out, int reset)
 #define TW 32            // tile width in pixels = N of one MFMA
 #define PW (TW + 2)
 
-struct conv_args {
-    const __bf16* in;        // [N][H][W][CIN]
-    const uint4* wp;         // packed weights of this layer
-    const float* bias;       // packed order
-    void* out;
-    const __bf16* skip;      // same shape as out, or null
-    const uint32_t* n_valid;
-    int N, H, W;
-    int relu, ps, n_chunks;  // bf16 output mode
-    int cout_real, s_final;  // fp32 output mode
-#ifdef RH_PHASE_TIMING
-    int dbg;                 // bit0: no patch loads, bit1: no output stores, bit2: no MFMA loop
-#endif
-};
-
-__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b)
-{
-    typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
-    typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2;
-    f32x2 v = {a, b};
-    bf16x2 r = __builtin_convertvector(v, bf16x2);     // round to nearest even
-    return *(uint32_t*)&r;
-}
-
-// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every
-// outstanding global load and store of the wave, which would expose the latency of the patch
-// prefetch, the skip reads and the output stores once per tile.
-__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
-
-__device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
-__device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xFFFF0000u); }
 
 // CIN: input channels (32 or 64).  MT: 32-channel M tiles per output chunk (1 or 2).
 // TH: tile height; each of the 4 waves owns RW = TH/4 rows of 32 pixels.
 // F32OUT: last layer of the network (fp32 output, true channel count cout_real <= 32*MT,
 // optional pixel shuffle s_final in the store address).  SKIP: add a same-shaped bf16 tensor
-// to the output (residual connections).  RELU: clamp at zero before rounding.
+// to the output (residual connections).  RELU: clamp at zero before rounding.  MINB: workgroups
+// that must fit on a CU together (2 for the memory-bound last layer: small tiles, so that one
+// workgroup's loads overlap the other's MFMAs; 1 = all registers and LDS for one workgroup).
 //
 // Per tile:   (A) barrier, prefetched patch registers -> LDS, (B) barrier, MFMA loop,
 //             (C) barrier, accumulators -> bf16 -> LDS, (D) barrier, LDS -> registers.
@@ -112,11 +77,9 @@ __device__ __forceinline__ void for_each_step(F& f)
     if constexpr (I < N) { f(std::integral_constant<int, I>{}); for_each_step<N, I + 1>(f); }
 }
 
-#define RSRC_FLAGS 0x00020000            // raw buffer, 32-bit data format (gfx9 family)
-#define OOB_OFF 0x80000000u              // beyond any descriptor used here (images are < 2 GiB)
 
-template <int CIN, int MT, int TH, bool F32OUT, bool SKIP, bool RELU>
-__global__ __launch_bounds__(256) void k_conv_mfma(conv_args a)
+template <int CIN, int MT, int TH, bool F32OUT, bool SKIP, bool RELU, int MINB>
+__global__ __launch_bounds__(256, MINB) void k_conv_mfma(conv_args a)
 {
     constexpr int KS = CIN / 16;             // MFMA k-steps per tap
     constexpr int NCH = CIN / 8;             // 16-byte channel groups per input pixel
@@ -291,14 +254,15 @@ __global__ __launch_bounds__(256) void k_conv_mfma(conv_args a)
                 static_assert(n_st + n_ld + n_sk <= NSLOT, "too many memory instructions for one step");
 #pragma unroll
                 for (int sl = 0; sl < NSLOT; ++sl) {
-                    if (st + 1 < NSTEP) {
+                    if (st + 1 < NSTEP && !DBG(2)) {
 #pragma unroll
                         for (int f = sl * FPS; f < (sl + 1) * FPS && f < NFR; ++f) {
                             if (f < 3 * MT) An[f / MT][f % MT] = *(const bf16x8*)(wlane + (((((f / MT) * 3 + kxn) * KS + ksn) * MT + f % MT) << 10));
                             else Bn[f - 3 * MT] = *(const bf16x8*)(b0n + (f - 3 * MT) * (PW * PIXB));
                         }
                     }
-                    if (sl < n_st) {
+                    if (DBG(1)) {
+                    } else if (sl < n_st) {
                         const int j = st * SPS + sl;
                         if (j < NOUT) {
                             const i32x4 v = {(int)outv[j].x, (int)outv[j].y, (int)outv[j].z, (int)outv[j].w};
@@ -522,18 +486,18 @@ rh_status rh_pack_weights_bf16(rh_ctx* ctx, const float* blob)
     return RH_OK;
 }
 
-template <int CIN, int MT, int TH, bool F32OUT, bool SKIP, bool RELU>
+template <int CIN, int MT, int TH, bool F32OUT, bool SKIP, bool RELU, int MINB = 1>
 static hipError_t launch_conv(rh_ctx* ctx, const conv_args& a, int grid)
 {
     constexpr int lds = 9 * (CIN / 16) * MT * 1024 + (TH + 2) * PW * CIN * 2;
     static bool attr_done = false;
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute((const void*)k_conv_mfma<CIN, MT, TH, F32OUT, SKIP, RELU>,
+        hipError_t e = hipFuncSetAttribute((const void*)k_conv_mfma<CIN, MT, TH, F32OUT, SKIP, RELU, MINB>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    hipLaunchKernelGGL((k_conv_mfma<CIN, MT, TH, F32OUT, SKIP, RELU>), dim3(grid), dim3(256), lds, ctx->stream, a);
+    hipLaunchKernelGGL((k_conv_mfma<CIN, MT, TH, F32OUT, SKIP, RELU, MINB>), dim3(grid), dim3(256), lds, ctx->stream, a);
     return hipSuccess;
 }
 
@@ -552,10 +516,12 @@ static rh_status conv(rh_ctx* ctx, const rh_layer& L, const __bf16* in, void* ou
     hipError_t e;
     // bf16-output convs come as (ReLU, no skip), (skip, no ReLU) or (neither)
     if (L.cin == 64) {
-        if (last) e = (MT == 2) ? launch_conv<64, 2, 16, true, false, false>(ctx, a, grid) : launch_conv<64, 1, 16, true, false, false>(ctx, a, grid);
-        else if (skip) e = launch_conv<64, 2, 16, false, true, false>(ctx, a, grid);
-        else if (relu) e = launch_conv<64, 2, 16, false, false, true>(ctx, a, grid);
-        else e = launch_conv<64, 2, 16, false, false, false>(ctx, a, grid);
+        if (last) e = (MT == 2) ? launch_conv<64, 2, 16, true, false, false>(ctx, a, grid) : launch_conv<64, 1, 8, true, false, false, 2>(ctx, a, 2 * grid);
+        else if (getenv("RH_SINGLE_TEAM")) {
+            if (skip) e = launch_conv<64, 2, 16, false, true, false>(ctx, a, grid);
+            else if (relu) e = launch_conv<64, 2, 16, false, false, true>(ctx, a, grid);
+            else e = launch_conv<64, 2, 16, false, false, false>(ctx, a, grid);
+        } else e = rh_launch_conv_duo(ctx->stream, a, grid, skip != nullptr, relu != 0);
     } else {
         if (last) e = (MT == 2) ? launch_conv<32, 2, 16, true, false, false>(ctx, a, grid) : launch_conv<32, 1, 16, true, false, false>(ctx, a, grid);
         else if (skip) e = launch_conv<32, 1, 16, false, true, false>(ctx, a, grid);

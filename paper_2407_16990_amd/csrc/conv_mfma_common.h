@@ -1,0 +1,47 @@
+// Definitions shared by the MFMA convolution kernels (conv_mfma.hip, conv_mfma_duo.hip).
+#pragma once
+#include "rh_internal.h"
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+typedef __attribute__((__vector_size__(4 * sizeof(int)))) int i32x4;
+
+struct conv_args {
+    const __bf16* in;        // [N][H][W][CIN]
+    const uint4* wp;         // packed weights of this layer
+    const float* bias;       // packed order
+    void* out;
+    const __bf16* skip;      // same shape as out, or null
+    const uint32_t* n_valid;
+    int N, H, W;
+    int relu, ps, n_chunks;  // bf16 output mode
+    int cout_real, s_final;  // fp32 output mode
+#ifdef RH_PHASE_TIMING
+    int dbg;                 // bit0: no patch loads, bit1: no output stores, bit2: no MFMA loop
+#endif
+};
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b)
+{
+    typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+    typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2;
+    f32x2 v = {a, b};
+    bf16x2 r = __builtin_convertvector(v, bf16x2);     // round to nearest even
+    return *(uint32_t*)&r;
+}
+
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every
+// outstanding global load and store of the wave, which would expose the latency of the patch
+// prefetch, the skip reads and the output stores once per tile.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+__device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xFFFF0000u); }
+
+#define RSRC_FLAGS 0x00020000            // raw buffer, 32-bit data format (gfx9 family)
+#define OOB_OFF 0x80000000u              // beyond any descriptor used here (images are < 2 GiB)
+
+// two-team kernel for the 64-channel bf16-output convs (conv_mfma_duo.hip)
+hipError_t rh_launch_conv_duo(hipStream_t stream, const conv_args& a, int grid, bool skip, bool relu);

@@ -1,0 +1,316 @@
+// 64 -> 64-channel-chunk bf16 conv3x3 on the matrix cores, two-team variant.
+//
+// Same implicit GEMM, LDS layouts, fragment order and buffer addressing as k_conv_mfma
+// (conv_mfma.hip), but the workgroup has 8 waves = two teams of 4.  The teams share the
+// LDS-resident weights and own one 10 x 34 pixel patch each: team t computes rows 8t..8t+7 of
+// the workgroup's 16 x 32 tile.  The teams run half a tile apart: while one team is in its
+// MFMA loop, the other rounds its finished accumulators to bf16, adds the skip tensor, writes
+// the result, and puts its next patch into LDS.  Every SIMD holds one wave of each team, so the
+// matrix pipe is fed by one wave while the other does vector-ALU, LDS and memory work.
+//
+// The hardware barrier counts all 8 waves, so both teams execute the same barrier sequence:
+// time is cut into phases of exactly two barriers.
+//   compute phase : MFMA steps 0..MID-1 | barrier | steps MID..11 | barrier
+//                   (LDS fragment reads and MFMAs only: a wave that issues a wide global memory
+//                   instruction cannot issue MFMAs for some 60-90 cycles, so the MFMA loop
+//                   carries none)
+//   drain phase   : issue the global loads (next patch, skip), accumulators -> bf16 -> own LDS
+//                   slice -> registers, + skip, global stores | barrier |
+//                   next patch registers -> LDS | barrier
+// Team 0 runs compute, drain, compute, ...; team 1 starts with an idle phase and team 0 ends
+// with one, so the phases pair up.  The number of phases depends only on kernel arguments and
+// the workgroup index (never on data), tiles past the end are "null" tiles (all loads out of
+// range -> zeros, all stores dropped), and no wave leaves the loop early: every barrier is
+// reached by all 8 waves.
+#include <type_traits>
+
+#include "conv_mfma_common.h"
+
+#define PW 34
+
+#ifdef RH_PHASE_TIMING
+__device__ unsigned long long rh_dbg2[32];
+extern "C" void rh_debug_read2(unsigned long long* out, int reset)
+{
+    (void)hipDeviceSynchronize();
+    (void)hipMemcpyFromSymbol(out, HIP_SYMBOL(rh_dbg2), sizeof(rh_dbg2));
+    if (reset) { unsigned long long z[32] = {0}; (void)hipMemcpyToSymbol(HIP_SYMBOL(rh_dbg2), z, sizeof(z)); }
+}
+#define PH2(i) do { unsigned long long t_ = clock64(); ph[i] += t_ - tprev; tprev = t_; } while (0)
+#define PH2_INIT unsigned long long ph[8] = {0, 0, 0, 0, 0, 0, 0, 0}; unsigned long long tprev = clock64()
+#define PH2_END do { if (ttid == 0) for (int i_ = 0; i_ < 8; ++i_) atomicAdd(&rh_dbg2[(SKIP ? 16 : 0) + team * 8 + i_], ph[i_]); } while (0)
+#else
+#define PH2(i) do { } while (0)
+#define PH2_INIT do { } while (0)
+#define PH2_END do { } while (0)
+#endif
+
+template <int N, int I = 0, typename F>
+__device__ __forceinline__ void for_each_step2(F& f)
+{
+    if constexpr (I < N) { f(std::integral_constant<int, I>{}); for_each_step2<N, I + 1>(f); }
+}
+
+__device__ __forceinline__ void phase_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+__device__ __forceinline__ void idle_phase() { phase_barrier(); phase_barrier(); }
+
+template <bool SKIP, bool RELU>
+__global__ __launch_bounds__(512) void k_conv_mfma_duo(conv_args a)
+{
+    constexpr int CIN = 64, MT = 2, KS = 4, NCH = 8, PIXB = 128, TH = 8, PH = TH + 2, RW = 2, NR = RW + 2;
+    constexpr int WBYTES = 9 * KS * MT * 1024, PATCHB = PH * PW * PIXB, NSTEP = 3 * KS, CQ = 64;
+    constexpr int NMAIN = PH, NHP = PH * 2 * NCH, NHALO = 1, NPRE = NMAIN + NHALO;      // 16-byte patch pieces per thread
+    static_assert(NHP <= 256, "halo pieces must fit one per thread");
+    // the compute phase's first barrier comes after MID of the 12 steps: it pairs with the end of
+    // the other team's loads + rounding + skip add + stores, which is longer with a skip tensor
+    constexpr int MID = SKIP ? 10 : 8;
+    constexpr int NCHO = 8, OPIXB = 128, NOUT = RW * 32 * NCHO / 64, PPJ = 8, JPR = 4;   // output pieces per lane
+
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    const int tid = threadIdx.x, team = tid >> 8, ttid = tid & 255, lane = tid & 63, wave = (tid >> 6) & 3;
+    const int lx = lane & 31, hi = lane >> 5;
+    uint8_t* lds_w = lds;
+    uint8_t* lds_p = lds + WBYTES + team * PATCHB;
+    float* lds_b = (float*)(lds + WBYTES + 2 * PATCHB);       // the chunk's 64 biases
+
+    const int n_img = a.n_valid ? min((int)*a.n_valid, a.N) : a.N;
+    const int tiles_x = (a.W + 31) / 32, tiles_y = (a.H + 15) / 16;
+    const int tiles_img = tiles_x * tiles_y;
+    const int n_tiles = n_img * tiles_img;
+    const int G = gridDim.x;
+    const int wg = (G % 8 == 0) ? (blockIdx.x % 8) * (G / 8) + blockIdx.x / 8 : blockIdx.x;
+    const int iters = n_tiles > wg ? (n_tiles - wg + G - 1) / G : 0;          // same for all 512 threads
+    const int ps = a.ps;
+    const uint32_t in_img_bytes = (uint32_t)a.H * a.W * PIXB;
+    const uint32_t out_img_bytes = (uint32_t)(a.H * ps) * (a.W * ps) * OPIXB;
+
+    // per-thread constants of the patch pieces (see k_conv_mfma)
+    const int m_col = ttid >> 3, m_c = ttid & 7;
+    const int m_goff = m_col * PIXB + m_c * 16;
+    const uint32_t m_lds = (uint32_t)((1 + m_col) * PIXB + ((m_c ^ ((1 + m_col) & 7)) << 4));
+    const int h_row = ttid >> 4, h_side = (ttid >> 3) & 1, h_c = ttid & 7;     // halo piece (ttid < NHP)
+    const int lcol = lane >> 3, lc = lane & 7;
+    const int o_lane = (lcol * ps) * OPIXB + lc * 16;
+    const int o_rowpitch = a.W * ps * OPIXB;
+    const int row_pitch = a.W * PIXB;
+
+    // origin of team's half of tile number `tile` (rows y0..y0+7), image index n
+    auto tile_origin = [&](int tile, int& n, int& y0, int& x0) __attribute__((always_inline)) {
+        n = tile / tiles_img;
+        const int tr = tile - n * tiles_img, ty = tr / tiles_x, tx = tr - ty * tiles_x;
+        y0 = ty * 16 + team * TH; x0 = tx * 32;
+    };
+    uint4 pre[NPRE];
+    auto load_piece = [&](int j, __amdgpu_buffer_rsrc_t rin, int y0, int x0) __attribute__((always_inline)) {
+        int off; bool ok;
+        if (j < NMAIN) {
+            const int gy = y0 - 1 + j;
+            ok = gy >= 0 && gy < a.H && x0 + m_col < a.W;
+            off = ((y0 - 1) * a.W + x0) * PIXB + m_goff + j * row_pitch;
+        } else {
+            const int gy = y0 - 1 + h_row, hx = h_side ? x0 + 32 : x0 - 1;
+            ok = ttid < NHP && gy >= 0 && gy < a.H && hx >= 0 && hx < a.W;
+            off = (gy * a.W + hx) * PIXB + h_c * 16;
+        }
+        const i32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rin, ok ? (uint32_t)off : OOB_OFF, 0, 0);
+        pre[j] = make_uint4(v[0], v[1], v[2], v[3]);
+    };
+    auto store_patch = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < NMAIN; ++j) *(uint4*)(lds_p + j * (PW * PIXB) + m_lds) = pre[j];
+        const int px = h_side ? PW - 1 : 0;
+        if (ttid < NHP) *(uint4*)(lds_p + (h_row * PW + px) * PIXB + ((h_c ^ (px & 7)) << 4)) = pre[NMAIN];
+    };
+    auto out_off = [&](int j, int y0, int x0, int si, int sj) __attribute__((always_inline)) {
+        const int y = y0 + wave * RW + j / JPR, xb = x0 + (j % JPR) * PPJ;
+        const bool ok = y < a.H && xb + lcol < a.W;
+        const int off = (y * ps + si) * o_rowpitch + (xb * ps + sj) * OPIXB + o_lane;
+        return ok ? (uint32_t)off : OOB_OFF;
+    };
+    auto in_rsrc = [&](int tile, int n) __attribute__((always_inline)) {
+        return __builtin_amdgcn_make_buffer_rsrc((void*)(a.in + (size_t)n * a.H * a.W * CIN), 0,
+                                                 tile < n_tiles ? in_img_bytes : 0u, RSRC_FLAGS);
+    };
+
+    for (int chunk = 0; chunk < a.n_chunks; ++chunk) {
+        __syncthreads();                                   // all 8 waves: previous chunk completely done
+        {
+            const uint4* src = a.wp + (size_t)chunk * (WBYTES / 16);
+            for (int i = tid; i < WBYTES / 16; i += 512) ((uint4*)lds_w)[i] = src[i];
+        }
+        if (tid < CQ) lds_b[tid] = a.bias[chunk * CQ + tid];
+        const int si = chunk / ps, sj = chunk - si * ps;
+        {   // first patch of both teams
+            int n, y0, x0; tile_origin(wg, n, y0, x0);
+            __amdgpu_buffer_rsrc_t rin = in_rsrc(wg, wg < n_tiles ? n : 0);
+#pragma unroll
+            for (int j = 0; j < NPRE; ++j) load_piece(j, rin, y0, x0);
+            store_patch();
+        }
+        __syncthreads();
+
+        // accumulators start from the bias: lane holds channels m*32 + 8*q + 4*hi + {0..3} in
+        // acc[.][m][4q..4q+3].  They are re-seeded in the drain phase, off the critical path.
+        f32x16 acc[RW][MT];
+        auto seed_acc = [&]() __attribute__((always_inline)) {
+#pragma unroll
+            for (int m = 0; m < MT; ++m)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float4 bv = *(const float4*)(lds_b + m * 32 + q * 8 + hi * 4);
+#pragma unroll
+                    for (int r = 0; r < RW; ++r) { acc[r][m][4 * q] = bv.x; acc[r][m][4 * q + 1] = bv.y; acc[r][m][4 * q + 2] = bv.z; acc[r][m][4 * q + 3] = bv.w; }
+                }
+        };
+        seed_acc();
+        PH2_INIT;
+        if (team == 1) idle_phase();
+        for (int it = 0; it < iters; ++it) {
+            PH2(0);
+            // ---------------- compute phase ----------------
+            const uint8_t* wlane = lds_w + (lane << 4);
+            const uint8_t* prow = lds_p + (wave * RW) * (PW * PIXB);
+            bf16x8 A0[3][MT], A1[3][MT], B0[NR], B1[NR];
+            {   // fragments of step 0
+                const uint8_t* b0 = prow + lx * PIXB + ((hi ^ (lx & 7)) << 4);
+#pragma unroll
+                for (int ky = 0; ky < 3; ++ky)
+#pragma unroll
+                    for (int m = 0; m < MT; ++m) A0[ky][m] = *(const bf16x8*)(wlane + ((((ky * 3) * KS) * MT + m) << 10));
+#pragma unroll
+                for (int py = 0; py < NR; ++py) B0[py] = *(const bf16x8*)(b0 + py * (PW * PIXB));
+            }
+            auto step = [&](auto st_c) __attribute__((always_inline)) {
+                constexpr int st = decltype(st_c)::value;
+                constexpr int NMF = 3 * RW * MT, NFR = 3 * MT + NR, NSLOT = 6;
+                constexpr int MPS = NMF / NSLOT, FPS = (NFR + NSLOT - 1) / NSLOT;
+                bf16x8 (&Ac)[3][MT] = (st & 1) ? A1 : A0;
+                bf16x8 (&Bc)[NR] = (st & 1) ? B1 : B0;
+                bf16x8 (&An)[3][MT] = (st & 1) ? A0 : A1;
+                bf16x8 (&Bn)[NR] = (st & 1) ? B0 : B1;
+                constexpr int kxn = (st + 1) / KS, ksn = (st + 1) - kxn * KS;
+                const int pxn = lx + kxn;
+                const uint8_t* b0n = prow + pxn * PIXB + (((2 * ksn + hi) ^ (pxn & 7)) << 4);
+#pragma unroll
+                for (int sl = 0; sl < NSLOT; ++sl) {
+                    if (st + 1 < NSTEP) {
+#pragma unroll
+                        for (int f = sl * FPS; f < (sl + 1) * FPS && f < NFR; ++f) {
+                            // fragments in the order of their first use in the next step:
+                            // B0, A0*, B1, A1*, B2, A2*, B3  (A ky-th pair follows B ky)
+                            constexpr int GRP = 1 + MT;
+                            const int g = f / GRP, w = f % GRP;
+                            if (g < 3 && w > 0) An[g][w - 1] = *(const bf16x8*)(wlane + ((((g * 3 + kxn) * KS + ksn) * MT + (w - 1)) << 10));
+                            else Bn[g < 3 ? g : 3 + (f - 3 * GRP)] = *(const bf16x8*)(b0n + (g < 3 ? g : 3 + (f - 3 * GRP)) * (PW * PIXB));
+                        }
+                    }
+#pragma unroll
+                    for (int k = sl * MPS; k < (sl + 1) * MPS; ++k) {
+                        const int m = k % MT, pair = k / MT;
+                        int py = 0, ky = 0, cnt = 0;
+#pragma unroll
+                        for (int p = 0; p < NR; ++p)
+#pragma unroll
+                            for (int q = 0; q < 3; ++q)
+                                if (p - q >= 0 && p - q < RW) { if (cnt == pair) { py = p; ky = q; } ++cnt; }
+                        const int r = py - ky;
+                        acc[r][m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Ac[ky][m], Bc[py], acc[r][m], 0, 0, 0);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                if constexpr (st == MID - 1 || st == NSTEP - 1) {   // the two barriers of the compute phase
+                    PH2(1 + st / 4 * 0);
+                    asm volatile("s_barrier" ::: "memory");
+                    __builtin_amdgcn_sched_barrier(0);
+                    PH2(2);
+                }
+            };
+            __builtin_amdgcn_s_setprio(2);                    // the wave feeding the matrix pipe goes first
+            for_each_step2<NSTEP>(step);
+            __builtin_amdgcn_s_setprio(0);
+
+            // ---------------- drain phase ----------------
+            const int tile = wg + it * G, ntile = tile + G;
+            int n, y0, x0; tile_origin(tile, n, y0, x0);
+            int nn, ny0, nx0; tile_origin(ntile, nn, ny0, nx0);
+            __amdgpu_buffer_rsrc_t rin = in_rsrc(ntile, ntile < n_tiles ? nn : 0);
+            __amdgpu_buffer_rsrc_t rsk = __builtin_amdgcn_make_buffer_rsrc(
+                (void*)((uint8_t*)a.skip + (size_t)n * out_img_bytes), 0, SKIP ? out_img_bytes : 0u, RSRC_FLAGS);
+            __amdgpu_buffer_rsrc_t rout = __builtin_amdgcn_make_buffer_rsrc(
+                (void*)((uint8_t*)a.out + (size_t)n * out_img_bytes), 0, out_img_bytes, RSRC_FLAGS);
+            uint4 sk[SKIP ? NOUT : 1];
+            // All global loads of the team are issued here, by waves that are not feeding the
+            // matrix pipe: the next tile's patch (stored to LDS at the end of the phase) and
+            // this tile's skip values (used after the first barrier).
+#pragma unroll
+            for (int j = 0; j < NPRE; ++j) load_piece(j, rin, ny0, nx0);
+            if constexpr (SKIP) {
+#pragma unroll
+                for (int j = 0; j < NOUT; ++j) {
+                    const i32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsk, out_off(j, y0, x0, 0, 0), 0, 0);
+                    sk[j] = make_uint4(v[0], v[1], v[2], v[3]);
+                }
+            }
+            uint8_t* stg = lds_p + wave * (RW * 32 * OPIXB);
+            const int okey = lx & 7;
+#pragma unroll
+            for (int m = 0; m < MT; ++m)
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+#pragma unroll
+                    for (int r = 0; r < RW; ++r) {
+                        float v0 = acc[r][m][4 * q + 0], v1 = acc[r][m][4 * q + 1], v2 = acc[r][m][4 * q + 2], v3 = acc[r][m][4 * q + 3];
+                        if constexpr (RELU) { v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); v2 = fmaxf(v2, 0.f); v3 = fmaxf(v3, 0.f); }
+                        uint2 pk;
+                        pk.x = pack_bf16x2(v0, v1); pk.y = pack_bf16x2(v2, v3);
+                        *(uint2*)(stg + (r * 32 + lx) * OPIXB + (((m * 4 + q) ^ okey) << 4) + hi * 8) = pk;
+                    }
+            seed_acc();
+            PH2(3);
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");     // the slice is private to the wave: no barrier
+            PH2(4);
+#pragma unroll
+            for (int j = 0; j < NOUT; ++j) {
+                const int r = j / JPR, px = (j % JPR) * PPJ + lcol;
+                uint4 o = *(const uint4*)(stg + (r * 32 + px) * OPIXB + ((lc ^ (px & 7)) << 4));
+                if constexpr (SKIP) {
+                    o.x = pack_bf16x2(bf16_lo(o.x) + bf16_lo(sk[j].x), bf16_hi(o.x) + bf16_hi(sk[j].x));
+                    o.y = pack_bf16x2(bf16_lo(o.y) + bf16_lo(sk[j].y), bf16_hi(o.y) + bf16_hi(sk[j].y));
+                    o.z = pack_bf16x2(bf16_lo(o.z) + bf16_lo(sk[j].z), bf16_hi(o.z) + bf16_hi(sk[j].z));
+                    o.w = pack_bf16x2(bf16_lo(o.w) + bf16_lo(sk[j].w), bf16_hi(o.w) + bf16_hi(sk[j].w));
+                }
+                const i32x4 v = {(int)o.x, (int)o.y, (int)o.z, (int)o.w};
+                __builtin_amdgcn_raw_buffer_store_b128(v, rout, out_off(j, y0, x0, si, sj), 0, 0);
+            }
+            PH2(5);
+            phase_barrier();                                  // 1: every wave of the team has read its slice back
+            PH2(6);
+            store_patch();                                    // next tile's patch (zeros after the last tile)
+            PH2(7);
+            phase_barrier();                                  // 2
+        }
+        if (team == 0) idle_phase();
+        PH2_END;
+    }
+}
+
+template <bool SKIP, bool RELU>
+static hipError_t launch_duo(hipStream_t stream, const conv_args& a, int grid)
+{
+    constexpr int lds = 9 * 4 * 2 * 1024 + 2 * 10 * PW * 128 + 256;
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute((const void*)k_conv_mfma_duo<SKIP, RELU>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    hipLaunchKernelGGL((k_conv_mfma_duo<SKIP, RELU>), dim3(grid), dim3(512), lds, stream, a);
+    return hipGetLastError();
+}
+
+hipError_t rh_launch_conv_duo(hipStream_t stream, const conv_args& a, int grid, bool skip, bool relu)
+{
+    if (skip) return launch_duo<true, false>(stream, a, grid);
+    if (relu) return launch_duo<false, true>(stream, a, grid);
+    return launch_duo<false, false>(stream, a, grid);
+}
