@@ -517,11 +517,7 @@ static rh_status conv(rh_ctx* ctx, const rh_layer& L, const __bf16* in, void* ou
     // bf16-output convs come as (ReLU, no skip), (skip, no ReLU) or (neither)
     if (L.cin == 64) {
         if (last) e = (MT == 2) ? launch_conv<64, 2, 16, true, false, false>(ctx, a, grid) : launch_conv<64, 1, 8, true, false, false, 2>(ctx, a, 2 * grid);
-        else if (getenv("RH_SINGLE_TEAM")) {
-            if (skip) e = launch_conv<64, 2, 16, false, true, false>(ctx, a, grid);
-            else if (relu) e = launch_conv<64, 2, 16, false, false, true>(ctx, a, grid);
-            else e = launch_conv<64, 2, 16, false, false, false>(ctx, a, grid);
-        } else e = rh_launch_conv_duo(ctx->stream, a, grid, skip != nullptr, relu != 0);
+        else e = rh_launch_conv_duo(ctx->stream, a, grid, skip != nullptr, relu != 0);    // two-team kernel
     } else {
         if (last) e = (MT == 2) ? launch_conv<32, 2, 16, true, false, false>(ctx, a, grid) : launch_conv<32, 1, 16, true, false, false>(ctx, a, grid);
         else if (skip) e = launch_conv<32, 1, 16, false, true, false>(ctx, a, grid);
