@@ -31,16 +31,16 @@
 #define PW 34
 
 #ifdef RH_PHASE_TIMING
-__device__ unsigned long long rh_dbg2[32];
+__device__ unsigned long long rh_dbg2[36];
 extern "C" void rh_debug_read2(unsigned long long* out, int reset)
 {
     (void)hipDeviceSynchronize();
     (void)hipMemcpyFromSymbol(out, HIP_SYMBOL(rh_dbg2), sizeof(rh_dbg2));
-    if (reset) { unsigned long long z[32] = {0}; (void)hipMemcpyToSymbol(HIP_SYMBOL(rh_dbg2), z, sizeof(z)); }
+    if (reset) { unsigned long long z[36] = {0}; (void)hipMemcpyToSymbol(HIP_SYMBOL(rh_dbg2), z, sizeof(z)); }
 }
 #define PH2(i) do { unsigned long long t_ = clock64(); ph[i] += t_ - tprev; tprev = t_; } while (0)
-#define PH2_INIT unsigned long long ph[8] = {0, 0, 0, 0, 0, 0, 0, 0}; unsigned long long tprev = clock64()
-#define PH2_END do { if (ttid == 0) for (int i_ = 0; i_ < 8; ++i_) atomicAdd(&rh_dbg2[(SKIP ? 16 : 0) + team * 8 + i_], ph[i_]); } while (0)
+#define PH2_INIT unsigned long long ph[8] = {0, 0, 0, 0, 0, 0, 0, 0}; unsigned long long tprev = clock64(); const unsigned long long c_start = tprev, w_start = wall_clock64()
+#define PH2_END do { if (ttid == 0) for (int i_ = 0; i_ < 8; ++i_) atomicAdd(&rh_dbg2[(SKIP ? 16 : 0) + team * 8 + i_], ph[i_]); if (tid == 0) { atomicAdd(&rh_dbg2[32], clock64() - c_start); atomicAdd(&rh_dbg2[33], wall_clock64() - w_start); } } while (0)
 #else
 #define PH2(i) do { } while (0)
 #define PH2_INIT do { } while (0)

@@ -139,6 +139,10 @@ __global__ __launch_bounds__(256) void k_plan_rank(const rh_rawbox* __restrict__
 // Free rectangle j: fxy[j] = x | y<<16, fwh[j] = w | h<<16, fbin[j].  Every thread tracks the
 // list length and bin count redundantly; only the list itself is shared.
 // box_pos[i] = {bin, bx | by<<16}; pcount[1] = n_bins, pcount[2] = overflow.
+// Barrier that orders LDS traffic only (the placement loop also issues global stores whose
+// completion nobody in the loop waits for).
+__device__ __forceinline__ void lds_sync() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 __global__ __launch_bounds__(256) void k_plan_place(const rh_rawbox* __restrict__ sorted, uint32_t* pcount,
                                                     int halo, int S, int max_bins, int free_cap,
                                                     uint32_t* __restrict__ box_pos)
@@ -147,7 +151,7 @@ __global__ __launch_bounds__(256) void k_plan_place(const rh_rawbox* __restrict_
     uint32_t* fxy = sm; uint32_t* fwh = sm + free_cap; uint32_t* fbin = sm + 2 * free_cap;
     __shared__ uint32_t s_at;
     __shared__ uint32_t s_size[256];
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, NT = blockDim.x;     // one wave is enough: the lists are short
     const uint32_t n = pcount[0];
     const int minside = RH_MB + 2 * halo;
     int nfree = 0, nbins = 0;
@@ -156,17 +160,18 @@ __global__ __launch_bounds__(256) void k_plan_place(const rh_rawbox* __restrict_
     if (tid == 0) s_at = NONE;
     for (; i < n && !overflow; ++i) {
         if ((i & 255u) == 0) {                                   // stage the next 256 box sizes
-            __syncthreads();
-            if (i + tid < n) s_size[tid] = sorted[i + tid].wmb | ((uint32_t)sorted[i + tid].hmb << 16);
+            lds_sync();
+            for (int t = tid; t < 256; t += NT)
+                if (i + t < n) s_size[t] = sorted[i + t].wmb | ((uint32_t)sorted[i + t].hmb << 16);
         }
-        __syncthreads();
+        lds_sync();
         const uint32_t sz = s_size[i & 255u];
         const int bw = RH_MB * (int)(sz & 0xFFFF) + 2 * halo, bh = RH_MB * (int)(sz >> 16) + 2 * halo;
-        for (int j = tid; j < nfree; j += 256) {
+        for (int j = tid; j < nfree; j += NT) {
             const uint32_t wh = fwh[j];
             if ((int)(wh & 0xFFFF) >= bw && (int)(wh >> 16) >= bh) { atomicMin(&s_at, (uint32_t)j); break; }
         }
-        __syncthreads();
+        lds_sync();
         uint32_t at = s_at;
         int fx, fy, fw, fh, fb, cur_n;
         if (at == NONE) {
@@ -193,26 +198,26 @@ __global__ __launch_bounds__(256) void k_plan_place(const rh_rawbox* __restrict_
         } else if (keep_r) { ixy[0] = Rxy; iwh[0] = Rwh; ni = 1; }
         else if (keep_b)   { ixy[0] = Bxy; iwh[0] = Bwh; ni = 1; }
         const int delta = ni - 1, first = (int)at + 1;
-        __syncthreads();                                          // all reads of entry `at` done
+        lds_sync();                                          // all reads of entry `at` done
         if (delta > 0) {
-            for (int hi = cur_n; hi > first; hi -= 256) {
+            for (int hi = cur_n; hi > first; hi -= NT) {
                 const int j = hi - 1 - tid;
                 const bool mv = j >= first;
                 uint32_t a = 0, b = 0, c = 0;
                 if (mv) { a = fxy[j]; b = fwh[j]; c = fbin[j]; }
-                __syncthreads();
+                lds_sync();
                 if (mv) { fxy[j + 1] = a; fwh[j + 1] = b; fbin[j + 1] = c; }
-                __syncthreads();
+                lds_sync();
             }
         } else if (delta < 0) {
-            for (int lo = first; lo < cur_n; lo += 256) {
+            for (int lo = first; lo < cur_n; lo += NT) {
                 const int j = lo + tid;
                 const bool mv = j < cur_n;
                 uint32_t a = 0, b = 0, c = 0;
                 if (mv) { a = fxy[j]; b = fwh[j]; c = fbin[j]; }
-                __syncthreads();
+                lds_sync();
                 if (mv) { fxy[j - 1] = a; fwh[j - 1] = b; fbin[j - 1] = c; }
-                __syncthreads();
+                lds_sync();
             }
         }
         if (tid < ni) { fxy[at + tid] = ixy[tid]; fwh[at + tid] = iwh[tid]; fbin[at + tid] = fb; }
@@ -220,7 +225,7 @@ __global__ __launch_bounds__(256) void k_plan_place(const rh_rawbox* __restrict_
         nfree = cur_n + delta;
     }
     // boxes that did not fit (only after an overflow)
-    for (uint32_t j = i + tid; j < n; j += 256) { box_pos[2 * j] = RH_NO_BIN; box_pos[2 * j + 1] = 0; }
+    for (uint32_t j = i + tid; j < n; j += NT) { box_pos[2 * j] = RH_NO_BIN; box_pos[2 * j + 1] = 0; }
     if (tid == 0) { pcount[1] = nbins; pcount[2] = overflow ? 1u : 0u; }
 }
 
@@ -282,7 +287,7 @@ rh_status rh_launch_plan(rh_ctx* ctx, int F, const float* imp, const uint8_t* ma
     const int nblk = (total + 255) / 256;
     hipLaunchKernelGGL(k_plan_rank, dim3(nblk), dim3(256), 0, ctx->stream, ctx->raw, ctx->pcount, ctx->sorted,
                        ctx->rank_of_id);
-    hipLaunchKernelGGL(k_plan_place, dim3(1), dim3(256), (size_t)ctx->free_cap * 12, ctx->stream, ctx->sorted,
+    hipLaunchKernelGGL(k_plan_place, dim3(1), dim3(64), (size_t)ctx->free_cap * 12, ctx->stream, ctx->sorted,
                        ctx->pcount, ctx->cfg.halo, ctx->cfg.bin_size, ctx->cfg.max_bins, ctx->free_cap, box_pos);
     hipLaunchKernelGGL(k_plan_emit, dim3(nblk), dim3(256), 0, ctx->stream, ctx->sorted, box_pos, ctx->pcount,
                        list, n_sel, ctx->owner_id, ctx->rank_of_id, ctx->mbw, per, ctx->cfg.halo, boxes, places,

@@ -20,6 +20,26 @@ __device__ __forceinline__ uint32_t imp_key(float v)
 // Kernel 1: one workgroup per segment.  Finds the segment's threshold key T and tie budget,
 // then the number of selected macroblocks and admitted ties of each of its frames.
 // seg_par[seg] = {g_begin, g_end, k, thr bits}.
+// A queue of up to KREG * 1024 keys (a 30-frame chunk of 480x272 streams is 15k) is read from
+// global memory once and kept in registers over the four radix passes.
+#define KREG 16
+#define FCHUNK 1024          // frames whose counts are held in LDS at a time
+
+__device__ __forceinline__ void hist_add(uint32_t* hist, bool todo, uint32_t bin, bool aggregate)
+{
+    if (!aggregate) { if (todo) atomicAdd(&hist[bin], 1u); return; }
+    // the top byte (sign and exponent) puts most keys into a few bins: lanes of a wave that
+    // hit the same bin are counted with one ballot and added by one lane
+    while (__any(todo)) {
+        const unsigned long long act = __ballot(todo);
+        const int first = __ffsll((long long)act) - 1;
+        const uint32_t b = __shfl(bin, first);
+        const unsigned long long same = __ballot(todo && bin == b);
+        if ((int)(threadIdx.x & 63) == first) atomicAdd(&hist[b], (uint32_t)__popcll(same));
+        todo = todo && bin != b;
+    }
+}
+
 __global__ __launch_bounds__(1024) void k_select_kth(const float* __restrict__ imp,
                                                      const uint32_t* __restrict__ seg_par, int mode,
                                                      int per, uint32_t* __restrict__ seg_T,
@@ -27,7 +47,8 @@ __global__ __launch_bounds__(1024) void k_select_kth(const float* __restrict__ i
                                                      uint32_t* __restrict__ frame_ties)
 {
     __shared__ uint32_t hist[256];
-    __shared__ uint32_t s_prefix, s_remaining, s_gt, s_eq;
+    __shared__ uint32_t s_prefix, s_remaining;
+    __shared__ uint32_t s_gt[FCHUNK], s_eq[FCHUNK], s_scan[2][FCHUNK];
     const int tid = threadIdx.x, seg = blockIdx.x;
     const uint32_t g0 = seg_par[4 * seg], g1 = seg_par[4 * seg + 1];
     const uint32_t n = g1 - g0;
@@ -41,24 +62,41 @@ __global__ __launch_bounds__(1024) void k_select_kth(const float* __restrict__ i
         if (k > n) k = n;
         if (k == 0) { T = 0xFFFFFFFFu; budget = 0u; }            // no key reaches 0xFFFFFFFF
         else {
+            const bool in_regs = n <= KREG * 1024u;
+            uint32_t keys[KREG];
+            if (in_regs) {
+#pragma unroll
+                for (int j = 0; j < KREG; ++j) {
+                    const uint32_t i = (uint32_t)j * 1024u + tid;
+                    keys[j] = i < n ? imp_key(imp[g0 + i]) : 0u;
+                }
+            }
             uint32_t prefix = 0, remaining = k;
             for (int pass = 3; pass >= 0; --pass) {
                 const int shift = pass * 8;
                 const uint32_t hi_mask = (pass == 3) ? 0u : (0xFFFFFFFFu << (shift + 8));
-                for (int i = tid; i < 256; i += 1024) hist[i] = 0;
+                if (tid < 256) hist[tid] = 0;
                 __syncthreads();
-                for (uint32_t i = tid; i < n; i += 1024) {
-                    uint32_t key = imp_key(imp[g0 + i]);
-                    if ((key & hi_mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+                if (in_regs) {
+#pragma unroll
+                    for (int j = 0; j < KREG; ++j) {
+                        const uint32_t i = (uint32_t)j * 1024u + tid;
+                        if ((uint32_t)j * 1024u < n)                 // uniform over the workgroup
+                            hist_add(hist, i < n && (keys[j] & hi_mask) == prefix, (keys[j] >> shift) & 255u, pass == 3);
+                    }
+                } else {
+                    for (uint32_t i0 = 0; i0 < n; i0 += 1024) {
+                        const uint32_t i = i0 + tid;
+                        const uint32_t key = i < n ? imp_key(imp[g0 + i]) : 0u;
+                        hist_add(hist, i < n && (key & hi_mask) == prefix, (key >> shift) & 255u, pass == 3);
+                    }
                 }
                 __syncthreads();
-                if (tid == 0) {
-                    uint32_t c = 0;
-                    for (int b = 255; b >= 0; --b) {
-                        uint32_t h = hist[b];
-                        if (c + h >= remaining) { s_prefix = prefix | ((uint32_t)b << shift); s_remaining = remaining - c; break; }
-                        c += h;
-                    }
+                if (tid < 256) {                               // bin t holds the k-th key iff  above(t) < remaining <= above(t) + hist[t]
+                    uint32_t above = 0;
+                    for (int b = tid + 1; b < 256; ++b) above += hist[b];
+                    const uint32_t h = hist[tid];
+                    if (above < remaining && remaining <= above + h) { s_prefix = prefix | ((uint32_t)tid << shift); s_remaining = remaining - above; }
                 }
                 __syncthreads();
                 prefix = s_prefix; remaining = s_remaining;
@@ -68,23 +106,45 @@ __global__ __launch_bounds__(1024) void k_select_kth(const float* __restrict__ i
         }
     }
     if (tid == 0) seg_T[seg] = T;
-    // per-frame counts, frames in ascending order so earlier frames get the ties first
-    uint32_t left = budget;
+    // per-frame counts: one wave per frame; the ties are then dealt to the frames in ascending
+    // order, so a frame may take  min(eq, budget - ties of the frames before it)
     const uint32_t f0 = g0 / per, f1 = g1 / per;
-    for (uint32_t f = f0; f < f1; ++f) {
-        if (tid == 0) { s_gt = 0; s_eq = 0; }
-        __syncthreads();
-        uint32_t gt = 0, eq = 0;
-        for (int i = tid; i < per; i += 1024) {
-            uint32_t key = imp_key(imp[(size_t)f * per + i]);
-            gt += key > T; eq += key == T;
+    const int lane = tid & 63, wave = tid >> 6;
+    uint32_t left = budget;                                    // uniform over the workgroup
+    for (uint32_t c0 = f0; c0 < f1; c0 += FCHUNK) {
+        const uint32_t nf = (f1 - c0) < FCHUNK ? (f1 - c0) : FCHUNK;
+        for (uint32_t j = wave; j < nf; j += 16) {
+            const size_t fb = (size_t)(c0 + j) * per;
+            uint32_t gt = 0, eq = 0;
+            for (int i = lane; i < per; i += 64) {
+                const uint32_t key = imp_key(imp[fb + i]);
+                gt += key > T; eq += key == T;
+            }
+            for (int o = 32; o > 0; o >>= 1) { gt += __shfl_xor(gt, o); eq += __shfl_xor(eq, o); }
+            if (lane == 0) { s_gt[j] = gt; s_eq[j] = eq; }
         }
-        if (gt) atomicAdd(&s_gt, gt);
-        if (eq) atomicAdd(&s_eq, eq);
         __syncthreads();
-        uint32_t ties = s_eq < left ? s_eq : left;
-        if (tid == 0) { frame_nsel[f] = s_gt + ties; frame_ties[f] = ties; }
-        left -= ties;
+        // inclusive scan of eq over the chunk (saturating: sums only matter up to `left`)
+        int cur = 0;
+        if ((uint32_t)tid < nf) s_scan[0][tid] = s_eq[tid];
+        __syncthreads();
+        for (uint32_t d = 1; d < nf; d <<= 1) {
+            if ((uint32_t)tid < nf) {
+                uint32_t v = s_scan[cur][tid];
+                if ((uint32_t)tid >= d) { const uint32_t u = s_scan[cur][tid - d]; v = (v + u < v) ? 0xFFFFFFFFu : v + u; }
+                s_scan[cur ^ 1][tid] = v;
+            }
+            cur ^= 1;
+            __syncthreads();
+        }
+        if ((uint32_t)tid < nf) {
+            const uint32_t eq = s_eq[tid], before = s_scan[cur][tid] - eq;   // exclusive (exact unless saturated, then >= left anyway)
+            const uint32_t room = before < left ? left - before : 0u;
+            const uint32_t ties = eq < room ? eq : room;
+            frame_nsel[c0 + tid] = s_gt[tid] + ties; frame_ties[c0 + tid] = ties;
+        }
+        const uint32_t tot = s_scan[cur][nf - 1];
+        left = tot < left ? left - tot : 0u;
         __syncthreads();
     }
 }

@@ -31,64 +31,112 @@ __global__ __launch_bounds__(256) void k_identity_places(rh_mbplace* __restrict_
     places[g] = p;
 }
 
-// One workgroup per macroblock: (16s x 16s) output pixels from an 18 x 18 input tile in LDS.
-// Each thread produces runs of 4 pixels = 12 bytes.
-__global__ __launch_bounds__(256) void k_unpack(const uint8_t* __restrict__ lr, int H, int W, int s,
+// Bilinear base + paste for integer scale S.  A workgroup writes a strip of NMBX macroblocks
+// (one macroblock row tall): the 64 lanes of a wave lie side by side along x, 4 output pixels
+// (12 bytes) each, so a wave instruction writes up to 768 contiguous bytes; the 4 waves split
+// the 16 input rows.  The input tile (18 rows, clamped at the frame edge) sits in LDS.
+// Exact integer interpolation: weights are multiples of 1/(2S) in each direction,
+// out = (sum + D*D/2) / (D*D) with D = 2S.  For a placed macroblock the pixel becomes
+// floor(255 * clamp(base/255 + net, 0, 1) + 0.5) in fp32 (base/255 from a 256-entry table of
+// correctly rounded quotients).
+template <int S>
+__global__ __launch_bounds__(256) void k_unpack(const uint8_t* __restrict__ lr, int H, int W, int mbw,
                                                 const float* __restrict__ enh, int n_img, int ih, int iw,
                                                 const rh_mbplace* __restrict__ places,
                                                 const int32_t* __restrict__ slot_of_mb,
                                                 uint8_t* __restrict__ hr, float* __restrict__ sel)
 {
-    __shared__ uint8_t tile[18][18][3];
-    const int mx = blockIdx.x, my = blockIdx.y, f = blockIdx.z, tid = threadIdx.x;
-    const int mbw = gridDim.x, mbh = gridDim.y;
+    constexpr int B = RH_MB * S, D = 2 * S, GPM = B / 4, NMBX = 64 / GPM, LANES = NMBX * GPM;
+    constexpr int TWID = RH_MB * NMBX + 2;
+    __shared__ uint8_t tile[18][TWID][3];
+    __shared__ float q255[256];
+    const int strip = blockIdx.x, my = blockIdx.y, f = blockIdx.z, tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6, mbh = gridDim.y;
     const uint8_t* src = lr + (size_t)f * H * W * 3;
-    for (int i = tid; i < 18 * 18 * 3; i += 256) {
-        const int c = i % 3, px = (i / 3) % 18, py = i / 54;
-        const int y = min(max(RH_MB * my - 1 + py, 0), H - 1), x = min(max(RH_MB * mx - 1 + px, 0), W - 1);
+    const int lx0 = RH_MB * NMBX * strip - 1;
+    for (int i = tid; i < 18 * TWID * 3; i += 256) {
+        const int c = i % 3, px = (i / 3) % TWID, py = i / (3 * TWID);
+        const int y = min(max(RH_MB * my - 1 + py, 0), H - 1), x = min(max(lx0 + px, 0), W - 1);
         tile[py][px][c] = src[((size_t)y * W + x) * 3 + c];
     }
+    q255[tid] = __fdiv_rn((float)tid, 255.0f);
+    __syncthreads();
+    const int mbi = lane / GPM, mx = strip * NMBX + mbi;
+    if (lane >= LANES || mx >= mbw) return;
+    const int gx = (lane - mbi * GPM) * 4;                // first of this lane's 4 pixels inside the macroblock
     const uint32_t g = ((uint32_t)f * mbh + my) * mbw + mx;
     const int slot = slot_of_mb[g];
     const float* net = nullptr;
     if (slot >= 0) {
         const rh_mbplace p = places[slot];
         if (p.bin != RH_NO_BIN && p.bin < n_img && p.px + RH_MB <= iw && p.py + RH_MB <= ih)
-            net = enh + (((size_t)p.bin * (ih * s) + (size_t)p.py * s) * (iw * s) + (size_t)p.px * s) * 3;
+            net = enh + (((size_t)p.bin * (ih * S) + (size_t)p.py * S) * (iw * S) + (size_t)p.px * S + gx) * 3;
     }
-    __syncthreads();
-    const int B = RH_MB * s, D = 2 * s, gpr = B / 4, ngrp = gpr * B;
-    const int HW = W * s;
-    uint8_t* dst = hr + (((size_t)f * H * s + (size_t)my * B) * HW + (size_t)mx * B) * 3;
-    for (int grp = tid; grp < ngrp; grp += 256) {
-        const int yy = grp / gpr, x4 = (grp - yy * gpr) * 4;
-        // vertical taps: source row = (2Y+1-s)/(2s) relative to the tile (tile row 0 = 16my-1)
-        const int ny = 2 * yy + 1 - s + D;                // shifted by one input row, always >= 0
-        const int ty = ny / D, wy1 = ny - ty * D, wy0 = D - wy1;
-        uint32_t bytes[12];
+    // horizontal taps of the 4 pixels: tile column and weight of the right neighbour
+    int tx[4], wx1[4];
 #pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            const int nx = 2 * (x4 + p) + 1 - s + D;
-            const int tx = nx / D, wx1 = nx - tx * D, wx0 = D - wx1;
+    for (int p = 0; p < 4; ++p) {
+        const int nx = 2 * (gx + p) + 1 - S + D;          // shifted by one input pixel, always >= 0
+        tx[p] = nx / D + RH_MB * mbi; wx1[p] = nx % D;
+    }
+    // horizontal sums of one tile row for the 4 pixels x 3 channels
+    auto hsum = [&](int row, int (&h)[12]) __attribute__((always_inline)) {
 #pragma unroll
-            for (int c = 0; c < 3; ++c) {
-                const int acc = wy0 * (wx0 * tile[ty][tx][c] + wx1 * tile[ty][tx + 1][c]) +
-                                wy1 * (wx0 * tile[ty + 1][tx][c] + wx1 * tile[ty + 1][tx + 1][c]);
-                uint32_t base = (uint32_t)(acc + D * D / 2) / (uint32_t)(D * D);
-                if (net) {
-                    const float nv = net[((size_t)yy * (iw * s) + x4 + p) * 3 + c];
-                    float e = __fadd_rn(__fdiv_rn((float)base, 255.0f), nv);
-                    e = fminf(fmaxf(e, 0.0f), 1.0f);
-                    if (sel) sel[(((size_t)slot * B + yy) * B + x4 + p) * 3 + c] = e;
-                    base = (uint32_t)floorf(__fadd_rn(__fmul_rn(e, 255.0f), 0.5f));
-                }
-                bytes[p * 3 + c] = base;
+        for (int p = 0; p < 4; ++p)
+#pragma unroll
+            for (int c = 0; c < 3; ++c) h[p * 3 + c] = (D - wx1[p]) * tile[row][tx[p]][c] + wx1[p] * tile[row][tx[p] + 1][c];
+    };
+    const int HW = W * S;
+    uint8_t* dst = hr + (((size_t)f * H * S + (size_t)my * B) * HW + (size_t)mx * B + gx) * 3;
+    int h0[12], h1[12], h2[12];                            // input rows r-1, r, r+1 (tile rows r, r+1, r+2)
+    const int r0 = wave * 4;
+    hsum(r0, h0); hsum(r0 + 1, h1);
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) {
+        const int r = r0 + rr;
+        hsum(r + 2, h2);
+#pragma unroll
+        for (int j = 0; j < S; ++j) {
+            const int ny = 2 * j + 1 - S;                  // relative to input row r, in units of 1/D
+            const int wy1 = ny < 0 ? ny + D : ny;
+            const int yy = r * S + j;
+            uint32_t bytes[12];
+#pragma unroll
+            for (int k = 0; k < 12; ++k) {
+                const int acc = ny < 0 ? (D - wy1) * h0[k] + wy1 * h1[k] : (D - wy1) * h1[k] + wy1 * h2[k];
+                bytes[k] = (uint32_t)(acc + D * D / 2) / (uint32_t)(D * D);
             }
+            if (net) {                                     // placed macroblock: one branch per row of 4 pixels
+                const float* nrow = net + (size_t)yy * (iw * S) * 3;
+                float nv[12];
+                if constexpr (S % 4 == 0) {                // 48-byte runs start 16-byte aligned
+                    const float4 a0 = ((const float4*)nrow)[0], a1 = ((const float4*)nrow)[1], a2 = ((const float4*)nrow)[2];
+                    nv[0] = a0.x; nv[1] = a0.y; nv[2] = a0.z; nv[3] = a0.w; nv[4] = a1.x; nv[5] = a1.y;
+                    nv[6] = a1.z; nv[7] = a1.w; nv[8] = a2.x; nv[9] = a2.y; nv[10] = a2.z; nv[11] = a2.w;
+                } else {
+#pragma unroll
+                    for (int k = 0; k < 12; ++k) nv[k] = nrow[k];
+                }
+                float ev[12];
+#pragma unroll
+                for (int k = 0; k < 12; ++k) {
+                    const float e = fminf(fmaxf(__fadd_rn(q255[bytes[k]], nv[k]), 0.0f), 1.0f);
+                    ev[k] = e;
+                    bytes[k] = (uint32_t)__fadd_rn(__fmul_rn(e, 255.0f), 0.5f);   // >= 0: truncation = floor
+                }
+                if (sel) {
+                    float* srow = sel + (((size_t)slot * B + yy) * B + gx) * 3;
+#pragma unroll
+                    for (int k = 0; k < 12; ++k) srow[k] = ev[k];
+                }
+            }
+            uint32_t* o = (uint32_t*)(dst + (size_t)yy * HW * 3);
+            o[0] = bytes[0] | (bytes[1] << 8) | (bytes[2] << 16) | (bytes[3] << 24);
+            o[1] = bytes[4] | (bytes[5] << 8) | (bytes[6] << 16) | (bytes[7] << 24);
+            o[2] = bytes[8] | (bytes[9] << 8) | (bytes[10] << 16) | (bytes[11] << 24);
         }
-        uint32_t* o = (uint32_t*)(dst + ((size_t)yy * HW + x4) * 3);
-        o[0] = bytes[0] | (bytes[1] << 8) | (bytes[2] << 16) | (bytes[3] << 24);
-        o[1] = bytes[4] | (bytes[5] << 8) | (bytes[6] << 16) | (bytes[7] << 24);
-        o[2] = bytes[8] | (bytes[9] << 8) | (bytes[10] << 16) | (bytes[11] << 24);
+#pragma unroll
+        for (int k = 0; k < 12; ++k) { h0[k] = h1[k]; h1[k] = h2[k]; }
     }
 }
 
@@ -107,8 +155,13 @@ rh_status rh_launch_unpack(rh_ctx* ctx, const float* enh, int n_img, int ih, int
     rh_prof_scope ps(ctx, RH_PROF_UNPACK, 3);
     rh_fill_i32(ctx, ctx->slot_of_mb, -1, (size_t)total);
     hipLaunchKernelGGL(k_slot_scatter, dim3(nb), dim3(256), 0, ctx->stream, places, n_places, total, ctx->slot_of_mb);
-    hipLaunchKernelGGL(k_unpack, dim3(ctx->mbw, ctx->mbh, F), dim3(256), 0, ctx->stream, lr, ctx->cfg.frame_h,
-                       ctx->cfg.frame_w, ctx->cfg.net.scale, enh, n_img, ih, iw, places, ctx->slot_of_mb, hr, sel);
+    const int S = ctx->cfg.net.scale;
+#define LAUNCH_UNPACK(SC)                                                                                       \
+    hipLaunchKernelGGL(k_unpack<SC>, dim3((ctx->mbw + (64 / (4 * SC)) - 1) / (64 / (4 * SC)), ctx->mbh, F), dim3(256), 0, \
+                       ctx->stream, lr, ctx->cfg.frame_h, ctx->cfg.frame_w, ctx->mbw, enh, n_img, ih, iw, places,  \
+                       ctx->slot_of_mb, hr, sel)
+    if (S == 1) LAUNCH_UNPACK(1); else if (S == 2) LAUNCH_UNPACK(2); else if (S == 3) LAUNCH_UNPACK(3); else LAUNCH_UNPACK(4);
+#undef LAUNCH_UNPACK
     RH_HIP(ctx, hipGetLastError());
     return RH_OK;
 }
