@@ -451,6 +451,19 @@ rh_status rh_pack_weights_bf16(rh_ctx* ctx, const float* blob)
             continue;
         }
         const bool last = (li == nl - 1);
+        L.tail3 = 0;
+        if (last && L.cout == 3) {             // [ks][lane][8]: row m = lane%32 = tap*3 + co, ci = 16*ks + 8*(lane/32) + e
+            L.tail3 = 1; L.cout_pad = 32; L.ps = 1;
+            for (int ks = 0; ks < L.cin / 16; ++ks)
+                for (int lane = 0; lane < 64; ++lane)
+                    for (int e = 0; e < 8; ++e) {
+                        const int m = lane & 31, tap = m / 3, co = m - tap * 3;
+                        const int ci = ks * 16 + 8 * (lane >> 5) + e;
+                        wp.push_back(f32_to_bf16_rne(m < 27 ? w[((size_t)co * 9 + tap) * L.cin + ci] : 0.0f));
+                    }
+            for (int co = 0; co < 4; ++co) bp.push_back(co < 3 ? b[co] : 0.0f);
+            continue;
+        }
         int ps = 1;
         if (!last && L.cout != C) {            // upsampling conv: cout = C * r^2
             ps = (L.cout == 4 * C) ? 2 : (L.cout == 9 * C ? 3 : 0);
@@ -515,7 +528,9 @@ static rh_status conv(rh_ctx* ctx, const rh_layer& L, const __bf16* in, void* ou
     const int MT = last ? L.cout_pad / 32 : L.cin / 32;
     hipError_t e;
     // bf16-output convs come as (ReLU, no skip), (skip, no ReLU) or (neither)
-    if (L.cin == 64) {
+    if (last && L.tail3 && s_final == 1) e = rh_launch_conv_tail3(ctx->stream, a, L.cin);
+    else if (last && L.tail3) RH_FAIL(ctx, RH_E_UNIMPLEMENTED, "3-channel last conv with a pixel shuffle");
+    else if (L.cin == 64) {
         if (last) e = (MT == 2) ? launch_conv<64, 2, 16, true, false, false>(ctx, a, grid) : launch_conv<64, 1, 8, true, false, false, 2>(ctx, a, 2 * grid);
         else e = rh_launch_conv_duo(ctx->stream, a, grid, skip != nullptr, relu != 0);    // two-team kernel
     } else {

@@ -45,3 +45,5 @@ __device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u 
 
 // two-team kernel for the 64-channel bf16-output convs (conv_mfma_duo.hip)
 hipError_t rh_launch_conv_duo(hipStream_t stream, const conv_args& a, int grid, bool skip, bool relu);
+// last conv with 3 output channels and no pixel shuffle (conv_tail.hip)
+hipError_t rh_launch_conv_tail3(hipStream_t stream, const conv_args& a, int cin);

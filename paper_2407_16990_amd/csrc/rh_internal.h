@@ -18,6 +18,7 @@ struct rh_layer {
     size_t bp_off;          // offset (floats) into bpack (bias, permuted/padded like the weights)
     int cout_pad;           // cout rounded up to the kernel's M tile
     int ps;                 // pixel-shuffle factor folded into the output-channel order (1 = none)
+    int tail3;              // 1: last conv with 3 outputs, packed for k_conv_tail3 (conv_tail.hip)
 };
 
 // Raw (unsorted) box written by the labelling kernel.
