@@ -63,6 +63,13 @@ def main():
     ap.add_argument("--config", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-frame-based", action="store_true")
+    ap.add_argument("--fraction", type=float, default=None,
+                    help="override the selected fraction of the configuration (the fraction sweep of configuration 4)")
+    ap.add_argument("--importance", choices=["clustered", "uniform"], default=None,
+                    help="override the importance recipe (uniform = iid, isolated macroblocks: the packer's worst case)")
+    ap.add_argument("--mem-batch", type=int, default=16, metavar="X",
+                    help="also time the memory-bound steps (pack gather, unpack) on X copies of the batch, where "
+                         "they are large enough to be bandwidth- rather than launch-bound (0 = skip)")
     ap.add_argument("--sync-counts", action="store_true",
                     help="read the bin count back to the host after rh_pack (one synchronisation per step) and "
                          "enhance exactly that many bins, instead of passing the device-side count")
@@ -79,10 +86,15 @@ def main():
     from paper_2407_16990_amd import RH
 
     cfg = wl.config(args.config)
+    if args.fraction is not None:
+        cfg = wl.replace(cfg, frac=args.fraction, name=f"{cfg.name}_frac{args.fraction:g}")
+    if args.importance is not None and args.importance != cfg.importance:
+        cfg = wl.replace(cfg, importance=args.importance, name=f"{cfg.name}_{args.importance}")
     F, s = cfg.n_frames, cfg.net.scale
     frames, imp, segs = wl.make_frames(cfg), wl.make_importance(cfg), wl.make_segments(cfg)
     blob = wl.make_weights(cfg.net, cfg.weight_seed, cfg.precision)
-    max_bins = 512 if cfg.index == 5 else 256
+    # room for the packer's worst case (isolated macroblocks: one box each)
+    max_bins = 512 if (cfg.index == 5 or cfg.importance == "uniform") else 256
     rh = RH(frame_w=cfg.width, frame_h=cfg.height, max_frames=F, halo=cfg.halo, bin_size=cfg.bin_size,
             max_bins=max_bins, net=cfg.net, weights=blob, precision=cfg.precision)
     d_frames = torch.from_numpy(frames).cuda()
@@ -153,6 +165,52 @@ def main():
         "enhance_tflops_all_layers": total_flops_per_lr_pixel(cfg.net) * px_lr /
                                      (sum(prof[k][0] for k in ("head", "conv", "conv_last")) / args.steps * 1e-3) / 1e12,
     }
+
+    # ---- the memory-bound steps: algorithmic bytes / event time, at batch size and at X batches ----
+    def mem_bytes(nb, boxes_host, nsel, nf):
+        box_px = sum((16 * int(b["wmb"]) + 2 * cfg.halo) * (16 * int(b["hmb"]) + 2 * cfg.halo) for b in boxes_host)
+        pack_b = nb * S * S * 3 + box_px * 3                      # every bin byte written, box pixels read
+        unpack_b = nf * cfg.height * s * cfg.width * s * 3 + nf * cfg.height * cfg.width * 3 + nsel * (16 * s) ** 2 * 3 * 4
+        return pack_b, unpack_b
+
+    boxes_host = RH.boxes_np(po.boxes, n_boxes)
+    pb, ub = mem_bytes(n_bins, boxes_host, k_sel, F)
+    result["memory_steps"] = {
+        "pack_gather": {"bytes": pb, "us": prof["gather"][0] / args.steps * 1e3, "GB/s": pb / (prof["gather"][0] / args.steps * 1e-3) / 1e9},
+        "unpack": {"bytes": ub, "us": prof["unpack"][0] / args.steps * 1e3, "GB/s": ub / (prof["unpack"][0] / args.steps * 1e-3) / 1e9},
+        "hbm_peak_GB/s": 8000.0}
+    if args.mem_batch > 0:
+        X = args.mem_batch
+        rhx = RH(frame_w=cfg.width, frame_h=cfg.height, max_frames=F * X, halo=cfg.halo, bin_size=cfg.bin_size,
+                 max_bins=max_bins * X, net=cfg.net, weights=blob, precision=cfg.precision)
+        xf = d_frames.repeat(X, 1, 1, 1)
+        xi = d_imp.repeat(X, 1, 1)
+        xsegs = [(r[0] + j * F, r[1] + j * F) + tuple(r[2:]) for j in range(X) for r in seg_rows]
+        xhr = torch.empty((F * X, cfg.height * s, cfg.width * s, 3), dtype=torch.uint8, device="cuda")
+        xpo = None
+        xnet = None
+        reps = 5
+        for it in range(reps + 1):
+            if it == 1:
+                rhx.profile_enable(True)
+                rhx.profile_read()
+            m_, l_, n_ = rhx.select_regions(xi, xsegs)
+            xpo = rhx.pack(xf, xi, m_, l_, n_, out=xpo)
+            if xnet is None:
+                xc = rhx.read_counts(xpo.counts)
+                # unpack only reads the enhanced tensor: any values do for timing
+                xnet = torch.zeros((xc[1], S * s, S * s, 3), dtype=torch.float32, device="cuda")
+            rhx.unpack(xnet, xpo.places, xpo.counts[3:4], xf, out=xhr)
+        torch.cuda.synchronize()
+        xprof = rhx.profile_read()
+        rhx.profile_enable(False)
+        xboxes = RH.boxes_np(xpo.boxes, xc[0])
+        xpb, xub = mem_bytes(xc[1], xboxes, xc[3], F * X)
+        result["memory_steps"][f"x{X}"] = {
+            "frames": F * X, "n_bins": xc[1],
+            "pack_gather": {"bytes": xpb, "us": xprof["gather"][0] / reps * 1e3, "GB/s": xpb / (xprof["gather"][0] / reps * 1e-3) / 1e9},
+            "unpack": {"bytes": xub, "us": xprof["unpack"][0] / reps * 1e3, "GB/s": xub / (xprof["unpack"][0] / reps * 1e-3) / 1e9}}
+        del rhx, xf, xi, xhr, xnet, xpo
 
     if not args.no_frame_based:
         # 100 % of the macroblocks: rh_enhance on whole frames + identity placement

@@ -226,7 +226,10 @@ __global__ __launch_bounds__(512) void k_conv_mfma_duo(conv_args a)
                     PH2(2);
                 }
             };
-            __builtin_amdgcn_s_setprio(2);                    // the wave feeding the matrix pipe goes first
+#ifndef DUO_PRIO
+#define DUO_PRIO 2
+#endif
+            __builtin_amdgcn_s_setprio(DUO_PRIO);             // the wave feeding the matrix pipe goes first
             for_each_step2<NSTEP>(step);
             __builtin_amdgcn_s_setprio(0);
 
@@ -241,17 +244,21 @@ __global__ __launch_bounds__(512) void k_conv_mfma_duo(conv_args a)
                 (void*)((uint8_t*)a.out + (size_t)n * out_img_bytes), 0, out_img_bytes, RSRC_FLAGS);
             uint4 sk[SKIP ? NOUT : 1];
             // All global loads of the team are issued here, by waves that are not feeding the
-            // matrix pipe: the next tile's patch (stored to LDS at the end of the phase) and
-            // this tile's skip values (used after the first barrier).
-#pragma unroll
-            for (int j = 0; j < NPRE; ++j) load_piece(j, rin, ny0, nx0);
-            if constexpr (SKIP) {
-#pragma unroll
-                for (int j = 0; j < NOUT; ++j) {
-                    const i32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsk, out_off(j, y0, x0, 0, 0), 0, 0);
-                    sk[j] = make_uint4(v[0], v[1], v[2], v[3]);
+            // matrix pipe: this tile's skip values (used after the wave-local wait) and the next
+            // tile's patch (stored to LDS at the end of the phase).  The CU's one address unit
+            // takes about 16 cycles per 64 x 16-byte instruction and all four waves of the team
+            // arrive together, so a wave that issues its loads back to back is held for 60-90
+            // cycles by each of them: the loads are dealt out one or two at a time between the
+            // 16 units of rounding work instead.
+            constexpr int NLD = NPRE + (SKIP ? NOUT : 0), NUNIT = MT * 4 * RW;
+            auto issue_load = [&](int i) __attribute__((always_inline)) {
+                if (SKIP && i < NOUT) {
+                    const i32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsk, out_off(i, y0, x0, 0, 0), 0, 0);
+                    sk[i] = make_uint4(v[0], v[1], v[2], v[3]);
+                } else {
+                    load_piece(i - (SKIP ? NOUT : 0), rin, ny0, nx0);
                 }
-            }
+            };
             uint8_t* stg = lds_p + wave * (RW * 32 * OPIXB);
             const int okey = lx & 7;
 #pragma unroll
@@ -260,20 +267,34 @@ __global__ __launch_bounds__(512) void k_conv_mfma_duo(conv_args a)
                 for (int q = 0; q < 4; ++q)
 #pragma unroll
                     for (int r = 0; r < RW; ++r) {
+                        const int u = (m * 4 + q) * RW + r;
+#pragma unroll
+                        for (int i = u * NLD / NUNIT; i < (u + 1) * NLD / NUNIT; ++i) issue_load(i);
                         float v0 = acc[r][m][4 * q + 0], v1 = acc[r][m][4 * q + 1], v2 = acc[r][m][4 * q + 2], v3 = acc[r][m][4 * q + 3];
-                        if constexpr (RELU) { v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); v2 = fmaxf(v2, 0.f); v3 = fmaxf(v3, 0.f); }
+                        if constexpr (RELU) {       // one v_med3 each (fmaxf would add a canonicalising v_max)
+                            const float inf = __builtin_inff();
+                            v0 = __builtin_amdgcn_fmed3f(v0, 0.f, inf); v1 = __builtin_amdgcn_fmed3f(v1, 0.f, inf);
+                            v2 = __builtin_amdgcn_fmed3f(v2, 0.f, inf); v3 = __builtin_amdgcn_fmed3f(v3, 0.f, inf);
+                        }
                         uint2 pk;
                         pk.x = pack_bf16x2(v0, v1); pk.y = pack_bf16x2(v2, v3);
                         *(uint2*)(stg + (r * 32 + lx) * OPIXB + (((m * 4 + q) ^ okey) << 4) + hi * 8) = pk;
+                        __builtin_amdgcn_sched_barrier(0);
                     }
             seed_acc();
             PH2(3);
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");     // the slice is private to the wave: no barrier
             PH2(4);
+            uint4 ov[NOUT];
 #pragma unroll
             for (int j = 0; j < NOUT; ++j) {
                 const int r = j / JPR, px = (j % JPR) * PPJ + lcol;
-                uint4 o = *(const uint4*)(stg + (r * 32 + px) * OPIXB + ((lc ^ (px & 7)) << 4));
+                ov[j] = *(const uint4*)(stg + (r * 32 + px) * OPIXB + ((lc ^ (px & 7)) << 4));
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int j = 0; j < NOUT; ++j) {
+                uint4 o = ov[j];
                 if constexpr (SKIP) {
                     o.x = pack_bf16x2(bf16_lo(o.x) + bf16_lo(sk[j].x), bf16_hi(o.x) + bf16_hi(sk[j].x));
                     o.y = pack_bf16x2(bf16_lo(o.y) + bf16_lo(sk[j].y), bf16_hi(o.y) + bf16_hi(sk[j].y));
@@ -282,6 +303,7 @@ __global__ __launch_bounds__(512) void k_conv_mfma_duo(conv_args a)
                 }
                 const i32x4 v = {(int)o.x, (int)o.y, (int)o.z, (int)o.w};
                 __builtin_amdgcn_raw_buffer_store_b128(v, rout, out_off(j, y0, x0, si, sj), 0, 0);
+                if constexpr (SKIP) __builtin_amdgcn_sched_barrier(0);
             }
             PH2(5);
             phase_barrier();                                  // 1: every wave of the team has read its slice back
@@ -312,7 +334,13 @@ static hipError_t launch_duo(hipStream_t stream, const conv_args& a, int grid)
 hipError_t rh_launch_conv_duo(hipStream_t stream, const conv_args& a, int grid, bool skip, bool relu)
 {
     // first barrier of the compute phase after 11 of the 12 steps (measured best for all variants)
-    if (skip) return launch_duo<true, false, 11>(stream, a, grid);
-    if (relu) return launch_duo<false, true, 11>(stream, a, grid);
-    return launch_duo<false, false, 11>(stream, a, grid);
+#ifndef DUO_MID_SKIP
+#define DUO_MID_SKIP 11
+#endif
+#ifndef DUO_MID_PLAIN
+#define DUO_MID_PLAIN 11
+#endif
+    if (skip) return launch_duo<true, false, DUO_MID_SKIP>(stream, a, grid);
+    if (relu) return launch_duo<false, true, DUO_MID_PLAIN>(stream, a, grid);
+    return launch_duo<false, false, DUO_MID_PLAIN>(stream, a, grid);
 }
