@@ -27,7 +27,9 @@ MFMA_BF16_PEAK = 2.5e15   # dense bf16 MFMA, FLOP/s (MI355X published)
 # HBM bytes per launch of the dominant kernel class on the default workload, from the rocprofv3
 # FETCH_SIZE / WRITE_SIZE runs summarised in profiles/conv_mfma_cfg3_hbm_counters.md (scaled by
 # the plain-copy calibration); not measured live, so only reported for that workload.
-MEASURED_TRAFFIC = {"cfg3_16x480x272_edsr64_x4_bf16": 564.4e6}
+MEASURED_TRAFFIC = {"cfg3_16x480x272_edsr64_x4_bf16": 565.0e6}
+CONV_KERNEL = {64: "k_conv_mfma_duo<SKIP,RELU,11> (bf16-output 64-channel convs: ReLU, skip-add and plain instantiations)",
+               32: "k_conv_mfma<32,1,16,false,SKIP,RELU> (bf16-output 32-channel convs)"}
 
 
 def conv_flops_per_lr_pixel(net):
@@ -67,6 +69,9 @@ def main():
                     help="override the selected fraction of the configuration (the fraction sweep of configuration 4)")
     ap.add_argument("--importance", choices=["clustered", "uniform"], default=None,
                     help="override the importance recipe (uniform = iid, isolated macroblocks: the packer's worst case)")
+    ap.add_argument("--probe-mfma", action="store_true",
+                    help="also run the register-only bf16 MFMA loop (all-ones and random operands) and report its "
+                         "TFLOP/s and sustained clock next to the published peak")
     ap.add_argument("--mem-batch", type=int, default=16, metavar="X",
                     help="also time the memory-bound steps (pack gather, unpack) on X copies of the batch, where "
                          "they are large enough to be bandwidth- rather than launch-bound (0 = skip)")
@@ -158,7 +163,7 @@ def main():
                    "occupy_ratio": 256.0 * k_sel / (n_bins * S * S) if n_bins else 0.0},
         "output_mpixel_per_s": out_mpix,
         "kernel_ms_per_step": {k: v[0] / args.steps for k, v in prof.items()},
-        "roofline": {"bound": "mfma", "kernel": "k_conv_mfma<64,2,16,false,*,*> (bf16-output convs: ReLU, skip and plain variants)", "achieved": achieved / 1e12,
+        "roofline": {"bound": "mfma", "kernel": CONV_KERNEL.get(cfg.net.channels, "k_conv_mfma"), "achieved": achieved / 1e12,
                      "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK,
                      "traffic": MEASURED_TRAFFIC.get(cfg.name), "avg_launch_us": avg_launch_s * 1e6, "launches_per_step": conv_n / args.steps,
                      "flop_per_launch": flop_per_launch},
@@ -211,6 +216,12 @@ def main():
             "pack_gather": {"bytes": xpb, "us": xprof["gather"][0] / reps * 1e3, "GB/s": xpb / (xprof["gather"][0] / reps * 1e-3) / 1e9},
             "unpack": {"bytes": xub, "us": xprof["unpack"][0] / reps * 1e3, "GB/s": xub / (xprof["unpack"][0] / reps * 1e-3) / 1e9}}
         del rhx, xf, xi, xhr, xnet, xpo
+
+    if args.probe_mfma:
+        result["mfma_probe"] = {}
+        for name, rnd in (("ones", False), ("random", True)):
+            tf, ghz, cyc = rh.probe_mfma(rnd, 40.0)
+            result["mfma_probe"][name] = {"TFLOP/s": tf, "clock_GHz": ghz, "cycles_per_mfma": cyc}
 
     if not args.no_frame_based:
         # 100 % of the macroblocks: rh_enhance on whole frames + identity placement

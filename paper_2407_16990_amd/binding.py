@@ -83,6 +83,7 @@ def load_library():
     L.rh_read_counts.argtypes = [vp, vp, C.POINTER(C.c_uint32 * 4)]
     L.rh_profile_enable.argtypes = [vp, i32]
     L.rh_profile_read.argtypes = [vp, C.POINTER(C.c_double * PROF_N), C.POINTER(C.c_uint32 * PROF_N)]
+    L.rh_probe_mfma.argtypes = [vp, C.c_int32, C.c_double, C.POINTER(C.c_double * 3)]
     _lib = L
     return L
 
@@ -212,6 +213,12 @@ class RH:
         ms, n = (C.c_double * PROF_N)(), (C.c_uint32 * PROF_N)()
         self._check(self.lib.rh_profile_read(self.h, C.byref(ms), C.byref(n)))
         return {k: (ms[i], n[i]) for i, k in enumerate(PROF_CLASSES)}
+
+    def probe_mfma(self, random_data: bool, ms_target: float = 30.0):
+        """-> (TFLOP/s, shader clock GHz, cycles per MFMA) of a register-only bf16 MFMA loop (synchronises)."""
+        out = (C.c_double * 3)()
+        self._check(self.lib.rh_probe_mfma(self.h, int(random_data), float(ms_target), C.byref(out)))
+        return out[0], out[1], out[2]
 
     # host-side views of the metadata
     @staticmethod
