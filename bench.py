@@ -69,6 +69,10 @@ def main():
                     help="override the selected fraction of the configuration (the fraction sweep of configuration 4)")
     ap.add_argument("--importance", choices=["clustered", "uniform"], default=None,
                     help="override the importance recipe (uniform = iid, isolated macroblocks: the packer's worst case)")
+    ap.add_argument("--bin-size", type=int, default=None, help="override the bin side S (pixels)")
+    ap.add_argument("--max-box-mbs", type=int, default=0,
+                    help="Partition's preset size in macroblocks (0 = the largest that fits a bin; 1 = every "
+                         "macroblock its own box, the paper's MB-packing / Block policy)")
     ap.add_argument("--probe-mfma", action="store_true",
                     help="also run the register-only bf16 MFMA loop (all-ones and random operands) and report its "
                          "TFLOP/s and sustained clock next to the published peak")
@@ -95,13 +99,18 @@ def main():
         cfg = wl.replace(cfg, frac=args.fraction, name=f"{cfg.name}_frac{args.fraction:g}")
     if args.importance is not None and args.importance != cfg.importance:
         cfg = wl.replace(cfg, importance=args.importance, name=f"{cfg.name}_{args.importance}")
+    if args.bin_size is not None and args.bin_size != cfg.bin_size:
+        cfg = wl.replace(cfg, bin_size=args.bin_size, name=f"{cfg.name}_S{args.bin_size}")
+    if args.max_box_mbs:
+        cfg = wl.replace(cfg, name=f"{cfg.name}_T{args.max_box_mbs}")
     F, s = cfg.n_frames, cfg.net.scale
     frames, imp, segs = wl.make_frames(cfg), wl.make_importance(cfg), wl.make_segments(cfg)
     blob = wl.make_weights(cfg.net, cfg.weight_seed, cfg.precision)
     # room for the packer's worst case (isolated macroblocks: one box each)
-    max_bins = 512 if (cfg.index == 5 or cfg.importance == "uniform") else 256
+    max_bins = 512 if (cfg.index == 5 or cfg.importance == "uniform" or args.max_box_mbs == 1) else 256
+    max_bins = max_bins * max(1, (128 // cfg.bin_size) ** 2)
     rh = RH(frame_w=cfg.width, frame_h=cfg.height, max_frames=F, halo=cfg.halo, bin_size=cfg.bin_size,
-            max_bins=max_bins, net=cfg.net, weights=blob, precision=cfg.precision)
+            max_bins=max_bins, net=cfg.net, weights=blob, precision=cfg.precision, max_box_mbs=args.max_box_mbs)
     d_frames = torch.from_numpy(frames).cuda()
     d_imp = torch.from_numpy(imp).cuda()
     seg_rows = [tuple(r) for r in segs.tolist()]
@@ -187,7 +196,8 @@ def main():
     if args.mem_batch > 0:
         X = args.mem_batch
         rhx = RH(frame_w=cfg.width, frame_h=cfg.height, max_frames=F * X, halo=cfg.halo, bin_size=cfg.bin_size,
-                 max_bins=max_bins * X, net=cfg.net, weights=blob, precision=cfg.precision)
+                 max_bins=max_bins * X, net=cfg.net, weights=blob, precision=cfg.precision,
+                 max_box_mbs=args.max_box_mbs)
         xf = d_frames.repeat(X, 1, 1, 1)
         xi = d_imp.repeat(X, 1, 1)
         xsegs = [(r[0] + j * F, r[1] + j * F) + tuple(r[2:]) for j in range(X) for r in seg_rows]

@@ -72,10 +72,12 @@ class Plan:
     places: np.ndarray   # int32 [k, 5]: mb_id, box, bin, px, py
     n_bins: int
     overflow: bool
+    place_rot: np.ndarray = None   # int32 [k]: 1 where the MB's box was packed turned
 
 
 def plan(mask: np.ndarray, imp: np.ndarray, halo: int, bin_size: int, conn: int = 8,
-         T: int | None = None, max_bins: int = 1 << 15) -> Plan:
+         T: int | None = None, max_bins: int = 1 << 15, sort_policy: str = "density",
+         rotate: bool = False) -> Plan:
     mask = np.ascontiguousarray(mask, dtype=np.uint8)
     imp = np.ascontiguousarray(imp, dtype=np.float32)
     F, mbh, mbw = mask.shape
@@ -85,11 +87,13 @@ def plan(mask: np.ndarray, imp: np.ndarray, halo: int, bin_size: int, conn: int 
     boxes = np.zeros((max(k, 1), 10), dtype=np.int32)
     places = np.zeros((max(k, 1), 5), dtype=np.int32)
     counts = np.zeros(3, dtype=np.int32)
+    rots = np.zeros(max(k, 1), dtype=np.int32)
     rc = lib().orc_plan(_p(mask), _p(imp), F, mbh, mbw, halo, bin_size, conn, T, max_bins,
-                        _p(boxes), _p(places), _p(counts))
+                        {"density": 0, "area": 1}[sort_policy], int(rotate),
+                        _p(boxes), _p(places), _p(rots), _p(counts))
     if rc != 0:
         raise ValueError("invalid packing geometry")
-    return Plan(boxes[: counts[0]].copy(), places[:k].copy(), int(counts[1]), bool(counts[2]))
+    return Plan(boxes[: counts[0]].copy(), places[:k].copy(), int(counts[1]), bool(counts[2]), rots[:k].copy())
 
 
 def gather(frames: np.ndarray, boxes: np.ndarray, halo: int, bin_size: int, n_bins: int) -> np.ndarray:
@@ -142,7 +146,7 @@ def sr_forward(net, blob: np.ndarray, imgs: np.ndarray) -> np.ndarray:
 
 
 def unpack(frames_lr: np.ndarray, s: int, net_out: np.ndarray, places: np.ndarray,
-           want_sel: bool = True):
+           want_sel: bool = True, place_rot: np.ndarray | None = None):
     """-> (frames_hr u8 [F,sH,sW,3], sel fp32 [k,16s,16s,3] or None)."""
     frames_lr = np.ascontiguousarray(frames_lr, dtype=np.uint8)
     net_out = np.ascontiguousarray(net_out, dtype=np.float64)
@@ -152,8 +156,12 @@ def unpack(frames_lr: np.ndarray, s: int, net_out: np.ndarray, places: np.ndarra
     k = len(places)
     hr = np.zeros((F, H * s, W * s, 3), dtype=np.uint8)
     sel = np.zeros((k, 16 * s, 16 * s, 3), dtype=np.float32) if want_sel else None
+    if place_rot is not None:
+        place_rot = np.ascontiguousarray(place_rot, dtype=np.int32).reshape(-1)
+        assert len(place_rot) == k
     lib().orc_unpack(_p(frames_lr), F, H, W, s, _p(net_out), oh // s, ow // s,
-                     _p(places), k, W // 16, H // 16, _p(hr), _p(sel) if want_sel else None)
+                     _p(places), _p(place_rot) if place_rot is not None else None, k, W // 16, H // 16,
+                     _p(hr), _p(sel) if want_sel else None)
     return hr, sel
 
 
@@ -177,11 +185,11 @@ class PathResult:
 
 
 def run_path(frames, imp, segs, net, blob, halo, bin_size, conn=8, T=None,
-             mode="topk", thr=None, max_bins=1 << 15) -> PathResult:
+             mode="topk", thr=None, max_bins=1 << 15, sort_policy="density", rotate=False) -> PathResult:
     """The whole hot path: select -> plan -> gather -> SR -> paste."""
     mask, lst = select(imp, segs, mode, thr)
-    pl = plan(mask, imp, halo, bin_size, conn, T, max_bins)
+    pl = plan(mask, imp, halo, bin_size, conn, T, max_bins, sort_policy, rotate)
     bins = gather(frames, pl.boxes, halo, bin_size, pl.n_bins)
     net_out = sr_forward(net, blob, bins)
-    hr, sel = unpack(frames, net.scale, net_out, pl.places)
+    hr, sel = unpack(frames, net.scale, net_out, pl.places, place_rot=pl.place_rot)
     return PathResult(mask, lst, pl, bins, net_out, hr, sel)

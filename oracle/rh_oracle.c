@@ -102,8 +102,9 @@ typedef struct {
     int frame, mbx0, mby0, wmb, hmb;
     int id;          /* smallest flat index among the MBs the box owns */
     float sum;       /* fp32 sum of owned importance, ascending flat index */
-    double key;      /* importance density = sum / (wmb*hmb) */
+    double key;      /* sort key, larger first: importance density = sum / (wmb*hmb), or the area */
     int bin, bx, by;
+    int rot;         /* 1: packed turned (rows and columns exchanged) */
 } obox;
 
 typedef struct { int bin, x, y, w, h; } orect;
@@ -123,16 +124,24 @@ static int obox_cmp(const void* pa, const void* pb)
     return (a->id > b->id) - (a->id < b->id);
 }
 
-/* Output rows: boxes_out[i] = {frame, mbx0, mby0, wmb, hmb, rot(=0), bin, bx, by, id}
+/* Output rows: boxes_out[i] = {frame, mbx0, mby0, wmb, hmb, rot, bin, bx, by, id}
  *              places_out[j] = {mb_id, box, bin, px, py}  (ascending mb_id)
+ *              place_rot_out[j] (may be NULL) = rot of the MB's box
  * counts_out = {n_boxes, n_bins, overflow}.
+ * sort_policy 0: importance density first (Alg. 1, Sort); 1: the classic large-item-first
+ * order the paper compares against (box area in MBs, descending).  Ties: ascending box id.
+ * rotate 0: boxes keep their orientation.  1: RotatePacking of Alg. 1 - a free area also
+ * accepts the box turned by a quarter, here read as "rows and columns exchanged"; the box is
+ * kept upright when it fits upright.  A turned box occupies (bh x bw) pixels; the MB at
+ * offset (dx, dy) of the upright box starts at (bx + dy, by + dx) and its pixels are
+ * transposed.
  * On overflow (more than max_bins bins needed) the first box that cannot be
  * placed and every later one get bin = 0xFFFF, bx = by = 0 (their MBs px = py = 0).
  * conn: 4 or 8.  T: largest box side in MBs (the partition's preset size).
  * Returns 0, or -1 on invalid geometry. */
 int orc_plan(const uint8_t* mask, const float* imp, int F, int mbh, int mbw,
-             int halo, int bin_size, int conn, int T, int max_bins,
-             int32_t* boxes_out, int32_t* places_out, int32_t* counts_out)
+             int halo, int bin_size, int conn, int T, int max_bins, int sort_policy, int rotate,
+             int32_t* boxes_out, int32_t* places_out, int32_t* place_rot_out, int32_t* counts_out)
 {
     int per = mbh * mbw, total = per * F;
     if (F < 0 || mbh < 1 || mbw < 1) return -1;
@@ -200,8 +209,9 @@ int orc_plan(const uint8_t* mask, const float* imp, int F, int mbh, int mbw,
             if (id < 0) continue;
             obox* b = &boxes[nb++];
             b->frame = f; b->mbx0 = x0; b->mby0 = y0; b->wmb = x1 - x0 + 1; b->hmb = y1 - y0 + 1;
-            b->id = id; b->sum = sum; b->key = (double)sum / (double)(b->wmb * b->hmb);
-            b->bin = -1; b->bx = b->by = 0;
+            b->id = id; b->sum = sum;
+            b->key = sort_policy == 1 ? (double)(b->wmb * b->hmb) : (double)sum / (double)(b->wmb * b->hmb);
+            b->bin = -1; b->bx = b->by = 0; b->rot = 0;
         }
     }
 
@@ -219,8 +229,12 @@ int orc_plan(const uint8_t* mask, const float* imp, int F, int mbh, int mbw,
         int bw = MBS * b->wmb + 2 * halo, bh = MBS * b->hmb + 2 * halo;
         if (overflow) { b->bin = 0xFFFF; continue; }
         int at = -1;
-        for (int j = 0; j < nfree; ++j)
-            if (fr[j].w >= bw && fr[j].h >= bh) { at = j; break; }
+        for (int j = 0; j < nfree; ++j) {
+            int upright = fr[j].w >= bw && fr[j].h >= bh;
+            int turned = rotate && fr[j].w >= bh && fr[j].h >= bw;      /* RotatePacking */
+            if (upright || turned) { at = j; b->rot = !upright; break; }
+        }
+        if (b->rot) { int t = bw; bw = bh; bh = t; }                    /* occupied size */
         if (at < 0) {
             if (nbins >= max_bins) { overflow = 1; b->bin = 0xFFFF; continue; }
             fr[nfree].bin = nbins++; fr[nfree].x = 0; fr[nfree].y = 0;
@@ -257,7 +271,7 @@ int orc_plan(const uint8_t* mask, const float* imp, int F, int mbh, int mbw,
     for (int i = 0; i < nb; ++i) {
         int32_t* o = boxes_out + 10 * i; obox* b = &boxes[i];
         o[0] = b->frame; o[1] = b->mbx0; o[2] = b->mby0; o[3] = b->wmb; o[4] = b->hmb;
-        o[5] = 0; o[6] = b->bin; o[7] = b->bx; o[8] = b->by; o[9] = b->id;
+        o[5] = b->rot; o[6] = b->bin; o[7] = b->bx; o[8] = b->by; o[9] = b->id;
     }
     /* Placement of every selected MB, ascending flat index. */
     int np = 0;
@@ -265,10 +279,12 @@ int orc_plan(const uint8_t* mask, const float* imp, int F, int mbh, int mbw,
         if (!mask[g]) continue;
         int y = (g % per) / mbw, x = g % mbw, found = idx_of_id[owner_id[g]];
         obox* b = &boxes[found];
+        int dx = halo + MBS * (x - b->mbx0), dy = halo + MBS * (y - b->mby0);
+        if (place_rot_out) place_rot_out[np] = b->rot;
         int32_t* o = places_out + 5 * np++;
         o[0] = g; o[1] = found; o[2] = b->bin;
-        o[3] = b->bin == 0xFFFF ? 0 : b->bx + halo + MBS * (x - b->mbx0);
-        o[4] = b->bin == 0xFFFF ? 0 : b->by + halo + MBS * (y - b->mby0);
+        o[3] = b->bin == 0xFFFF ? 0 : b->bx + (b->rot ? dy : dx);
+        o[4] = b->bin == 0xFFFF ? 0 : b->by + (b->rot ? dx : dy);
     }
     counts_out[0] = nb; counts_out[1] = nbins; counts_out[2] = overflow;
     free(comp); free(stack); free(comp_first); free(bx0); free(bx1); free(by0); free(by1);
@@ -279,7 +295,8 @@ int orc_plan(const uint8_t* mask, const float* imp, int F, int mbh, int mbw,
 /* ------------------------------------------------------------------------ */
 /* Sec. 3.3.3: stitch real pixels into the bins following the plan.
  * bins[b][y][x][c] is zero everywhere except inside placed boxes, where it is
- * the frame pixel under the box (zero where the box's halo leaves the frame). */
+ * the frame pixel under the box (zero where the box's halo leaves the frame).
+ * A turned box (rot = 1) is stored with rows and columns exchanged. */
 void orc_gather(const uint8_t* frames, int F, int H, int W,
                 const int32_t* boxes, int n_boxes, int halo, int bin_size, int n_bins,
                 uint8_t* bins)
@@ -299,7 +316,8 @@ void orc_gather(const uint8_t* frames, int F, int H, int W,
                 uint8_t v = 0;
                 if (sy >= 0 && sy < H && sx >= 0 && sx < W)
                     v = frames[(((size_t)f * H + sy) * W + sx) * 3 + c];
-                bins[(((size_t)bin * S + (b[8] + j)) * S + (b[7] + k)) * 3 + c] = v;
+                int row = b[5] ? k : j, col = b[5] ? j : k;
+                bins[(((size_t)bin * S + (b[8] + row)) * S + (b[7] + col)) * 3 + c] = v;
             }
         }
     }
@@ -443,11 +461,12 @@ void orc_sr_forward(int topology, int C, int nblk, int s, const float* blob,
  * frames_hr = bilinear base everywhere; each placed MB's (16s x 16s) block is
  * replaced by clamp(base/255 + net_out, 0, 1) quantised to 8 bits.  The last
  * three operations are taken in fp32 because they decide an integer that the
- * GPU decides in fp32.  net: fp64 [n_img][s*ih][s*iw][3].  places rows as in
- * orc_plan.  sel (optional): fp32 [k][16s][16s][3], the unquantised values. */
+ * GPU decides in fp32.  net: fp64 [n_img][s*ih][s*iw][3].  places rows and place_rot
+ * (may be NULL = none turned) as in orc_plan.  sel (optional): fp32 [k][16s][16s][3], the
+ * unquantised values. */
 void orc_unpack(const uint8_t* frames_lr, int F, int H, int W, int s,
                 const double* net, int ih, int iw,
-                const int32_t* places, int k, int mbw_frame, int mbh_frame,
+                const int32_t* places, const int32_t* place_rot, int k, int mbw_frame, int mbh_frame,
                 uint8_t* frames_hr, float* sel)
 {
     size_t lr = (size_t)H * W * 3, hr = lr * s * s;
@@ -462,7 +481,9 @@ void orc_unpack(const uint8_t* frames_lr, int F, int H, int W, int s,
         int f = g / per, my = (g % per) / mbw_frame, mx = g % mbw_frame;
         for (int y = 0; y < B; ++y) for (int x = 0; x < B; ++x) for (int c = 0; c < 3; ++c) {
             size_t di = (size_t)f * hr + (((size_t)(my * B + y)) * WW + (mx * B + x)) * 3 + c;
-            size_t si = (size_t)bin * nimg + (((size_t)(py * s + y)) * (iw * s) + (px * s + x)) * 3 + c;
+            int ny = y, nx = x;
+            if (place_rot && place_rot[i]) { ny = x; nx = y; }   /* turned box: transposed back */
+            size_t si = (size_t)bin * nimg + (((size_t)(py * s + ny)) * (iw * s) + (px * s + nx)) * 3 + c;
             float base = (float)frames_hr[di] / 255.0f;
             float e = base + (float)net[si];
             e = e < 0.0f ? 0.0f : (e > 1.0f ? 1.0f : e);

@@ -257,3 +257,69 @@ def test_all_selected_single_bin_equals_frame_based(orc):
     pl = orc.identity_places(1, 3, 3); pl[:, 3:] += 4
     hr, sel = orc.unpack(frames, 2, net, pl)
     assert np.array_equal(hr, r.frames_hr) and np.array_equal(sel, r.sel)
+
+
+def _rotating_case(orc):
+    """A small batch whose plan turns at least one box when RotatePacking is on."""
+    rng = np.random.default_rng(7)
+    F, mbh, mbw = 3, 6, 8
+    cfg = wl.replace(wl.config(1), n_frames=F, width=16 * mbw, height=16 * mbh)
+    frames = wl.make_frames(cfg)
+    mask = (rng.random((F, mbh, mbw)) < 0.35).astype(np.uint8)
+    imp = rng.random((F, mbh, mbw)).astype(np.float32)
+    pl = orc.plan(mask, imp, 4, 80, 4, 4, rotate=True)
+    assert pl.boxes[:, 5].sum() > 0 and (pl.boxes[:, 3] != pl.boxes[:, 4])[pl.boxes[:, 5] == 1].all()
+    return cfg, frames, mask, imp, pl
+
+
+def test_gather_turned_boxes_are_transposed_windows(orc):
+    """Alg. 1, RotatePacking: a turned box is the transposed source window (numpy's transpose is
+    the definition here), upright boxes are the window itself, everything else is zero."""
+    cfg, frames, mask, imp, pl = _rotating_case(orc)
+    halo, S, H, W = 4, 80, cfg.height, cfg.width
+    bins = orc.gather(frames, pl.boxes, halo, S, pl.n_bins)
+    covered = np.zeros(bins.shape[:3], dtype=bool)
+    for (f, x0, y0, w, h, rot, b, bx, by, bid) in pl.boxes.tolist():
+        bw, bh = 16 * w + 2 * halo, 16 * h + 2 * halo
+        src = np.zeros((bh, bw, 3), dtype=np.uint8)
+        ys = np.arange(16 * y0 - halo, 16 * y0 - halo + bh); xs = np.arange(16 * x0 - halo, 16 * x0 - halo + bw)
+        vy = (ys >= 0) & (ys < H); vx = (xs >= 0) & (xs < W)
+        src[np.ix_(vy, vx)] = frames[f][np.ix_(ys[vy], xs[vx])]
+        if rot:
+            src = src.transpose(1, 0, 2); bw, bh = bh, bw
+        assert np.array_equal(bins[b, by:by + bh, bx:bx + bw], src)
+        assert not covered[b, by:by + bh, bx:bx + bw].any()
+        covered[b, by:by + bh, bx:bx + bw] = True
+    assert np.all(bins[~covered] == 0)
+    for (g, box, b, px, py), rot in zip(pl.places.tolist(), pl.place_rot.tolist()):
+        f, rem = divmod(g, cfg.mbw * cfg.mbh); y, x = divmod(rem, cfg.mbw)
+        mb = frames[f, 16 * y:16 * y + 16, 16 * x:16 * x + 16]
+        assert np.array_equal(bins[b, py:py + 16, px:px + 16], mb.transpose(1, 0, 2) if rot else mb)
+
+
+def test_paste_turned_boxes_transposes_back(orc):
+    """The paste of a turned box reads the enhanced block transposed: with an 'enhancer' whose output
+    is a known function of the bin coordinates, every pasted value is checked against that function
+    at the exchanged coordinates, in numpy."""
+    cfg, frames, mask, imp, pl = _rotating_case(orc)
+    s, S = 2, 80
+    B = 16 * s
+    rng = np.random.default_rng(3)
+    net = rng.uniform(-0.2, 0.2, size=(pl.n_bins, S * s, S * s, 3))
+    hr, sel = orc.unpack(frames, s, net, pl.places, place_rot=pl.place_rot)
+    n_rot = 0
+    for i, ((g, box, b, px, py), rot) in enumerate(zip(pl.places.tolist(), pl.place_rot.tolist())):
+        f, rem = divmod(g, cfg.mbw * cfg.mbh); y, x = divmod(rem, cfg.mbw)
+        blk = net[b, py * s:py * s + B, px * s:px * s + B]
+        if rot:
+            blk = blk.transpose(1, 0, 2); n_rot += 1
+        base = orc.bilinear(frames[f], s)[y * B:(y + 1) * B, x * B:(x + 1) * B].astype(np.float64) / 255.0
+        e = np.clip(base + blk, 0, 1)
+        assert np.abs(sel[i] - e).max() < 1e-6
+        got = hr[f, y * B:(y + 1) * B, x * B:(x + 1) * B].astype(np.float64)
+        assert np.abs(got - np.floor(e * 255.0 + 0.5)).max() <= 1
+    assert n_rot > 0
+    # with nothing turned the same call ignores the flag array
+    hr0, _ = orc.unpack(frames, s, net, pl.places, place_rot=np.zeros(len(pl.places), dtype=np.int32))
+    hr1, _ = orc.unpack(frames, s, net, pl.places)
+    assert np.array_equal(hr0, hr1) and not np.array_equal(hr0, hr)

@@ -25,7 +25,7 @@ def owned_sets(plan, mask):
     return own
 
 
-def check_valid(plan, mask, imp, halo, S, T, conn):
+def check_valid(plan, mask, imp, halo, S, T, conn, sort_policy="density", rotate=False):
     """Everything that must hold for any correct run, checked by brute force."""
     F, mbh, mbw = mask.shape
     per = mbh * mbw
@@ -35,13 +35,15 @@ def check_valid(plan, mask, imp, halo, S, T, conn):
     rects = []
     for i, (f, x0, y0, w, h, rot, b, bx, by, bid) in enumerate(plan.boxes.tolist()):
         gs = sorted(own[i])
-        assert bid == gs[0] and rot == 0
+        assert bid == gs[0] and rot in ((0, 1) if rotate else (0,))
         xs = [g % mbw for g in gs]; ys = [(g % per) // mbw for g in gs]
         assert all(g // per == f for g in gs)
         assert (min(xs), min(ys), max(xs) - min(xs) + 1, max(ys) - min(ys) + 1) == (x0, y0, w, h)  # tight
         assert w <= T and h <= T
         assert len({lab[f][y, x] for x, y in zip(xs, ys)}) == 1             # one region per box
         bw, bh = 16 * w + 2 * halo, 16 * h + 2 * halo
+        if rot:
+            bw, bh = bh, bw                                                   # occupied size
         if b != 0xFFFF:
             assert 0 <= b < plan.n_bins and bx >= 0 and by >= 0 and bx + bw <= S and by + bh <= S
             rects.append((b, bx, by, bw, bh))
@@ -54,13 +56,17 @@ def check_valid(plan, mask, imp, halo, S, T, conn):
         s = np.float32(0)
         for g in sorted(own[i]):
             s = np.float32(s + imp.ravel()[g])
-        keys.append((-Fraction(float(s)) / (row[3] * row[4]), row[9]))
+        if sort_policy == "area":
+            keys.append((-row[3] * row[4], row[9]))
+        else:
+            keys.append((-Fraction(float(s)) / (row[3] * row[4]), row[9]))
     assert keys == sorted(keys)
     # placement rows
-    for g, box, b, px, py in plan.places.tolist():
+    for j, (g, box, b, px, py) in enumerate(plan.places.tolist()):
         f, x0, y0, w, h, rot, bb, bx, by, bid = plan.boxes[box].tolist()
-        assert b == bb
-        assert px == bx + halo + 16 * (g % mbw - x0) and py == by + halo + 16 * ((g % per) // mbw - y0)
+        assert b == bb and plan.place_rot[j] == rot
+        dx, dy = halo + 16 * (g % mbw - x0), halo + 16 * ((g % per) // mbw - y0)
+        assert (px, py) == ((bx + dy, by + dx) if rot else (bx + dx, by + dy))
     # MBs of one region that fall in the same T-cell of the region's bbox share a box
     for f in range(F):
         for r in range(1, lab[f].max() + 1):
@@ -74,18 +80,23 @@ def check_valid(plan, mask, imp, halo, S, T, conn):
             assert len(set(cell.values())) == len(cell)
 
 
-def simulate_first_fit(sizes, halo, S, max_bins=1 << 15):
+def simulate_first_fit(sizes, halo, S, max_bins=1 << 15, rotate=False):
     """Independent re-simulation of the placement rules from their prose statement."""
     m = 16 + 2 * halo
     free, out, nb = [], [], 0
     for (bw, bh) in sizes:
-        idx = next((i for i, r in enumerate(free) if r[3] >= bw and r[4] >= bh), None)
+        def fits(r):
+            return (r[3] >= bw and r[4] >= bh) or (rotate and r[3] >= bh and r[4] >= bw)
+        idx = next((i for i, r in enumerate(free) if fits(r)), None)
         if idx is None:
             if nb >= max_bins:
                 break
             free.append((nb, 0, 0, S, S)); idx = len(free) - 1; nb += 1
         b, x, y, w, h = free[idx]
-        out.append((b, x, y))
+        turned = not (w >= bw and h >= bh)
+        if turned:
+            bw, bh = bh, bw
+        out.append((b, x, y, int(turned)) if rotate else (b, x, y))
         if (w - bw) * h >= w * (h - bh):
             right, bottom = (b, x + bw, y, w - bw, h), (b, x, y + bh, bw, h - bh)
         else:
@@ -96,11 +107,18 @@ def simulate_first_fit(sizes, halo, S, max_bins=1 << 15):
     return out, nb, free
 
 
-def check_against_simulation(plan, halo, S, max_bins=1 << 15):
+def check_against_simulation(plan, halo, S, max_bins=1 << 15, rotate=False):
     sizes = [(16 * r[3] + 2 * halo, 16 * r[4] + 2 * halo) for r in plan.boxes.tolist()]
-    out, nb, free = simulate_first_fit(sizes, halo, S, max_bins)
-    got = [(r[6], r[7], r[8]) for r in plan.boxes.tolist() if r[6] != 0xFFFF]
+    out, nb, free = simulate_first_fit(sizes, halo, S, max_bins, rotate)
+    if rotate:
+        got = [(r[6], r[7], r[8], r[5]) for r in plan.boxes.tolist() if r[6] != 0xFFFF]
+        sizes = [(h, w) if o[3] else (w, h) for (w, h), o in zip(sizes, out)]     # occupied sizes
+        out3 = [o[:3] for o in out]
+    else:
+        got = [(r[6], r[7], r[8]) for r in plan.boxes.tolist() if r[6] != 0xFFFF]
+        out3 = out
     assert got == out and nb == plan.n_bins
+    out = out3
     # area conservation: free + placed + dropped slivers = n_bins * S^2  =>  free + placed <= total
     placed = sum(w * h for (w, h), _ in zip(sizes, out))
     assert placed + sum(r[3] * r[4] for r in free) <= nb * S * S
@@ -209,3 +227,54 @@ def test_benchmark_configs_plan_valid(orc, ci):
         check_valid(pl, mask, imp, cfg.halo, cfg.bin_size, T, 8)
     occ = 256 * len(lst) / (pl.n_bins * cfg.bin_size ** 2)
     assert 0.1 < occ <= 1.0
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_policy_options_valid_and_first_fit(orc, seed):
+    """Large-item-first order and RotatePacking (Alg. 1): same brute-force validity checks and the
+    independent re-simulation, with the option switched on on both sides."""
+    rng = np.random.default_rng(100 + seed)
+    F, mbh, mbw = 4, 7, 9
+    mask = (rng.random((F, mbh, mbw)) < [0.15, 0.3, 0.5, 0.7][seed % 4]).astype(np.uint8)
+    imp = rng.random((F, mbh, mbw)).astype(np.float32)
+    n_rot = 0
+    for conn, T, halo, S in [(8, 3, 4, 64), (4, 4, 3, 80), (8, 5, 6, 96), (8, 6, 10, 128)]:
+        for policy, rotate in (("area", False), ("density", True), ("area", True)):
+            pl = orc.plan(mask, imp, halo, S, conn, T, sort_policy=policy, rotate=rotate)
+            assert not pl.overflow
+            check_valid(pl, mask, imp, halo, S, T, conn, policy, rotate)
+            check_against_simulation(pl, halo, S, rotate=rotate)
+            n_rot += int(pl.boxes[:, 5].sum())
+    assert n_rot > 0                                    # the turned branch is exercised
+
+
+def test_rotate_hand_traced(orc):
+    """tests/golden/rotate_three_boxes.txt: a 40x24 box, a 40x40 box and another 40x24 box in a 64x64
+    bin with halo 4; the third only fits the 24x40 remainder when turned (traced by hand)."""
+    mask = np.zeros((3, 3, 3), dtype=np.uint8); imp = np.zeros((3, 3, 3), dtype=np.float32)
+    mask[0, 0, 0:2] = 1; imp[0, 0, 0:2] = 0.9
+    mask[1, 0:2, 0:2] = 1; imp[1, 0:2, 0:2] = 0.5
+    mask[2, 0, 0:2] = 1; imp[2, 0, 0:2] = 0.2
+    rows = [tuple(int(v) for v in ln.split()) for ln in open(os.path.join(GOLD, "rotate_three_boxes.txt"))
+            if ln.strip() and not ln.startswith("#")]
+    want_rot = [r[1:] for r in rows if r[0] == 1]       # (bin, bx, by, rot) per box, rotation on
+    want_off = [r[1:] for r in rows if r[0] == 0]
+    want_pl = [r[1:] for r in rows if r[0] == 2]        # (mb_id, px, py) of the turned box's MBs
+    pl = orc.plan(mask, imp, 4, 64, 8, 3, rotate=True)
+    assert [(r[6], r[7], r[8], r[5]) for r in pl.boxes.tolist()] == want_rot and pl.n_bins == 1
+    got = {g: (px, py) for g, box, b, px, py in pl.places.tolist()}
+    assert all(got[g] == (px, py) for g, px, py in want_pl)
+    pl0 = orc.plan(mask, imp, 4, 64, 8, 3, rotate=False)
+    assert [(r[6], r[7], r[8], r[5]) for r in pl0.boxes.tolist()] == want_off and pl0.n_bins == 2
+
+
+def test_area_policy_order_differs_from_density(orc):
+    """A large sparse box and a small dense one: density-first packs the small one first,
+    large-item-first the large one (the comparison of Sec. 3.3.2)."""
+    mask = np.zeros((1, 4, 8), dtype=np.uint8); imp = np.zeros((1, 4, 8), dtype=np.float32)
+    mask[0, 0, 0] = mask[0, 1, 1] = mask[0, 2, 2] = 1; imp[0, 0, 0] = imp[0, 1, 1] = imp[0, 2, 2] = 0.3   # 3x3 bbox
+    mask[0, 0, 6] = 1; imp[0, 0, 6] = 0.9
+    d = orc.plan(mask, imp, 4, 128, 8, 6)
+    a = orc.plan(mask, imp, 4, 128, 8, 6, sort_policy="area")
+    assert [r[3] * r[4] for r in d.boxes.tolist()] == [1, 9]
+    assert [r[3] * r[4] for r in a.boxes.tolist()] == [9, 1]
