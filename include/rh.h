@@ -47,6 +47,7 @@ typedef enum {
 enum { RH_FP32 = 0, RH_BF16 = 1 };                   /* rh_config.precision              */
 enum { RH_NET_PLAIN = 0, RH_NET_RES = 1, RH_NET_EDSR = 2 };
 enum { RH_TOPK = 0, RH_THRESHOLD = 1 };              /* rh_select_regions mode           */
+enum { RH_SORT_DENSITY = 0, RH_SORT_AREA = 1 };      /* rh_config.sort_policy            */
 
 /*
  * The SR network (Sec. 3.3.3 only says "pre-trained EDSR"; the topologies are this build's).
@@ -73,13 +74,25 @@ typedef struct {
     int32_t max_box_mbs;        /* Partition's preset size in MBs; 0 = (bin_size-2*halo)/16 */
     int32_t precision;          /* RH_FP32 | RH_BF16                                       */
     rh_net_desc net;
+    int32_t sort_policy;        /* packing order (Alg. 1, Sort): RH_SORT_DENSITY = importance
+                                   density first (the paper's), RH_SORT_AREA = the classic
+                                   large-item-first order it is compared with (Sec. 3.3.2);
+                                   ties: ascending box id                                   */
+    int32_t rotate;             /* 1: RotatePacking (Alg. 1): a free area also takes a box
+                                   turned by a quarter - stored with rows and columns
+                                   exchanged - when it does not fit upright.  A conv net is
+                                   not equivariant under that, so the enhanced pixels of a
+                                   turned box differ from the upright ones (the paper accepts
+                                   this); 0 keeps every box upright                         */
 } rh_config;
 
 /* One selection segment: frames [frame_begin, frame_end).  RH_TOPK uses k, RH_THRESHOLD thr. */
 typedef struct { uint32_t frame_begin, frame_end, k; float thr; } rh_segment;
 
 /* A placed box (Alg. 1): MB rectangle (mbx0, mby0, wmb, hmb) of frame `frame`, packed with its
- * halo at pixel (bx, by) of bin `bin`; id = smallest flat index of the MBs it owns; rot = 0.
+ * halo at pixel (bx, by) of bin `bin`; id = smallest flat index of the MBs it owns.
+ * rot = 1 (only with rh_config.rotate): the box is stored turned, bin pixel (bx + i, by + j) =
+ * box pixel (column j, row i), and occupies (16*hmb + 2*halo) x (16*wmb + 2*halo) pixels.
  * bin = 0xFFFF marks a box that did not fit within max_bins. */
 typedef struct {
     uint32_t frame;
@@ -89,8 +102,9 @@ typedef struct {
     uint32_t id;
 } rh_box;                                             /* 24 bytes */
 
-/* Where one selected MB lives: its 16x16 pixels start at (px, py) of bin `bin`. */
-typedef struct { uint32_t mb_id, box; uint16_t bin, px, py, pad; } rh_mbplace;   /* 16 bytes */
+/* Where one selected MB lives: its 16x16 pixels start at (px, py) of bin `bin`; rot = 1: they
+ * are stored with rows and columns exchanged (the MB belongs to a turned box). */
+typedef struct { uint32_t mb_id, box; uint16_t bin, px, py, rot; } rh_mbplace;   /* 16 bytes */
 
 /* Largest N with 256*N <= bin_h*bin_w*n_bins (Sec. 3.3.1, the MB budget). */
 uint32_t rh_budget(uint32_t bin_h, uint32_t bin_w, uint32_t n_bins);

@@ -25,7 +25,7 @@ BOX_DTYPE = np.dtype([("frame", "<u4"), ("mbx0", "<u2"), ("mby0", "<u2"), ("wmb"
                       ("rot", "u1"), ("pad0", "u1"), ("bin", "<u2"), ("bx", "<u2"), ("by", "<u2"),
                       ("pad1", "<u2"), ("id", "<u4")])
 PLACE_DTYPE = np.dtype([("mb_id", "<u4"), ("box", "<u4"), ("bin", "<u2"), ("px", "<u2"), ("py", "<u2"),
-                        ("pad", "<u2")])
+                        ("rot", "<u2")])
 assert BOX_DTYPE.itemsize == 24 and PLACE_DTYPE.itemsize == 16
 
 
@@ -36,7 +36,8 @@ class NetDesc(C.Structure):
 class Config(C.Structure):
     _fields_ = [("frame_w", C.c_int32), ("frame_h", C.c_int32), ("max_frames", C.c_int32), ("halo", C.c_int32),
                 ("bin_size", C.c_int32), ("max_bins", C.c_int32), ("connectivity", C.c_int32),
-                ("max_box_mbs", C.c_int32), ("precision", C.c_int32), ("net", NetDesc)]
+                ("max_box_mbs", C.c_int32), ("precision", C.c_int32), ("net", NetDesc),
+                ("sort_policy", C.c_int32), ("rotate", C.c_int32)]
 
 
 class Segment(C.Structure):
@@ -104,7 +105,8 @@ class RH:
     """One context = one configuration on the current device and torch stream."""
 
     def __init__(self, *, frame_w, frame_h, max_frames, halo, bin_size, max_bins, net, weights: np.ndarray,
-                 precision="bf16", connectivity=8, max_box_mbs=0, device="cuda:0", stream=None):
+                 precision="bf16", connectivity=8, max_box_mbs=0, sort_policy="density", rotate=False,
+                 device="cuda:0", stream=None):
         self.lib = load_library()
         if not torch.cuda.is_available():
             raise RuntimeError("paper_2407_16990_amd needs a GPU: there is no CPU fallback")
@@ -112,7 +114,8 @@ class RH:
         torch.cuda.set_device(self.device)
         self.cfg = Config(frame_w, frame_h, max_frames, halo, bin_size, max_bins, connectivity, max_box_mbs,
                           {"fp32": RH_FP32, "bf16": RH_BF16}[precision],
-                          NetDesc(TOPOLOGY[net.topology], net.channels, net.n_blocks, net.scale))
+                          NetDesc(TOPOLOGY[net.topology], net.channels, net.n_blocks, net.scale),
+                          {"density": 0, "area": 1}[sort_policy], int(bool(rotate)))
         self.scale = net.scale
         self.mbw, self.mbh = frame_w // 16, frame_h // 16
         w = np.ascontiguousarray(weights, dtype=np.float32)

@@ -11,7 +11,7 @@ __global__ __launch_bounds__(256) void k_bins_zero(uint4* __restrict__ bins, con
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) bins[i] = z;
 }
 
-// A work unit is an 8-row band of one box; workgroups stride over the units, each wave copies
+// A work unit is an 8-row band of one box (as stored in the bin); workgroups stride over the units, each wave copies
 // 2 rows, lanes run along the row's bytes (contiguous in both the frame and the bin).  Box
 // rectangles of one bin are disjoint, so no two units write the same byte.
 __global__ __launch_bounds__(256) void k_gather(const uint8_t* __restrict__ frames, const rh_box* __restrict__ boxes,
@@ -28,6 +28,22 @@ __global__ __launch_bounds__(256) void k_gather(const uint8_t* __restrict__ fram
         const int x_lo = max(0, -sx0) * 3, x_hi = min(bw, W - sx0) * 3;   // in-frame byte range of a row
         const uint8_t* src = frames + (size_t)b.frame * H * W * 3;
         uint8_t* dst = bins + ((size_t)b.bin * S + b.by) * S * 3 + (size_t)b.bx * 3;
+        if (b.rot) {
+            // turned box: bin row i holds box column i, so a row's bytes come from one source
+            // column (strided reads; turned boxes are the exception)
+#pragma unroll
+            for (int rr = 0; rr < 2; ++rr) {
+                const int i = (u % bands) * 8 + wave * 2 + rr;     // bin row = box column
+                if (i >= bw) continue;
+                const int sx = sx0 + i;
+                uint8_t* drow = dst + (size_t)i * S * 3;
+                for (int c = lane; c < bh * 3; c += 64) {
+                    const int j = c / 3, ch = c - 3 * j, sy = sy0 + j;
+                    drow[c] = (sx >= 0 && sx < W && sy >= 0 && sy < H) ? src[((size_t)sy * W + sx) * 3 + ch] : (uint8_t)0;
+                }
+            }
+            continue;
+        }
 #pragma unroll
         for (int rr = 0; rr < 2; ++rr) {
             const int j = (u % bands) * 8 + wave * 2 + rr;

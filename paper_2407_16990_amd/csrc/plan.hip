@@ -14,7 +14,7 @@ __global__ void k_plan_zero(uint32_t* pcount) { if (threadIdx.x < 8) pcount[thre
 // A region's label is the smallest in-frame index of its macroblocks.
 __global__ __launch_bounds__(256) void k_plan_label(const uint8_t* __restrict__ mask,
                                                     const float* __restrict__ imp, int mbw, int mbh,
-                                                    int conn, int T, uint32_t* __restrict__ owner_id,
+                                                    int conn, int T, int sort_policy, uint32_t* __restrict__ owner_id,
                                                     rh_rawbox* __restrict__ raw, uint32_t* pcount)
 {
     extern __shared__ uint32_t sm[];
@@ -95,13 +95,14 @@ __global__ __launch_bounds__(256) void k_plan_label(const uint8_t* __restrict__ 
             rh_rawbox b;
             b.frame = f; b.mbx0 = x0; b.mby0 = y0; b.wmb = x1 - x0 + 1; b.hmb = y1 - y0 + 1;
             b.id = (uint32_t)(base + i); b.sum = sum;
-            b.key = (double)sum / (double)((x1 - x0 + 1) * (y1 - y0 + 1));
+            const int area = (x1 - x0 + 1) * (y1 - y0 + 1);
+            b.key = sort_policy == RH_SORT_AREA ? (double)area : (double)sum / (double)area;
             raw[slot] = b;
         }
     }
 }
 
-// a before b in the packing order: higher density first, NaN last, ties by ascending id.
+// a before b in the packing order: higher key (density, or area) first, NaN last, ties by ascending id.
 __device__ __forceinline__ bool box_before(double ka, uint32_t ia, double kb, uint32_t ib)
 {
     const bool an = ka != ka, bn = kb != kb;
@@ -138,13 +139,14 @@ __global__ __launch_bounds__(256) void k_plan_rank(const rh_rawbox* __restrict__
 // First fit (Alg. 1 main loop) with the reading of InnerFree given in the header.
 // Free rectangle j: fxy[j] = x | y<<16, fwh[j] = w | h<<16, fbin[j].  Every thread tracks the
 // list length and bin count redundantly; only the list itself is shared.
-// box_pos[i] = {bin, bx | by<<16}; pcount[1] = n_bins, pcount[2] = overflow.
+// box_pos[i] = {bin | turned<<16, bx | by<<16}; pcount[1] = n_bins, pcount[2] = overflow.
+// rotate: a rectangle that cannot take the box upright may take it turned (RotatePacking).
 // Barrier that orders LDS traffic only (the placement loop also issues global stores whose
 // completion nobody in the loop waits for).
 __device__ __forceinline__ void lds_sync() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
 __global__ __launch_bounds__(256) void k_plan_place(const rh_rawbox* __restrict__ sorted, uint32_t* pcount,
-                                                    int halo, int S, int max_bins, int free_cap,
+                                                    int halo, int S, int max_bins, int free_cap, int rotate,
                                                     uint32_t* __restrict__ box_pos)
 {
     extern __shared__ uint32_t sm[];
@@ -166,10 +168,11 @@ __global__ __launch_bounds__(256) void k_plan_place(const rh_rawbox* __restrict_
         }
         lds_sync();
         const uint32_t sz = s_size[i & 255u];
-        const int bw = RH_MB * (int)(sz & 0xFFFF) + 2 * halo, bh = RH_MB * (int)(sz >> 16) + 2 * halo;
+        int bw = RH_MB * (int)(sz & 0xFFFF) + 2 * halo, bh = RH_MB * (int)(sz >> 16) + 2 * halo;
         for (int j = tid; j < nfree; j += NT) {
             const uint32_t wh = fwh[j];
-            if ((int)(wh & 0xFFFF) >= bw && (int)(wh >> 16) >= bh) { atomicMin(&s_at, (uint32_t)j); break; }
+            const int w = (int)(wh & 0xFFFF), h = (int)(wh >> 16);
+            if ((w >= bw && h >= bh) || (rotate && w >= bh && h >= bw)) { atomicMin(&s_at, (uint32_t)j); break; }
         }
         lds_sync();
         uint32_t at = s_at;
@@ -182,7 +185,9 @@ __global__ __launch_bounds__(256) void k_plan_place(const rh_rawbox* __restrict_
             cur_n = nfree;
             if (nfree + 1 > free_cap) { overflow = true; break; }
         }
-        if (tid == 0) { box_pos[2 * i] = fb; box_pos[2 * i + 1] = (uint32_t)fx | ((uint32_t)fy << 16); }
+        const bool turned = !(fw >= bw && fh >= bh);         // upright whenever that fits
+        if (turned) { const int t = bw; bw = bh; bh = t; }   // occupied size
+        if (tid == 0) { box_pos[2 * i] = (uint32_t)fb | (turned ? 0x10000u : 0u); box_pos[2 * i + 1] = (uint32_t)fx | ((uint32_t)fy << 16); }
         // remainder: the larger of (right strip, full height) and (bottom strip, full width),
         // plus what is left of the other
         const int ar = (fw - bw) * fh, ab = fw * (fh - bh);
@@ -246,7 +251,7 @@ __global__ __launch_bounds__(256) void k_plan_emit(const rh_rawbox* __restrict__
         const rh_rawbox b = sorted[i];
         rh_box o;
         o.frame = b.frame; o.mbx0 = b.mbx0; o.mby0 = b.mby0; o.wmb = (uint8_t)b.wmb; o.hmb = (uint8_t)b.hmb;
-        o.rot = 0; o.pad0 = 0; o.bin = (uint16_t)box_pos[2 * i];
+        o.rot = (uint8_t)((box_pos[2 * i] >> 16) & 1u); o.pad0 = 0; o.bin = (uint16_t)(box_pos[2 * i] & 0xFFFFu);
         o.bx = (uint16_t)(box_pos[2 * i + 1] & 0xFFFF); o.by = (uint16_t)(box_pos[2 * i + 1] >> 16);
         o.pad1 = 0; o.id = b.id;
         boxes[i] = o;
@@ -257,11 +262,13 @@ __global__ __launch_bounds__(256) void k_plan_emit(const rh_rawbox* __restrict__
         const uint32_t in = g % (uint32_t)per;
         const int y = in / mbw, x = in - y * mbw;
         rh_mbplace p;
-        p.mb_id = g; p.box = rk; p.bin = (uint16_t)box_pos[2 * rk];
-        const bool placed = box_pos[2 * rk] != RH_NO_BIN;
-        p.px = placed ? (uint16_t)((box_pos[2 * rk + 1] & 0xFFFF) + halo + RH_MB * (x - b.mbx0)) : 0;
-        p.py = placed ? (uint16_t)((box_pos[2 * rk + 1] >> 16) + halo + RH_MB * (y - b.mby0)) : 0;
-        p.pad = 0;
+        p.mb_id = g; p.box = rk; p.bin = (uint16_t)(box_pos[2 * rk] & 0xFFFFu);
+        const bool placed = p.bin != RH_NO_BIN;
+        const bool turned = (box_pos[2 * rk] >> 16) & 1u;
+        const int dx = halo + RH_MB * (x - b.mbx0), dy = halo + RH_MB * (y - b.mby0);
+        p.px = placed ? (uint16_t)((box_pos[2 * rk + 1] & 0xFFFF) + (turned ? dy : dx)) : 0;
+        p.py = placed ? (uint16_t)((box_pos[2 * rk + 1] >> 16) + (turned ? dx : dy)) : 0;
+        p.rot = turned ? 1 : 0;
         places[i] = p;
     }
 }
@@ -283,12 +290,13 @@ rh_status rh_launch_plan(rh_ctx* ctx, int F, const float* imp, const uint8_t* ma
     rh_prof_scope ps(ctx, RH_PROF_PLAN, 5);
     hipLaunchKernelGGL(k_plan_zero, dim3(1), dim3(64), 0, ctx->stream, ctx->pcount);
     hipLaunchKernelGGL(k_plan_label, dim3(F), dim3(256), (size_t)per * 16, ctx->stream, mask, imp, ctx->mbw,
-                       ctx->mbh, ctx->cfg.connectivity, ctx->T, ctx->owner_id, ctx->raw, ctx->pcount);
+                       ctx->mbh, ctx->cfg.connectivity, ctx->T, ctx->cfg.sort_policy, ctx->owner_id, ctx->raw, ctx->pcount);
     const int nblk = (total + 255) / 256;
     hipLaunchKernelGGL(k_plan_rank, dim3(nblk), dim3(256), 0, ctx->stream, ctx->raw, ctx->pcount, ctx->sorted,
                        ctx->rank_of_id);
     hipLaunchKernelGGL(k_plan_place, dim3(1), dim3(64), (size_t)ctx->free_cap * 12, ctx->stream, ctx->sorted,
-                       ctx->pcount, ctx->cfg.halo, ctx->cfg.bin_size, ctx->cfg.max_bins, ctx->free_cap, box_pos);
+                       ctx->pcount, ctx->cfg.halo, ctx->cfg.bin_size, ctx->cfg.max_bins, ctx->free_cap, ctx->cfg.rotate,
+                       box_pos);
     hipLaunchKernelGGL(k_plan_emit, dim3(nblk), dim3(256), 0, ctx->stream, ctx->sorted, box_pos, ctx->pcount,
                        list, n_sel, ctx->owner_id, ctx->rank_of_id, ctx->mbw, per, ctx->cfg.halo, boxes, places,
                        counts);

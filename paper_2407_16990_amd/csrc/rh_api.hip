@@ -73,6 +73,8 @@ extern "C" rh_status rh_create(const rh_config* cfg, const float* weights, size_
     if (cfg->halo < 0 || cfg->bin_size < 16 || cfg->bin_size % 4 || cfg->bin_size > 4096) return RH_E_SHAPE;
     if (RH_MB + 2 * cfg->halo > cfg->bin_size) return RH_E_SHAPE;
     if (cfg->connectivity != 4 && cfg->connectivity != 8) return RH_E_INVALID;
+    if (cfg->sort_policy != RH_SORT_DENSITY && cfg->sort_policy != RH_SORT_AREA) return RH_E_INVALID;
+    if (cfg->rotate != 0 && cfg->rotate != 1) return RH_E_INVALID;
     if (cfg->precision != RH_FP32 && cfg->precision != RH_BF16) return RH_E_INVALID;
     const int Tmax = (cfg->bin_size - 2 * cfg->halo) / RH_MB;
     if (cfg->max_box_mbs < 0 || cfg->max_box_mbs > Tmax || Tmax > 255) return RH_E_SHAPE;

@@ -27,7 +27,7 @@ __global__ __launch_bounds__(256) void k_identity_places(rh_mbplace* __restrict_
     if (g >= total) return;
     const uint32_t f = g / per, in = g % per;
     rh_mbplace p;
-    p.mb_id = g; p.box = f; p.bin = (uint16_t)f; p.px = (uint16_t)(RH_MB * (in % mbw)); p.py = (uint16_t)(RH_MB * (in / mbw)); p.pad = 0;
+    p.mb_id = g; p.box = f; p.bin = (uint16_t)f; p.px = (uint16_t)(RH_MB * (in % mbw)); p.py = (uint16_t)(RH_MB * (in / mbw)); p.rot = 0;
     places[g] = p;
 }
 
@@ -67,10 +67,15 @@ __global__ __launch_bounds__(256) void k_unpack(const uint8_t* __restrict__ lr, 
     const uint32_t g = ((uint32_t)f * mbh + my) * mbw + mx;
     const int slot = slot_of_mb[g];
     const float* net = nullptr;
+    bool turned = false;
     if (slot >= 0) {
         const rh_mbplace p = places[slot];
-        if (p.bin != RH_NO_BIN && p.bin < n_img && p.px + RH_MB <= iw && p.py + RH_MB <= ih)
-            net = enh + (((size_t)p.bin * (ih * S) + (size_t)p.py * S) * (iw * S) + (size_t)p.px * S + gx) * 3;
+        if (p.bin != RH_NO_BIN && p.bin < n_img && p.px + RH_MB <= iw && p.py + RH_MB <= ih) {
+            turned = p.rot != 0;
+            // upright: this lane's first pixel of row 0; turned: the block's first pixel (rows and
+            // columns are exchanged when reading)
+            net = enh + (((size_t)p.bin * (ih * S) + (size_t)p.py * S) * (iw * S) + (size_t)p.px * S + (turned ? 0 : gx)) * 3;
+        }
     }
     // horizontal taps of the 4 pixels: tile column and weight of the right neighbour
     int tx[4], wx1[4];
@@ -109,7 +114,13 @@ __global__ __launch_bounds__(256) void k_unpack(const uint8_t* __restrict__ lr, 
             if (net) {                                     // placed macroblock: one branch per row of 4 pixels
                 const float* nrow = net + (size_t)yy * (iw * S) * 3;
                 float nv[12];
-                if constexpr (S % 4 == 0) {                // 48-byte runs start 16-byte aligned
+                if (turned) {                              // output (yy, gx + p) <- block (gx + p, yy)
+#pragma unroll
+                    for (int p = 0; p < 4; ++p) {
+                        const float* t = net + ((size_t)(gx + p) * (iw * S) + yy) * 3;
+                        nv[3 * p] = t[0]; nv[3 * p + 1] = t[1]; nv[3 * p + 2] = t[2];
+                    }
+                } else if constexpr (S % 4 == 0) {         // 48-byte runs start 16-byte aligned
                     const float4 a0 = ((const float4*)nrow)[0], a1 = ((const float4*)nrow)[1], a2 = ((const float4*)nrow)[2];
                     nv[0] = a0.x; nv[1] = a0.y; nv[2] = a0.z; nv[3] = a0.w; nv[4] = a1.x; nv[5] = a1.y;
                     nv[6] = a1.z; nv[7] = a1.w; nv[8] = a2.x; nv[9] = a2.y; nv[10] = a2.z; nv[11] = a2.w;

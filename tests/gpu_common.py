@@ -37,14 +37,15 @@ def places_as_rows(p: np.ndarray) -> np.ndarray:
     return np.stack([p[k].astype(np.int64) for k in ("mb_id", "box", "bin", "px", "py")], axis=1)
 
 
-def check_select_and_plan(rh: RH, cfg, frames, imp, segs, mode="topk", thr=None, conn=8, T=None, max_bins=1 << 15):
+def check_select_and_plan(rh: RH, cfg, frames, imp, segs, mode="topk", thr=None, conn=8, T=None, max_bins=1 << 15,
+                          sort_policy="density", rotate=False):
     """Selection + plan + packed bytes, bit-exact.  Returns (oracle plan, gpu pack output, dev handles)."""
     seg_rows = [tuple(s) + ((float(thr[i]),) if thr is not None else ()) for i, s in enumerate(np.asarray(segs).tolist())]
     o_mask, o_list = oracle.select(imp, np.asarray(segs, dtype=np.uint32).reshape(-1, 3), mode, thr)
     g_mask, g_list, handles = gpu_select(rh, imp, seg_rows, mode)
     assert np.array_equal(g_mask, o_mask), "mask differs"
     assert np.array_equal(g_list, o_list), "list differs"
-    o_plan = oracle.plan(o_mask, imp, cfg.halo, cfg.bin_size, conn, T, max_bins)
+    o_plan = oracle.plan(o_mask, imp, cfg.halo, cfg.bin_size, conn, T, max_bins, sort_policy, rotate)
     d_frames, d_imp = dev(frames), dev(imp)
     po = rh.pack(d_frames, d_imp, *handles)
     counts = po.counts.cpu().numpy().astype(np.int64)
@@ -53,6 +54,7 @@ def check_select_and_plan(rh: RH, cfg, frames, imp, segs, mode="topk", thr=None,
     g_places = places_as_rows(RH.places_np(po.places, counts[3]))
     assert np.array_equal(g_boxes, o_plan.boxes.astype(np.int64)), "boxes differ"
     assert np.array_equal(g_places, o_plan.places.astype(np.int64)), "places differ"
+    assert np.array_equal(RH.places_np(po.places, counts[3])["rot"].astype(np.int64), o_plan.place_rot), "turned flags differ"
     o_bins = oracle.gather(frames, o_plan.boxes, cfg.halo, cfg.bin_size, o_plan.n_bins)
     g_bins = po.bins[: o_plan.n_bins].cpu().numpy()
     assert np.array_equal(g_bins, o_bins), "packed bytes differ"

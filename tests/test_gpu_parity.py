@@ -13,14 +13,18 @@ from gpu_common import check_select_and_plan, dev, gpu_select, make_rh, rel_l2
 pytestmark = pytest.mark.gpu
 
 
-def full_path_check(cfg, n_frames=None, precision=None, segs=None, max_bins=None):
+def full_path_check(cfg, n_frames=None, precision=None, segs=None, max_bins=None, sort_policy="density", rotate=False,
+                    expect_turned=False):
     F = cfg.n_frames if n_frames is None else n_frames
     precision = precision or cfg.precision
     frames, imp = wl.make_frames(cfg, F), wl.make_importance(cfg, F)
     segs = wl.make_segments(cfg, F) if segs is None else segs
     blob = wl.make_weights(cfg.net, cfg.weight_seed, precision)
-    rh = make_rh(cfg, blob, F, precision=precision, max_bins=max_bins)
-    o_plan, po, (d_frames, d_imp, o_bins) = check_select_and_plan(rh, cfg, frames, imp, segs)
+    rh = make_rh(cfg, blob, F, precision=precision, max_bins=max_bins, sort_policy=sort_policy, rotate=rotate)
+    o_plan, po, (d_frames, d_imp, o_bins) = check_select_and_plan(rh, cfg, frames, imp, segs, sort_policy=sort_policy,
+                                                                  rotate=rotate)
+    if expect_turned:
+        assert o_plan.boxes[:, 5].sum() > 0, "the case is meant to turn at least one box"
     s = cfg.net.scale
     # enhance: both the exact-N call and the device-count call
     g_net = rh.enhance(po.bins, n=o_plan.n_bins)
@@ -34,7 +38,7 @@ def full_path_check(cfg, n_frames=None, precision=None, segs=None, max_bins=None
     assert torch.equal(g_net, g_net2)
     # unpack
     hr, sel = rh.unpack(g_net, po.places, po.counts[3:4], d_frames, want_sel=True)
-    o_hr, o_sel = oracle.unpack(frames, s, o_net, o_plan.places)
+    o_hr, o_sel = oracle.unpack(frames, s, o_net, o_plan.places, place_rot=o_plan.place_rot)
     k = len(o_plan.places)
     g_sel = sel[:k].cpu().numpy()
     e_sel = rel_l2(g_sel, o_sel)
@@ -214,3 +218,43 @@ def test_frame_based_run_bf16_matches_oracle():
     assert rel_l2(sel.cpu().numpy(), o_sel) <= 1e-2 and np.abs(sel.cpu().numpy() - o_sel).max() <= 2 / 255
     assert np.abs(hr.cpu().numpy().astype(int) - o_hr.astype(int)).max() <= 2
     rh.close()
+
+
+# ---- packing policy options (Alg. 1: Sort order, RotatePacking) ---------------------------------
+
+@pytest.mark.parametrize("ci", [1, 3, 5])
+@pytest.mark.parametrize("sort_policy,rotate", [("area", False), ("density", True), ("area", True)])
+def test_policy_options_metadata_and_bytes_at_full_size(ci, sort_policy, rotate):
+    cfg = wl.config(ci)
+    frames, imp = wl.make_frames(cfg), wl.make_importance(cfg)
+    net = wl.Net("plain", 4, 2, cfg.net.scale)
+    blob = wl.make_weights(net, 0, "fp32")
+    rh = make_rh(wl.replace(cfg, net=net), blob, precision="fp32", sort_policy=sort_policy, rotate=rotate)
+    check_select_and_plan(rh, cfg, frames, imp, wl.make_segments(cfg), sort_policy=sort_policy, rotate=rotate)
+    rh.close()
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_rotate_random_masks_metadata_and_bytes(seed):
+    """Scattered selections in small bins: many boxes only fit turned."""
+    cfg = wl.replace(wl.config(1), n_frames=4, width=160, height=112, halo=3 + seed, bin_size=64 + 16 * (seed % 3),
+                     importance="uniform", frac=[0.2, 0.35, 0.5, 0.7][seed])
+    frames, imp = wl.make_frames(cfg), wl.make_importance(cfg)
+    net = wl.Net("plain", 4, 2, 2)
+    rh = make_rh(wl.replace(cfg, net=net), wl.make_weights(net, 0, "fp32"), precision="fp32", rotate=True,
+                 connectivity=4 if seed % 2 else 8)
+    o_plan, *_ = check_select_and_plan(rh, cfg, frames, imp, wl.make_segments(cfg), conn=4 if seed % 2 else 8, rotate=True)
+    assert o_plan.boxes[:, 5].sum() > 0
+    rh.close()
+
+
+def test_rotate_whole_path_fp32():
+    cfg = wl.replace(wl.config(1), n_frames=3, width=160, height=112, halo=4, bin_size=64, importance="uniform", frac=0.5)
+    full_path_check(cfg, rotate=True, expect_turned=True)
+
+
+@pytest.mark.parametrize("scale", [3, 4])
+def test_rotate_whole_path_bf16_edsr(scale):
+    cfg = wl.replace(wl.config(3), n_frames=2, width=160, height=112, halo=6, bin_size=96, importance="uniform", frac=0.4,
+                     net=wl.Net("edsr", 64, 2, scale, 0.02))
+    full_path_check(cfg, rotate=True, expect_turned=True)
