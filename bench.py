@@ -73,6 +73,10 @@ def main():
     ap.add_argument("--max-box-mbs", type=int, default=0,
                     help="Partition's preset size in macroblocks (0 = the largest that fits a bin; 1 = every "
                          "macroblock its own box, the paper's MB-packing / Block policy)")
+    ap.add_argument("--policy-study", type=int, default=0, metavar="N",
+                    help="occupy ratio (selected-MB pixels / packed pixels) of the packing policies over N random "
+                         "importance maps of the configuration: importance-density order (the paper's), the same "
+                         "with RotatePacking, large-item-first order, and one box per macroblock (MB packing)")
     ap.add_argument("--probe-mfma", action="store_true",
                     help="also run the register-only bf16 MFMA loop (all-ones and random operands) and report its "
                          "TFLOP/s and sustained clock next to the published peak")
@@ -226,6 +230,34 @@ def main():
             "pack_gather": {"bytes": xpb, "us": xprof["gather"][0] / reps * 1e3, "GB/s": xpb / (xprof["gather"][0] / reps * 1e-3) / 1e9},
             "unpack": {"bytes": xub, "us": xprof["unpack"][0] / reps * 1e3, "GB/s": xub / (xprof["unpack"][0] / reps * 1e-3) / 1e9}}
         del rhx, xf, xi, xhr, xnet, xpo
+
+    if args.policy_study > 0:
+        pols = {"density": dict(), "density+rotate": dict(rotate=True), "area": dict(sort_policy="area"),
+                "area+rotate": dict(sort_policy="area", rotate=True), "mb_packing": dict(max_box_mbs=1)}
+        ctxs = {k: RH(frame_w=cfg.width, frame_h=cfg.height, max_frames=F, halo=cfg.halo, bin_size=cfg.bin_size,
+                      max_bins=4 * max_bins, net=cfg.net, weights=blob, precision=cfg.precision, **kw)
+                for k, kw in pols.items()}
+        occ = {k: [] for k in pols}
+        plan_ms = {k: 0.0 for k in pols}
+        for it in range(args.policy_study):
+            ci = wl.replace(cfg, index=1000 + it)                     # another seed of the same recipe
+            x_imp = torch.from_numpy(wl.make_importance(ci)).cuda()
+            x_segs = [tuple(r) for r in wl.make_segments(ci).tolist()]
+            for k, c in ctxs.items():
+                c.profile_enable(True)
+                m_, l_, n_ = c.select_regions(x_imp, x_segs)
+                o_ = c.pack(d_frames, x_imp, m_, l_, n_)
+                cnt = c.read_counts(o_.counts)
+                plan_ms[k] += c.profile_read()["plan"][0]
+                occ[k].append(256.0 * cnt[3] / (cnt[1] * S * S) if cnt[1] else 0.0)
+        result["policy_study"] = {"n": args.policy_study, "bin_size": S, "halo": cfg.halo}
+        for k, v in occ.items():
+            a = np.asarray(v)
+            result["policy_study"][k] = {"occupy_mean": float(a.mean()), "occupy_p05": float(np.percentile(a, 5)),
+                                         "occupy_p10": float(np.percentile(a, 10)), "occupy_p50": float(np.percentile(a, 50)),
+                                         "plan_ms_mean": plan_ms[k] / args.policy_study}
+        for c in ctxs.values():
+            c.close()
 
     if args.probe_mfma:
         result["mfma_probe"] = {}
