@@ -258,3 +258,61 @@ def test_rotate_whole_path_bf16_edsr(scale):
     cfg = wl.replace(wl.config(3), n_frames=2, width=160, height=112, halo=6, bin_size=96, importance="uniform", frac=0.4,
                      net=wl.Net("edsr", 64, 2, scale, 0.02))
     full_path_check(cfg, rotate=True, expect_turned=True)
+
+
+# ---- full benchmark sizes, in the launch configuration bench.py times --------------------------
+
+@pytest.mark.parametrize("ci,sample", [(3, 3), (5, 2)])
+def test_full_size_bf16_sampled_bins(ci, sample):
+    """The whole batch of configurations 3 and 5 through the path exactly as bench.py drives it
+    (capacity-sized enhance call with the device-side bin count).  Metadata and packed bytes are
+    compared in full; the network output and the pasted pixels on a sample of bins the oracle can
+    afford (first, last, and one in the middle), every unselected macroblock against the bilinear
+    base, and bins past the count must stay untouched."""
+    cfg = wl.config(ci)
+    F, s, S = cfg.n_frames, cfg.net.scale, cfg.bin_size
+    frames, imp, segs = wl.make_frames(cfg), wl.make_importance(cfg), wl.make_segments(cfg)
+    blob = wl.make_weights(cfg.net, cfg.weight_seed, cfg.precision)
+    max_bins = 512 if ci == 5 else 256
+    rh = make_rh(cfg, blob, max_bins=max_bins)
+    o_plan, po, (d_frames, d_imp, o_bins) = check_select_and_plan(rh, cfg, frames, imp, segs, max_bins=max_bins)
+    nb = o_plan.n_bins
+    net_out = torch.full((nb + 1, S * s, S * s, 3), 7.0, dtype=torch.float32, device="cuda")
+    # capacity (nb + 1 images) above the device-side count (nb): the last image must not be touched
+    rh.enhance(po.bins[: nb + 1], n=nb + 1, n_valid=po.counts[1:2], out=net_out)
+    assert bool((net_out[nb] == 7.0).all()), "an image past the device-side count was written"
+    hr, sel = rh.unpack(net_out, po.places, po.counts[3:4], d_frames, want_sel=True)
+    pick = sorted({0, nb // 2, nb - 1})[:sample]
+    o_net = oracle.sr_forward(cfg.net, blob, o_bins[pick])
+    g_net = net_out[pick].cpu().numpy()
+    e = rel_l2(g_net, o_net)
+    print(f"[{cfg.name}] {nb} bins, sampled {pick}: net rel-L2={e:.3e}", flush=True)
+    assert e <= 1e-2
+    # pasted pixels of the macroblocks that live in the sampled bins
+    B = 16 * s
+    g_sel = sel.cpu().numpy()
+    per = cfg.mbw * cfg.mbh
+    worst, n_chk = 0.0, 0
+    base_cache = {}
+    for i, (g, box, b, px, py) in enumerate(o_plan.places.tolist()):
+        if b not in pick:
+            continue
+        f, rem = divmod(g, per); y, x = divmod(rem, cfg.mbw)
+        if f not in base_cache:
+            base_cache[f] = oracle.bilinear(frames[f], s)
+        base = base_cache[f][y * B:(y + 1) * B, x * B:(x + 1) * B].astype(np.float32) / np.float32(255.0)
+        blk = o_net[pick.index(b), py * s:py * s + B, px * s:px * s + B].astype(np.float32)
+        want = np.clip(base + blk, 0.0, 1.0)
+        worst = max(worst, float(np.abs(g_sel[i] - want).max())); n_chk += 1
+    print(f"[{cfg.name}] {n_chk} pasted macroblocks checked, max abs={worst:.3e}", flush=True)
+    assert n_chk > 0 and worst <= 2.0 / 255.0
+    # every unselected macroblock of every frame is the bilinear base, byte for byte
+    g_hr = hr.cpu().numpy()
+    o_mask = oracle.select(imp, segs)[0]
+    for f in range(F):
+        base = base_cache.get(f)
+        if base is None:
+            base = oracle.bilinear(frames[f], s)
+        keep = ~np.kron(o_mask[f], np.ones((B, B), dtype=np.uint8)).astype(bool)
+        assert np.array_equal(g_hr[f][keep], base[keep])
+    rh.close()
