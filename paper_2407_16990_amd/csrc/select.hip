@@ -47,12 +47,25 @@ __global__ __launch_bounds__(1024) void k_select_kth(const float* __restrict__ i
                                                      uint32_t* __restrict__ frame_ties)
 {
     __shared__ uint32_t hist[256];
+    __shared__ uint32_t s_wtot[4];
     __shared__ uint32_t s_prefix, s_remaining;
     __shared__ uint32_t s_gt[FCHUNK], s_eq[FCHUNK], s_scan[2][FCHUNK];
     const int tid = threadIdx.x, seg = blockIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
     const uint32_t g0 = seg_par[4 * seg], g1 = seg_par[4 * seg + 1];
     const uint32_t n = g1 - g0;
+    const uint32_t f0 = g0 / per, f1 = g1 / per;
     uint32_t k = seg_par[4 * seg + 2];
+    // a queue that fits is read once and stays in registers for the radix passes and the counts
+    const bool in_regs = n <= KREG * 1024u && f1 - f0 <= FCHUNK;
+    uint32_t keys[KREG];
+    if (in_regs) {
+#pragma unroll
+        for (int j = 0; j < KREG; ++j) {
+            const uint32_t i = (uint32_t)j * 1024u + tid;
+            keys[j] = i < n ? imp_key(imp[g0 + i]) : 0u;
+        }
+    }
     uint32_t T, budget;
     if (mode == RH_THRESHOLD) {
         float thr = __uint_as_float(seg_par[4 * seg + 3]);
@@ -62,15 +75,6 @@ __global__ __launch_bounds__(1024) void k_select_kth(const float* __restrict__ i
         if (k > n) k = n;
         if (k == 0) { T = 0xFFFFFFFFu; budget = 0u; }            // no key reaches 0xFFFFFFFF
         else {
-            const bool in_regs = n <= KREG * 1024u;
-            uint32_t keys[KREG];
-            if (in_regs) {
-#pragma unroll
-                for (int j = 0; j < KREG; ++j) {
-                    const uint32_t i = (uint32_t)j * 1024u + tid;
-                    keys[j] = i < n ? imp_key(imp[g0 + i]) : 0u;
-                }
-            }
             uint32_t prefix = 0, remaining = k;
             for (int pass = 3; pass >= 0; --pass) {
                 const int shift = pass * 8;
@@ -92,53 +96,80 @@ __global__ __launch_bounds__(1024) void k_select_kth(const float* __restrict__ i
                     }
                 }
                 __syncthreads();
-                if (tid < 256) {                               // bin t holds the k-th key iff  above(t) < remaining <= above(t) + hist[t]
-                    uint32_t above = 0;
-                    for (int b = tid + 1; b < 256; ++b) above += hist[b];
-                    const uint32_t h = hist[tid];
+                // bin t holds the k-th key iff  above(t) < remaining <= above(t) + hist[t],  above(t) = sum of
+                // the bins over t: a suffix scan by shuffles inside each of the 4 waves that hold the bins
+                uint32_t h = 0, suf = 0;
+                if (tid < 256) {
+                    h = hist[tid]; suf = h;
+#pragma unroll
+                    for (int o = 1; o < 64; o <<= 1) { const uint32_t t = __shfl_down(suf, o); if (lane + o < 64) suf += t; }
+                    if (lane == 0) s_wtot[wave] = suf;
+                }
+                __syncthreads();
+                if (tid < 256) {
+                    uint32_t above = suf - h;
+                    for (int w = wave + 1; w < 4; ++w) above += s_wtot[w];
                     if (above < remaining && remaining <= above + h) { s_prefix = prefix | ((uint32_t)tid << shift); s_remaining = remaining - above; }
                 }
                 __syncthreads();
                 prefix = s_prefix; remaining = s_remaining;
-                __syncthreads();
             }
             T = prefix; budget = remaining;
         }
     }
     if (tid == 0) seg_T[seg] = T;
-    // per-frame counts: one wave per frame; the ties are then dealt to the frames in ascending
-    // order, so a frame may take  min(eq, budget - ties of the frames before it)
-    const uint32_t f0 = g0 / per, f1 = g1 / per;
-    const int lane = tid & 63, wave = tid >> 6;
+    // per-frame counts of keys above T (gt) and equal to T (eq); the ties are then dealt to the
+    // frames in ascending order: a frame may take  min(eq, budget - ties of the frames before it)
     uint32_t left = budget;                                    // uniform over the workgroup
     for (uint32_t c0 = f0; c0 < f1; c0 += FCHUNK) {
         const uint32_t nf = (f1 - c0) < FCHUNK ? (f1 - c0) : FCHUNK;
-        for (uint32_t j = wave; j < nf; j += 16) {
-            const size_t fb = (size_t)(c0 + j) * per;
-            uint32_t gt = 0, eq = 0;
-            for (int i = lane; i < per; i += 64) {
-                const uint32_t key = imp_key(imp[fb + i]);
-                gt += key > T; eq += key == T;
+        if (in_regs) {                                         // one chunk: counts straight from the registers
+            if ((uint32_t)tid < nf) { s_gt[tid] = 0; s_eq[tid] = 0; }
+            __syncthreads();
+#pragma unroll
+            for (int j = 0; j < KREG; ++j) {
+                if ((uint32_t)j * 1024u >= n) continue;            // uniform over the workgroup
+                const uint32_t i = (uint32_t)j * 1024u + tid;
+                const bool gt = i < n && keys[j] > T, eq = i < n && keys[j] == T;
+                const uint32_t fr = i / (uint32_t)per;             // frame within the segment
+                bool todo = gt || eq;
+                while (__any(todo)) {                              // one round per frame present in the wave
+                    const int first = __ffsll((long long)__ballot(todo)) - 1;
+                    const uint32_t fs = __shfl(fr, first);
+                    const bool same = todo && fr == fs;
+                    const uint32_t ng = (uint32_t)__popcll(__ballot(same && gt)), ne = (uint32_t)__popcll(__ballot(same && eq));
+                    if (lane == first) { if (ng) atomicAdd(&s_gt[fs], ng); if (ne) atomicAdd(&s_eq[fs], ne); }
+                    todo = todo && !same;
+                }
             }
-            for (int o = 32; o > 0; o >>= 1) { gt += __shfl_xor(gt, o); eq += __shfl_xor(eq, o); }
-            if (lane == 0) { s_gt[j] = gt; s_eq[j] = eq; }
+        } else {                                               // one wave per frame, from global memory
+            for (uint32_t j = wave; j < nf; j += 16) {
+                const size_t fb = (size_t)(c0 + j) * per;
+                uint32_t gt = 0, eq = 0;
+                for (int i = lane; i < per; i += 64) {
+                    const uint32_t key = imp_key(imp[fb + i]);
+                    gt += key > T; eq += key == T;
+                }
+                for (int o = 32; o > 0; o >>= 1) { gt += __shfl_xor(gt, o); eq += __shfl_xor(eq, o); }
+                if (lane == 0) { s_gt[j] = gt; s_eq[j] = eq; }
+            }
         }
         __syncthreads();
-        // inclusive scan of eq over the chunk (saturating: sums only matter up to `left`)
+        // inclusive scan of eq over the chunk
         int cur = 0;
         if ((uint32_t)tid < nf) s_scan[0][tid] = s_eq[tid];
         __syncthreads();
         for (uint32_t d = 1; d < nf; d <<= 1) {
             if ((uint32_t)tid < nf) {
                 uint32_t v = s_scan[cur][tid];
-                if ((uint32_t)tid >= d) { const uint32_t u = s_scan[cur][tid - d]; v = (v + u < v) ? 0xFFFFFFFFu : v + u; }
+                if ((uint32_t)tid >= d) v += s_scan[cur][tid - d];    // at most n < 2^32 in total: no overflow
                 s_scan[cur ^ 1][tid] = v;
             }
             cur ^= 1;
             __syncthreads();
         }
         if ((uint32_t)tid < nf) {
-            const uint32_t eq = s_eq[tid], before = s_scan[cur][tid] - eq;   // exclusive (exact unless saturated, then >= left anyway)
+            const uint32_t eq = s_eq[tid], before = s_scan[cur][tid] - eq;
             const uint32_t room = before < left ? left - before : 0u;
             const uint32_t ties = eq < room ? eq : room;
             frame_nsel[c0 + tid] = s_gt[tid] + ties; frame_ties[c0 + tid] = ties;
