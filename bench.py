@@ -69,6 +69,8 @@ def main():
                     help="override the selected fraction of the configuration (the fraction sweep of configuration 4)")
     ap.add_argument("--importance", choices=["clustered", "uniform"], default=None,
                     help="override the importance recipe (uniform = iid, isolated macroblocks: the packer's worst case)")
+    ap.add_argument("--exact-border", action="store_true",
+                    help="enhance with rh_enhance_exact (per-layer zeroing of the out-of-frame part of the boxes)")
     ap.add_argument("--bin-size", type=int, default=None, help="override the bin side S (pixels)")
     ap.add_argument("--max-box-mbs", type=int, default=0,
                     help="Partition's preset size in macroblocks (0 = the largest that fits a bin; 1 = every "
@@ -107,6 +109,8 @@ def main():
         cfg = wl.replace(cfg, bin_size=args.bin_size, name=f"{cfg.name}_S{args.bin_size}")
     if args.max_box_mbs:
         cfg = wl.replace(cfg, name=f"{cfg.name}_T{args.max_box_mbs}")
+    if args.exact_border:
+        cfg = wl.replace(cfg, name=f"{cfg.name}_exact_border")
     F, s = cfg.n_frames, cfg.net.scale
     frames, imp, segs = wl.make_frames(cfg), wl.make_importance(cfg), wl.make_segments(cfg)
     blob = wl.make_weights(cfg.net, cfg.weight_seed, cfg.precision)
@@ -128,7 +132,9 @@ def main():
         nonlocal po
         mask, lst, n_sel = rh.select_regions(d_imp, seg_rows)
         po = rh.pack(d_frames, d_imp, mask, lst, n_sel, out=po)
-        if args.sync_counts:
+        if args.exact_border:
+            rh.enhance_exact(po.bins, po.boxes, po.counts, n=max_bins, n_valid=po.counts[1:2], out=net_out)
+        elif args.sync_counts:
             rh.enhance(po.bins, n=rh.read_counts(po.counts)[1], out=net_out)
         else:
             rh.enhance(po.bins, n=max_bins, n_valid=po.counts[1:2], out=net_out)   # device-side bin count

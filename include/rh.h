@@ -165,6 +165,20 @@ rh_status rh_enhance(rh_ctx* ctx, const uint8_t* in, int32_t N, int32_t H, int32
                      float* out, const uint32_t* n_valid);
 
 /*
+ * Exact-border variant of rh_enhance for packed bins (in: dev u8 [N][S][S][3], S = bin_size).
+ * rh_enhance pads every layer with zeros at the *bin* border only, so a box whose halo leaves the
+ * frame carries non-zero activations where a whole-frame run has padding, and macroblocks within
+ * the receptive field of a frame border differ from the frame-based result.  Here, after every
+ * layer but the last, the activations of every placed box are set to zero where the box's source
+ * pixels lie outside the frame (at that layer's resolution): with halo >= the network's
+ * receptive-field radius the packed result then equals the frame-based one at every selected
+ * macroblock, border ones included.  boxes / counts: dev, as written by rh_pack for these bins
+ * (turned boxes are handled).  Costs one small extra launch per layer.
+ */
+rh_status rh_enhance_exact(rh_ctx* ctx, const uint8_t* in, int32_t N, const rh_box* boxes,
+                           const uint32_t* counts, float* out, const uint32_t* n_valid);
+
+/*
  * Paste (Sec. 3.3.3; problem statement of Sec. 3.2.1: SR on selected MBs, bilinear IN(.)
  * elsewhere).  frames_hr u8 [F][s*H][s*W][3] = bilinear interpolation of frames_lr (integer
  * factor s, half-pixel centres, edge clamp, exact integer arithmetic, round half up); every

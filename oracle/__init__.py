@@ -133,15 +133,27 @@ def pixel_shuffle(x: np.ndarray, r: int) -> np.ndarray:
     return out
 
 
-def sr_forward(net, blob: np.ndarray, imgs: np.ndarray) -> np.ndarray:
-    """imgs u8 [N,H,W,3] -> raw network output fp64 [N,sH,sW,3]."""
+def border_keep(frame_h: int, frame_w: int, boxes: np.ndarray, halo: int, bin_size: int, n_bins: int) -> np.ndarray:
+    """Exact-border mode: u8 [n_bins,S,S], 0 at box pixels whose source lies outside the frame."""
+    boxes = np.ascontiguousarray(boxes, dtype=np.int32).reshape(-1, 10)
+    keep = np.ones((n_bins, bin_size, bin_size), dtype=np.uint8)
+    lib().orc_border_keep(frame_h, frame_w, _p(boxes), len(boxes), halo, bin_size, n_bins, _p(keep))
+    return keep
+
+
+def sr_forward(net, blob: np.ndarray, imgs: np.ndarray, keep: np.ndarray | None = None) -> np.ndarray:
+    """imgs u8 [N,H,W,3] -> raw network output fp64 [N,sH,sW,3].  keep (u8 [N,H,W], optional):
+    exact-border mode, every layer's output is zeroed where keep == 0."""
     imgs = np.ascontiguousarray(imgs, dtype=np.uint8)
     blob = np.ascontiguousarray(blob, dtype=np.float32)
     N, H, W, _ = imgs.shape
     s = net.scale
     out = np.zeros((N, H * s, W * s, 3), dtype=np.float64)
+    if keep is not None:
+        keep = np.ascontiguousarray(keep, dtype=np.uint8)
+        assert keep.shape == (N, H, W)
     lib().orc_sr_forward(TOPOLOGY[net.topology], net.channels, net.n_blocks, s, _p(blob),
-                         _p(imgs), N, H, W, _p(out))
+                         _p(imgs), N, H, W, _p(keep) if keep is not None else None, _p(out))
     return out
 
 
@@ -185,11 +197,13 @@ class PathResult:
 
 
 def run_path(frames, imp, segs, net, blob, halo, bin_size, conn=8, T=None,
-             mode="topk", thr=None, max_bins=1 << 15, sort_policy="density", rotate=False) -> PathResult:
+             mode="topk", thr=None, max_bins=1 << 15, sort_policy="density", rotate=False,
+             exact_border=False) -> PathResult:
     """The whole hot path: select -> plan -> gather -> SR -> paste."""
     mask, lst = select(imp, segs, mode, thr)
     pl = plan(mask, imp, halo, bin_size, conn, T, max_bins, sort_policy, rotate)
     bins = gather(frames, pl.boxes, halo, bin_size, pl.n_bins)
-    net_out = sr_forward(net, blob, bins)
+    keep = border_keep(frames.shape[1], frames.shape[2], pl.boxes, halo, bin_size, pl.n_bins) if exact_border else None
+    net_out = sr_forward(net, blob, bins, keep)
     hr, sel = unpack(frames, net.scale, net_out, pl.places, place_rot=pl.place_rot)
     return PathResult(mask, lst, pl, bins, net_out, hr, sel)

@@ -393,10 +393,23 @@ static const float* take_layer(const float** p, int cin, int cout, olayer* L)
 
 static double* dalloc(size_t n) { return (double*)malloc(sizeof(double) * (n ? n : 1)); }
 
+/* Exact-border mode: keep (u8 [H][W], may be NULL) is 0 at the pixels of the image that lie
+ * outside the source frame (halo of a box that leaves the frame).  Every layer's output is set
+ * to zero there, at that layer's resolution (rr x the input's), so that the next convolution
+ * sees what per-layer zero padding at the frame border gives in a whole-frame run. */
+static void apply_keep(double* buf, int h, int w, int C, const uint8_t* keep, int rr)
+{
+    if (!keep) return;
+    int W0 = w / rr;
+    for (int y = 0; y < h; ++y) for (int x = 0; x < w; ++x)
+        if (!keep[(size_t)(y / rr) * W0 + x / rr])
+            for (int c = 0; c < C; ++c) buf[((size_t)y * w + x) * C + c] = 0.0;
+}
+
 /* One image through the network.  topology: 0 plain, 1 res, 2 edsr.
  * in: u8 [H][W][3]; out: fp64 [sH][sW][3] (the network's raw output). */
 static void sr_one(int topology, int C, int nblk, int s, const float* blob,
-                   const uint8_t* in, int H, int W, double* out)
+                   const uint8_t* in, int H, int W, const uint8_t* keep, double* out)
 {
     size_t px = (size_t)H * W;
     const float* p = blob; olayer L;
@@ -405,8 +418,10 @@ static void sr_one(int topology, int C, int nblk, int s, const float* blob,
     double* a = dalloc(px * C); double* t = dalloc(px * C);
     if (topology == 0) {
         take_layer(&p, 3, C, &L); orc_conv3x3(x, H, W, 3, L.w, L.b, C, 1, a);
+        apply_keep(a, H, W, C, keep, 1);
         for (int l = 0; l < nblk - 2; ++l) {
             take_layer(&p, C, C, &L); orc_conv3x3(a, H, W, C, L.w, L.b, C, 1, t);
+            apply_keep(t, H, W, C, keep, 1);
             double* sw = a; a = t; t = sw;
         }
         int Co = 3 * s * s; double* y = dalloc(px * Co);
@@ -414,13 +429,16 @@ static void sr_one(int topology, int C, int nblk, int s, const float* blob,
         orc_pixel_shuffle(y, H, W, Co, s, out); free(y);
     } else {
         take_layer(&p, 3, C, &L); orc_conv3x3(x, H, W, 3, L.w, L.b, C, 0, a);
+        apply_keep(a, H, W, C, keep, 1);
         double* head = NULL;
         if (topology == 2) { head = dalloc(px * C); memcpy(head, a, sizeof(double) * px * C); }
         double* u = dalloc(px * C);
         for (int blk = 0; blk < nblk; ++blk) {          /* x <- x + conv(relu(conv(x))) */
             take_layer(&p, C, C, &L); orc_conv3x3(a, H, W, C, L.w, L.b, C, 1, t);
+            apply_keep(t, H, W, C, keep, 1);
             take_layer(&p, C, C, &L); orc_conv3x3(t, H, W, C, L.w, L.b, C, 0, u);
             for (size_t i = 0; i < px * C; ++i) a[i] = a[i] + u[i];
+            apply_keep(a, H, W, C, keep, 1);
         }
         if (topology == 1) {
             int Co = 3 * s * s; double* y = dalloc(px * Co);
@@ -429,6 +447,7 @@ static void sr_one(int topology, int C, int nblk, int s, const float* blob,
         } else {
             take_layer(&p, C, C, &L); orc_conv3x3(a, H, W, C, L.w, L.b, C, 0, u);
             for (size_t i = 0; i < px * C; ++i) u[i] = u[i] + head[i];   /* long skip */
+            apply_keep(u, H, W, C, keep, 1);
             int h = H, w = W; double* cur = u; u = NULL;
             int stages = (s == 4) ? 2 : 1, r = (s == 4) ? 2 : s;
             for (int st = 0; st < stages; ++st) {
@@ -437,6 +456,7 @@ static void sr_one(int topology, int C, int nblk, int s, const float* blob,
                 double* z = dalloc((size_t)h * w * Co);
                 orc_pixel_shuffle(y, h, w, Co, r, z); free(y); free(cur);
                 cur = z; h *= r; w *= r;
+                apply_keep(cur, h, w, C, keep, h / H);
             }
             take_layer(&p, C, 3, &L); orc_conv3x3(cur, h, w, C, L.w, L.b, 3, 0, out);
             free(cur);
@@ -446,14 +466,37 @@ static void sr_one(int topology, int C, int nblk, int s, const float* blob,
     free(x); free(a); free(t);
 }
 
-/* Batch of N images, each u8 [H][W][3] -> fp64 [sH][sW][3]. */
+/* Batch of N images, each u8 [H][W][3] -> fp64 [sH][sW][3].  keep: NULL, or u8 [N][H][W] for the
+ * exact-border mode (see apply_keep). */
 void orc_sr_forward(int topology, int C, int nblk, int s, const float* blob,
-                    const uint8_t* in, int N, int H, int W, double* out)
+                    const uint8_t* in, int N, int H, int W, const uint8_t* keep, double* out)
 {
     size_t ipx = (size_t)H * W * 3, opx = ipx * s * s;
 #pragma omp parallel for schedule(dynamic, 1)
     for (int n = 0; n < N; ++n)
-        sr_one(topology, C, nblk, s, blob, in + n * ipx, H, W, out + n * opx);
+        sr_one(topology, C, nblk, s, blob, in + n * ipx, H, W, keep ? keep + (size_t)n * H * W : NULL, out + n * opx);
+}
+
+/* Exact-border mode: keep[b][y][x] = 0 where bin pixel (x, y) belongs to a placed box and its
+ * source pixel lies outside the frame, 1 everywhere else. */
+void orc_border_keep(int H, int W, const int32_t* boxes, int n_boxes, int halo, int bin_size, int n_bins,
+                     uint8_t* keep)
+{
+    size_t S = (size_t)bin_size;
+    memset(keep, 1, (size_t)n_bins * S * S);
+    for (int i = 0; i < n_boxes; ++i) {
+        const int32_t* b = boxes + 10 * i;
+        int bin = b[6];
+        if (bin < 0 || bin >= n_bins) continue;
+        int bw = MBS * b[3] + 2 * halo, bh = MBS * b[4] + 2 * halo;
+        int sx0 = MBS * b[1] - halo, sy0 = MBS * b[2] - halo;
+        for (int j = 0; j < bh; ++j) for (int k = 0; k < bw; ++k) {
+            int sy = sy0 + j, sx = sx0 + k;
+            if (sy >= 0 && sy < H && sx >= 0 && sx < W) continue;
+            int row = b[5] ? k : j, col = b[5] ? j : k;
+            keep[((size_t)bin * S + (b[8] + row)) * S + (b[7] + col)] = 0;
+        }
+    }
 }
 
 /* ------------------------------------------------------------------------ */

@@ -83,30 +83,33 @@ rh_status rh_launch_enhance_fp32(rh_ctx* ctx, const uint8_t* in, int N, int H, i
     float* a = (float*)ctx->act; float* t = a + lr; float* h = t + lr; float* u1 = h + lr; float* u2 = u1 + up1;
     const std::vector<rh_layer>& L = ctx->layers;
     size_t li = 0;
+    // exact-border mode (a no-op otherwise): clear the out-of-frame part of the boxes in a layer's output
+#define ZERO(buf, res) do { st = rh_zero_outside(ctx, (buf), C * (int)sizeof(float), (res), N, n_valid); if (st != RH_OK) return st; } while (0)
     if (d.topology == RH_NET_PLAIN) {
-        conv(ctx, L[li++], in, 1, a, nullptr, N, H, W, 1, 1, n_valid);
-        for (int l = 0; l < d.n_blocks - 2; ++l) { conv(ctx, L[li++], a, 0, t, nullptr, N, H, W, 1, 1, n_valid); float* sw = a; a = t; t = sw; }
+        conv(ctx, L[li++], in, 1, a, nullptr, N, H, W, 1, 1, n_valid); ZERO(a, 1);
+        for (int l = 0; l < d.n_blocks - 2; ++l) { conv(ctx, L[li++], a, 0, t, nullptr, N, H, W, 1, 1, n_valid); ZERO(t, 1); float* sw = a; a = t; t = sw; }
         conv(ctx, L[li++], a, 0, out, nullptr, N, H, W, 0, s, n_valid);
     } else {
-        conv(ctx, L[li++], in, 1, h, nullptr, N, H, W, 0, 1, n_valid);
+        conv(ctx, L[li++], in, 1, h, nullptr, N, H, W, 0, 1, n_valid); ZERO(h, 1);
         const float* x = h;                         // block input; the head output stays in h for EDSR
         for (int b = 0; b < d.n_blocks; ++b) {
-            conv(ctx, L[li++], x, 0, t, nullptr, N, H, W, 1, 1, n_valid);
+            conv(ctx, L[li++], x, 0, t, nullptr, N, H, W, 1, 1, n_valid); ZERO(t, 1);
             // x + conv(t): for the first block the result goes to a so that h survives
-            conv(ctx, L[li++], t, 0, a, x, N, H, W, 0, 1, n_valid);
+            conv(ctx, L[li++], t, 0, a, x, N, H, W, 0, 1, n_valid); ZERO(a, 1);
             x = a;
         }
         if (d.topology == RH_NET_RES) {
             conv(ctx, L[li++], x, 0, out, nullptr, N, H, W, 0, s, n_valid);
         } else {
-            conv(ctx, L[li++], x, 0, t, h, N, H, W, 0, 1, n_valid);          // body end + long skip
+            conv(ctx, L[li++], x, 0, t, h, N, H, W, 0, 1, n_valid); ZERO(t, 1);         // body end + long skip
             const int r = (s == 4) ? 2 : s;
-            conv(ctx, L[li++], t, 0, u1, nullptr, N, H, W, 0, r, n_valid);
+            conv(ctx, L[li++], t, 0, u1, nullptr, N, H, W, 0, r, n_valid); ZERO(u1, r);
             const float* last = u1; int hh = H * r, ww = W * r;
-            if (s == 4) { conv(ctx, L[li++], u1, 0, u2, nullptr, N, hh, ww, 0, 2, n_valid); last = u2; hh *= 2; ww *= 2; }
+            if (s == 4) { conv(ctx, L[li++], u1, 0, u2, nullptr, N, hh, ww, 0, 2, n_valid); ZERO(u2, 2 * r); last = u2; hh *= 2; ww *= 2; }
             conv(ctx, L[li++], last, 0, out, nullptr, N, hh, ww, 0, 1, n_valid);
         }
     }
+#undef ZERO
     RH_HIP(ctx, hipGetLastError());
     return RH_OK;
 }

@@ -570,6 +570,9 @@ rh_status rh_launch_enhance_bf16(rh_ctx* ctx, const uint8_t* in, int N, int H, i
         if (C == 64) hipLaunchKernelGGL(k_head_bf16<64>, dim3(grid), dim3(256), 0, ctx->stream, in, hw, hb, h, N, H, W, head_relu, n_valid);
         else hipLaunchKernelGGL(k_head_bf16<32>, dim3(grid), dim3(256), 0, ctx->stream, in, hw, hb, h, N, H, W, head_relu, n_valid);
     }
+    // exact-border mode (a no-op otherwise): clear the out-of-frame part of the boxes in a layer's output
+#define ZERO(buf, res) do { st = rh_zero_outside(ctx, (void*)(buf), C * 2, (res), N, n_valid); if (st != RH_OK) return st; } while (0)
+    ZERO(h, 1);
     // one event pair around the run of bf16-output convs (they are launched back to back) and
     // one around the last conv: per-launch events would put a bubble between the launches
     uint32_t n_conv = 0;
@@ -578,28 +581,29 @@ rh_status rh_launch_enhance_bf16(rh_ctx* ctx, const uint8_t* in, int N, int H, i
 #define LAST_CONV(...) do { rh_prof_end(ctx, n_conv); rh_prof_scope ps_(ctx, RH_PROF_CONV_LAST); st = conv(ctx, __VA_ARGS__); if (st != RH_OK) return st; } while (0)
     if (d.topology == RH_NET_PLAIN) {
         const __bf16* x = h;
-        for (int l = 0; l < d.n_blocks - 2; ++l) { __bf16* o = (x == a) ? t : a; CONV(L[li++], x, o, nullptr, N, H, W, 1, false, 1, n_valid); x = o; }
+        for (int l = 0; l < d.n_blocks - 2; ++l) { __bf16* o = (x == a) ? t : a; CONV(L[li++], x, o, nullptr, N, H, W, 1, false, 1, n_valid); ZERO(o, 1); x = o; }
         LAST_CONV(L[li++], x, out, nullptr, N, H, W, 0, true, s, n_valid);
     } else {
         const __bf16* x = h;
         for (int b = 0; b < d.n_blocks; ++b) {
-            CONV(L[li++], x, t, nullptr, N, H, W, 1, false, 1, n_valid);
-            CONV(L[li++], t, a, x, N, H, W, 0, false, 1, n_valid);       // x + conv(t)
+            CONV(L[li++], x, t, nullptr, N, H, W, 1, false, 1, n_valid); ZERO(t, 1);
+            CONV(L[li++], t, a, x, N, H, W, 0, false, 1, n_valid); ZERO(a, 1);      // x + conv(t)
             x = a;
         }
         if (d.topology == RH_NET_RES) {
             LAST_CONV(L[li++], x, out, nullptr, N, H, W, 0, true, s, n_valid);
         } else {
-            CONV(L[li++], x, t, h, N, H, W, 0, false, 1, n_valid);        // body end + long skip
+            CONV(L[li++], x, t, h, N, H, W, 0, false, 1, n_valid); ZERO(t, 1);       // body end + long skip
             const int r = (s == 4) ? 2 : s;
-            CONV(L[li++], t, u1, nullptr, N, H, W, 0, false, 1, n_valid);
+            CONV(L[li++], t, u1, nullptr, N, H, W, 0, false, 1, n_valid); ZERO(u1, r);
             const __bf16* lastin = u1; int hh = H * r, ww = W * r;
-            if (s == 4) { CONV(L[li++], u1, u2, nullptr, N, hh, ww, 0, false, 1, n_valid); lastin = u2; hh *= 2; ww *= 2; }
+            if (s == 4) { CONV(L[li++], u1, u2, nullptr, N, hh, ww, 0, false, 1, n_valid); ZERO(u2, 2 * r); lastin = u2; hh *= 2; ww *= 2; }
             LAST_CONV(L[li++], lastin, out, nullptr, N, hh, ww, 0, true, 1, n_valid);
         }
     }
 #undef CONV
 #undef LAST_CONV
+#undef ZERO
     RH_HIP(ctx, hipGetLastError());
     return RH_OK;
 }

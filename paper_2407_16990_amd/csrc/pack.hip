@@ -57,6 +57,60 @@ __global__ __launch_bounds__(256) void k_gather(const uint8_t* __restrict__ fram
     }
 }
 
+// Exact-border mode.  Sets to zero, in an activation tensor [N][S*res][S*res] of px_bytes-byte
+// pixels, the part of every placed box whose source pixels lie outside the frame.  Unit = 8-row
+// band of a box as stored in the bin; a wave takes 2 stored rows.  Per stored row the outside
+// part is the whole row (the source row - or, for a turned box, column - is outside) or a run at
+// each end; the runs are cleared with 16-byte stores (px_bytes is a multiple of 16).
+__global__ __launch_bounds__(256) void k_zero_outside(uint8_t* __restrict__ act, int px_bytes, int res,
+                                                      const rh_box* __restrict__ boxes, const uint32_t* __restrict__ counts,
+                                                      int n_img, const uint32_t* __restrict__ n_valid, int H, int W,
+                                                      int halo, int S, int bands)
+{
+    const uint32_t n_units = counts[0] * (uint32_t)bands;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int nv = n_valid ? min((int)*n_valid, n_img) : n_img;
+    const size_t row_pitch = (size_t)S * res * px_bytes;
+    for (uint32_t u = blockIdx.x; u < n_units; u += gridDim.x) {
+        const rh_box b = boxes[u / bands];
+        if (b.bin == RH_NO_BIN || (int)b.bin >= nv) continue;
+        const int bw = RH_MB * b.wmb + 2 * halo, bh = RH_MB * b.hmb + 2 * halo;
+        const int sx0 = RH_MB * b.mbx0 - halo, sy0 = RH_MB * b.mby0 - halo;
+        if (sx0 >= 0 && sy0 >= 0 && sx0 + bw <= W && sy0 + bh <= H) continue;      // box entirely inside the frame
+        // stored rows run along the box's rows (upright) or columns (turned)
+        const int n_rows = b.rot ? bw : bh, n_cols = b.rot ? bh : bw;
+        if (b.bx + n_cols > S || b.by + n_rows > S) continue;                      // not a box of this geometry: never write outside the bin
+        const int r0 = b.rot ? sx0 : sy0, rlim = b.rot ? W : H;                    // source coordinate of stored row 0, its limit
+        const int c0s = b.rot ? sy0 : sx0, clim = b.rot ? H : W;                   // same for stored columns
+        const int lo_end = min(n_cols, max(0, -c0s)), hi_beg = max(0, min(n_cols, clim - c0s));
+#pragma unroll
+        for (int rr = 0; rr < 2; ++rr) {
+            const int j = (u % bands) * 8 + wave * 2 + rr;
+            if (j >= n_rows) continue;
+            const bool row_out = r0 + j < 0 || r0 + j >= rlim;
+            // runs of stored columns to clear: [0, e0) and [b1, n_cols)
+            const int e0 = row_out ? n_cols : lo_end, b1 = row_out ? n_cols : hi_beg;
+            for (int dy = 0; dy < res; ++dy) {
+                uint8_t* row = act + ((size_t)b.bin * S * res + (size_t)(b.by + j) * res + dy) * row_pitch + (size_t)b.bx * res * px_bytes;
+                const int n0 = e0 * res * px_bytes / 16, s1 = b1 * res * px_bytes / 16, n1 = n_cols * res * px_bytes / 16;
+                for (int c = lane; c < n0; c += 64) ((uint4*)row)[c] = make_uint4(0, 0, 0, 0);
+                for (int c = s1 + lane; c < n1; c += 64) ((uint4*)row)[c] = make_uint4(0, 0, 0, 0);
+            }
+        }
+    }
+}
+
+rh_status rh_zero_outside(rh_ctx* ctx, void* act, int px_bytes, int res, int N, const uint32_t* n_valid)
+{
+    if (!ctx->bz_boxes) return RH_OK;
+    if (px_bytes % 16) RH_FAIL(ctx, RH_E_UNIMPLEMENTED, "exact-border mode needs pixels of a multiple of 16 bytes, got %d", px_bytes);
+    const int bands = (RH_MB * ctx->T + 2 * ctx->cfg.halo + 7) / 8;
+    hipLaunchKernelGGL(k_zero_outside, dim3(2048), dim3(256), 0, ctx->stream, (uint8_t*)act, px_bytes, res, ctx->bz_boxes,
+                       ctx->bz_counts, N, n_valid, ctx->cfg.frame_h, ctx->cfg.frame_w, ctx->cfg.halo, ctx->cfg.bin_size, bands);
+    RH_HIP(ctx, hipGetLastError());
+    return RH_OK;
+}
+
 rh_status rh_launch_gather(rh_ctx* ctx, const uint8_t* frames, int F, const rh_box* boxes,
                            const uint32_t* counts, uint8_t* bins)
 {

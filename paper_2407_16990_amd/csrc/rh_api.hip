@@ -226,6 +226,20 @@ extern "C" rh_status rh_enhance(rh_ctx* ctx, const uint8_t* in, int32_t N, int32
                                          : rh_launch_enhance_fp32(ctx, in, N, H, W, out, n_valid);
 }
 
+extern "C" rh_status rh_enhance_exact(rh_ctx* ctx, const uint8_t* in, int32_t N, const rh_box* boxes,
+                                      const uint32_t* counts, float* out, const uint32_t* n_valid)
+{
+    if (!ctx) return RH_E_INVALID;
+    if (!in || !out || !boxes || !counts) RH_FAIL(ctx, RH_E_INVALID, "rh_enhance_exact: null argument");
+    if (N < 1 || N > 65535) RH_FAIL(ctx, RH_E_SHAPE, "rh_enhance_exact: bad N=%d", N);
+    const int S = ctx->cfg.bin_size;
+    ctx->bz_boxes = boxes; ctx->bz_counts = counts;
+    const rh_status st = ctx->cfg.precision == RH_BF16 ? rh_launch_enhance_bf16(ctx, in, N, S, S, out, n_valid)
+                                                       : rh_launch_enhance_fp32(ctx, in, N, S, S, out, n_valid);
+    ctx->bz_boxes = nullptr; ctx->bz_counts = nullptr;
+    return st;
+}
+
 extern "C" rh_status rh_unpack(rh_ctx* ctx, const float* enhanced, int32_t n_img, int32_t ih, int32_t iw,
                                const rh_mbplace* places, const uint32_t* n_places, const uint8_t* frames_lr,
                                int32_t F, uint8_t* frames_hr, float* sel)

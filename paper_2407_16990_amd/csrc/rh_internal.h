@@ -68,6 +68,10 @@ struct rh_ctx {
     uint32_t* pcount;       // [8] plan counters: 0 n_raw boxes
     // unpack scratch
     int32_t* slot_of_mb;    // [total MBs] index into places or -1
+    // exact-border mode: the boxes of the bins being enhanced (set for the duration of one
+    // rh_enhance_exact call, null otherwise)
+    const rh_box* bz_boxes;
+    const uint32_t* bz_counts;
     // enhance workspace (grow-only)
     void* act;
     size_t act_bytes;
@@ -105,6 +109,9 @@ rh_status rh_launch_identity_places(rh_ctx*, int F, rh_mbplace* places, uint32_t
 rh_status rh_pack_weights_bf16(rh_ctx*, const float* host_blob);
 rh_status rh_upload_segments(rh_ctx*, const rh_segment* segs, int nseg, int F);
 rh_status rh_plan_init(rh_ctx*);
+// exact-border mode: zero the out-of-frame part of every box in an activation tensor
+// [N][S*res][S*res][px_bytes]; a no-op unless an rh_enhance_exact call is in progress
+rh_status rh_zero_outside(rh_ctx*, void* act, int px_bytes, int res, int N, const uint32_t* n_valid);
 void rh_fill_i32(rh_ctx*, int32_t* p, int32_t v, size_t n);
 rh_status rh_ensure_workspace(rh_ctx*, size_t bytes);
 

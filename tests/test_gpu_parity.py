@@ -316,3 +316,55 @@ def test_full_size_bf16_sampled_bins(ci, sample):
         keep = ~np.kron(o_mask[f], np.ones((B, B), dtype=np.uint8)).astype(bool)
         assert np.array_equal(g_hr[f][keep], base[keep])
     rh.close()
+
+
+# ---- exact-border mode ---------------------------------------------------------------------------
+
+def exact_border_check(cfg, precision, rotate=False, border_bias=True):
+    F, s = cfg.n_frames, cfg.net.scale
+    frames, imp, segs = wl.make_frames(cfg), wl.make_importance(cfg), wl.make_segments(cfg)
+    if border_bias:                                           # pull border macroblocks into the selection
+        imp[:, 0, :] += 5.0; imp[:, :, 0] += 5.0; imp[:, -1, -3:] += 5.0
+    blob = wl.make_weights(cfg.net, cfg.weight_seed, precision)
+    rh = make_rh(cfg, blob, precision=precision, rotate=rotate)
+    o_plan, po, (d_frames, d_imp, o_bins) = check_select_and_plan(rh, cfg, frames, imp, segs, rotate=rotate)
+    keep = oracle.border_keep(cfg.height, cfg.width, o_plan.boxes, cfg.halo, cfg.bin_size, o_plan.n_bins)
+    assert (keep == 0).sum() > 0
+    o_net = oracle.sr_forward(cfg.net, blob, o_bins, keep)
+    o_plain = oracle.sr_forward(cfg.net, blob, o_bins)
+    g_net = rh.enhance_exact(po.bins, po.boxes, po.counts, n=o_plan.n_bins, n_valid=po.counts[1:2]).cpu().numpy()
+    tol = 1e-5 if precision == "fp32" else 1e-2
+    e, e_plain = rel_l2(g_net, o_net), rel_l2(g_net, o_plain)
+    print(f"[{cfg.name}/{precision}] exact-border net rel-L2={e:.3e} (against the plain mode: {e_plain:.3e})", flush=True)
+    assert e <= tol and e_plain > 3 * e
+    # the plain call is unchanged by the exact one having run
+    g_plain = rh.enhance(po.bins, n=o_plan.n_bins).cpu().numpy()
+    assert rel_l2(g_plain, o_plain) <= tol
+    rh.close()
+    return g_net, o_plan, frames, blob
+
+
+def test_exact_border_fp32_equals_frame_based_at_border_macroblocks():
+    """fp32, halo = receptive-field radius: the GPU's exact-border output equals the GPU-independent
+    whole-frame oracle run at every selected macroblock, border ones included."""
+    cfg = wl.config(1)
+    g_net, o_plan, frames, blob = exact_border_check(cfg, "fp32")
+    s, B = cfg.net.scale, 16 * cfg.net.scale
+    full = oracle.sr_forward(cfg.net, blob, frames)[0]
+    worst = 0.0
+    for g, box, b, px, py in o_plan.places.tolist():
+        y, x = divmod(g, cfg.mbw)
+        worst = max(worst, float(np.abs(g_net[b, py * s:py * s + B, px * s:px * s + B] - full[y * B:(y + 1) * B, x * B:(x + 1) * B]).max()))
+    assert worst <= 1e-5, worst
+
+
+@pytest.mark.parametrize("net", [wl.Net("edsr", 8, 2, 4, 0.05), wl.Net("res", 8, 2, 2, 0.05), wl.Net("edsr", 12, 1, 3, 0.05)])
+def test_exact_border_fp32_topologies_with_turned_boxes(net):
+    cfg = wl.replace(wl.config(1), net=net, n_frames=3, width=160, height=112, halo=4, bin_size=64, importance="uniform", frac=0.5)
+    exact_border_check(cfg, "fp32", rotate=True)
+
+
+@pytest.mark.parametrize("net", [wl.Net("edsr", 64, 2, 4, 0.02), wl.Net("edsr", 64, 1, 3, 0.02), wl.Net("res", 32, 2, 2, 0.03)])
+def test_exact_border_bf16(net):
+    cfg = wl.replace(wl.config(3), n_frames=2, width=160, height=112, halo=6, bin_size=96, net=net)
+    exact_border_check(cfg, "bf16")

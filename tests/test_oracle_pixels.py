@@ -323,3 +323,42 @@ def test_paste_turned_boxes_transposes_back(orc):
     hr0, _ = orc.unpack(frames, s, net, pl.places, place_rot=np.zeros(len(pl.places), dtype=np.int32))
     hr1, _ = orc.unpack(frames, s, net, pl.places)
     assert np.array_equal(hr0, hr1) and not np.array_equal(hr0, hr)
+
+
+@pytest.mark.parametrize("topo", ["plain", "edsr"])
+def test_exact_border_mode_equals_frame_based_everywhere(orc, topo):
+    """Exact-border mode: with halo >= receptive-field radius the packed path equals plain
+    frame-based SR of the frame at EVERY selected macroblock, border ones included (the plain
+    mode only does so for interior ones); the whole-frame forward pass is the definition."""
+    if topo == "plain":
+        cfg, R = wl.config(1), 4                              # 4 convs
+    else:
+        cfg = wl.replace(wl.config(1), net=wl.Net("edsr", 6, 1, 2, 0.1), halo=6)
+        R = 6                                                  # head, 2 block convs, body end, upsampler, tail(at x2: 1/2 px)
+    frames, imp = wl.make_frames(cfg), wl.make_importance(cfg)
+    imp[0, 0, :] += 5.0; imp[0, :, 0] += 5.0; imp[0, -1, -3:] += 5.0          # force border MBs into the selection
+    blob = wl.make_weights(cfg.net, cfg.weight_seed, "fp32")
+    segs = wl.make_segments(cfg)
+    s, B = cfg.net.scale, 16 * cfg.net.scale
+    full_plain = orc.sr_forward(cfg.net, blob, frames)[0]
+    r = orc.run_path(frames, imp, segs, cfg.net, blob, cfg.halo, cfg.bin_size, exact_border=True)
+    r0 = orc.run_path(frames, imp, segs, cfg.net, blob, cfg.halo, cfg.bin_size)
+    n_border = n_fixed = 0
+    for g, box, b, px, py in r.plan.places.tolist():
+        y, x = divmod(g, cfg.mbw)
+        want = full_plain[y * B:(y + 1) * B, x * B:(x + 1) * B]
+        assert np.array_equal(r.net_out[b, py * s:py * s + B, px * s:px * s + B], want)
+        if y in (0, cfg.mbh - 1) or x in (0, cfg.mbw - 1):
+            n_border += 1
+            n_fixed += not np.array_equal(r0.net_out[b, py * s:py * s + B, px * s:px * s + B], want)
+    assert n_border >= 20 and n_fixed >= 10               # the plain mode really differs there
+    # the mask itself: zero exactly on the out-of-frame part of the boxes
+    keep = orc.border_keep(cfg.height, cfg.width, r.plan.boxes, cfg.halo, cfg.bin_size, r.plan.n_bins)
+    zeros = 0
+    for (f, x0, y0, w, h, rot, b, bx, by, bid) in r.plan.boxes.tolist():
+        bw, bh = 16 * w + 2 * cfg.halo, 16 * h + 2 * cfg.halo
+        ys = np.arange(16 * y0 - cfg.halo, 16 * y0 - cfg.halo + bh); xs = np.arange(16 * x0 - cfg.halo, 16 * x0 - cfg.halo + bw)
+        inside = ((ys >= 0) & (ys < cfg.height))[:, None] & ((xs >= 0) & (xs < cfg.width))[None, :]
+        assert np.array_equal(keep[b, by:by + bh, bx:bx + bw].astype(bool), inside)
+        zeros += int((~inside).sum())
+    assert int((keep == 0).sum()) == zeros > 0
