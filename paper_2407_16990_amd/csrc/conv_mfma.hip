@@ -369,52 +369,6 @@ __global__ __launch_bounds__(256, MINB) void k_conv_mfma(conv_args a)
     }
 }
 
-// First conv of the network: 3 input channels read from the u8 image (x/255 rounded to bf16),
-// C output channels, on the vector ALUs (K = 27 is too short for the matrix cores to matter).
-// Thread = one pixel; the weights are uniform over the workgroup (scalar loads).
-template <int C>
-__global__ __launch_bounds__(256) void k_head_bf16(const uint8_t* __restrict__ in, const float* __restrict__ w /*[C][27] bf16-exact*/,
-                                                   const float* __restrict__ bias, __bf16* __restrict__ out, int N, int H,
-                                                   int W, int relu, const uint32_t* __restrict__ n_valid)
-{
-    const int n_img = n_valid ? min((int)*n_valid, N) : N;
-    const size_t total = (size_t)n_img * H * W;
-    for (size_t p = (size_t)blockIdx.x * 256 + threadIdx.x; p < total; p += (size_t)gridDim.x * 256) {
-        const int x = p % W, y = (p / W) % H;
-        const size_t nb = p - (size_t)y * W - x;       // n*H*W
-        float v[27];
-#pragma unroll
-        for (int ky = 0; ky < 3; ++ky)
-#pragma unroll
-            for (int kx = 0; kx < 3; ++kx) {
-                const int yy = y + ky - 1, xx = x + kx - 1;
-                const bool ok = yy >= 0 && yy < H && xx >= 0 && xx < W;
-#pragma unroll
-                for (int c = 0; c < 3; ++c) {
-                    float f = ok ? __fdiv_rn((float)in[(nb + (size_t)yy * W + xx) * 3 + c], 255.0f) : 0.0f;
-                    uint32_t u = pack_bf16x2(f, 0.0f);
-                    v[(ky * 3 + kx) * 3 + c] = bf16_lo(u);
-                }
-            }
-        uint32_t* o = (uint32_t*)(out + p * C);
-#pragma unroll 1
-        for (int c0 = 0; c0 < C; c0 += 8) {
-            float acc[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                acc[j] = bias[c0 + j];
-#pragma unroll
-                for (int k = 0; k < 27; ++k) acc[j] = fmaf(w[(c0 + j) * 27 + k], v[k], acc[j]);
-                if (relu) acc[j] = fmaxf(acc[j], 0.0f);
-            }
-            uint4 pk;
-            pk.x = pack_bf16x2(acc[0], acc[1]); pk.y = pack_bf16x2(acc[2], acc[3]);
-            pk.z = pack_bf16x2(acc[4], acc[5]); pk.w = pack_bf16x2(acc[6], acc[7]);
-            *(uint4*)(o + c0 / 2) = pk;
-        }
-    }
-}
-
 // ------------------------------------------------------------------------------------------
 // host side
 
@@ -439,14 +393,15 @@ rh_status rh_pack_weights_bf16(rh_ctx* ctx, const float* blob)
         rh_layer& L = ctx->layers[li];
         L.wp_off = wp.size() * 2; L.bp_off = bp.size();
         const float* w = blob + L.w_off; const float* b = blob + L.b_off;
-        if (L.cin == 3) {                      // head: [C][27] fp32 (values bf16-rounded)
+        if (L.cin == 3) {                      // head: [ky][m][lane][8], row = cout, k = 8*(lane/32) + e = kx*3 + c (>= 9: zero)
             L.cout_pad = L.cout; L.ps = 1;
-            // stored in bpack: weights then bias
-            for (int co = 0; co < L.cout; ++co)
-                for (int k = 0; k < 27; ++k) {
-                    uint32_t u = (uint32_t)f32_to_bf16_rne(w[(size_t)co * 27 + k]) << 16; float f; memcpy(&f, &u, 4);
-                    bp.push_back(f);
-                }
+            for (int ky = 0; ky < 3; ++ky)
+                for (int m = 0; m < L.cout / 32; ++m)
+                    for (int lane = 0; lane < 64; ++lane)
+                        for (int e = 0; e < 8; ++e) {
+                            const int co = m * 32 + (lane & 31), j = 8 * (lane >> 5) + e;
+                            wp.push_back(f32_to_bf16_rne(j < 9 ? w[((size_t)co * 3 + ky) * 9 + j] : 0.0f));
+                        }
             for (int co = 0; co < L.cout; ++co) bp.push_back(b[co]);
             continue;
         }
@@ -563,12 +518,9 @@ rh_status rh_launch_enhance_bf16(rh_ctx* ctx, const uint8_t* in, int N, int H, i
     const int head_relu = d.topology == RH_NET_PLAIN;
     {
         const rh_layer& l0 = L[li++];
-        const float* hw = ctx->bpack + l0.bp_off; const float* hb = hw + (size_t)C * 27;
-        const size_t px = (size_t)N * H * W;
-        const int grid = (int)((px + 255) / 256 < 4096 ? (px + 255) / 256 : 4096);
         rh_prof_scope ps(ctx, RH_PROF_HEAD);
-        if (C == 64) hipLaunchKernelGGL(k_head_bf16<64>, dim3(grid), dim3(256), 0, ctx->stream, in, hw, hb, h, N, H, W, head_relu, n_valid);
-        else hipLaunchKernelGGL(k_head_bf16<32>, dim3(grid), dim3(256), 0, ctx->stream, in, hw, hb, h, N, H, W, head_relu, n_valid);
+        RH_HIP(ctx, rh_launch_head_mfma(ctx->stream, C, in, (const uint4*)((const uint8_t*)ctx->wpack + l0.wp_off),
+                                        ctx->bpack + l0.bp_off, h, N, H, W, head_relu, n_valid));
     }
     // exact-border mode (a no-op otherwise): clear the out-of-frame part of the boxes in a layer's output
 #define ZERO(buf, res) do { st = rh_zero_outside(ctx, (void*)(buf), C * 2, (res), N, n_valid); if (st != RH_OK) return st; } while (0)
