@@ -135,19 +135,28 @@ __global__ __launch_bounds__(512) void k_conv_mfma_duo(conv_args a)
 
     for (int chunk = 0; chunk < a.n_chunks; ++chunk) {
         __syncthreads();                                   // all 8 waves: previous chunk completely done
-        {
+        {   // the chunk's weights and the first patch of both teams: all loads are issued before
+            // the first LDS store waits for any of them
+            constexpr int NWL = WBYTES / 16 / 512;         // 16-byte weight pieces per thread
+            static_assert(NWL * 512 * 16 == WBYTES, "weights must split evenly over the workgroup");
             const uint4* src = a.wp + (size_t)chunk * (WBYTES / 16);
-            for (int i = tid; i < WBYTES / 16; i += 512) ((uint4*)lds_w)[i] = src[i];
-        }
-        if (tid < CQ) lds_b[tid] = a.bias[chunk * CQ + tid];
-        const int si = chunk / ps, sj = chunk - si * ps;
-        {   // first patch of both teams
             int n, y0, x0; tile_origin(wg, n, y0, x0);
             __amdgpu_buffer_rsrc_t rin = in_rsrc(wg, wg < n_tiles ? n : 0);
 #pragma unroll
             for (int j = 0; j < NPRE; ++j) load_piece(j, rin, y0, x0);
+            constexpr int WB = 3;                          // weight pieces in flight per thread (register budget)
+#pragma unroll
+            for (int i0 = 0; i0 < NWL; i0 += WB) {
+                uint4 wreg[WB];
+#pragma unroll
+                for (int i = 0; i < WB; ++i) if (i0 + i < NWL) wreg[i] = src[(i0 + i) * 512 + tid];
+#pragma unroll
+                for (int i = 0; i < WB; ++i) if (i0 + i < NWL) ((uint4*)lds_w)[(i0 + i) * 512 + tid] = wreg[i];
+            }
+            if (tid < CQ) lds_b[tid] = a.bias[chunk * CQ + tid];
             store_patch();
         }
+        const int si = chunk / ps, sj = chunk - si * ps;
         __syncthreads();
 
         // accumulators start from the bias: lane holds channels m*32 + 8*q + 4*hi + {0..3} in
