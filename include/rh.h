@@ -18,7 +18,7 @@
  *     a text for the last failure on that context.
  *   - One context serves one stream at a time; calls on one context must not overlap.
  *   - Tensors are dense, row-major, channels last: frames u8 [F][H][W][3].
- *   - Flat macroblock index g = (f*MBH + y)*MBW + x with MBW = W/16, MBH = H/16; f counts the
+ *   - Flat macroblock index g = (f*MBH + y)*MBW + x with MBW = ceil(W/16), MBH = ceil(H/16); f counts the
  *     (stream, frame) pairs of the batch in the caller's order (the MB index of Sec. 3.3.1).
  */
 #ifndef RH_H
@@ -65,7 +65,9 @@ enum { RH_SORT_DENSITY = 0, RH_SORT_AREA = 1 };      /* rh_config.sort_policy   
 typedef struct { int32_t topology, channels, n_blocks, scale; } rh_net_desc;
 
 typedef struct {
-    int32_t frame_w, frame_h;   /* multiples of 16, else RH_E_SHAPE                        */
+    int32_t frame_w, frame_h;   /* >= 16; MB grid = ceil(w/16) x ceil(h/16): a partial MB at
+                                   the right / bottom edge is one MB, zero-filled when packed,
+                                   and only its in-frame part is pasted                     */
     int32_t max_frames;         /* capacity F of one batch                                 */
     int32_t halo;               /* pixels of context added on each side of a box           */
     int32_t bin_size;           /* bins are bin_size x bin_size pixels (multiple of 4)     */

@@ -172,7 +172,7 @@ def unpack(frames_lr: np.ndarray, s: int, net_out: np.ndarray, places: np.ndarra
         place_rot = np.ascontiguousarray(place_rot, dtype=np.int32).reshape(-1)
         assert len(place_rot) == k
     lib().orc_unpack(_p(frames_lr), F, H, W, s, _p(net_out), oh // s, ow // s,
-                     _p(places), _p(place_rot) if place_rot is not None else None, k, W // 16, H // 16,
+                     _p(places), _p(place_rot) if place_rot is not None else None, k, (W + 15) // 16, (H + 15) // 16,
                      _p(hr), _p(sel) if want_sel else None)
     return hr, sel
 

@@ -118,7 +118,7 @@ class RH:
                           NetDesc(TOPOLOGY[net.topology], net.channels, net.n_blocks, net.scale),
                           {"density": 0, "area": 1}[sort_policy], int(bool(rotate)))
         self.scale = net.scale
-        self.mbw, self.mbh = frame_w // 16, frame_h // 16
+        self.mbw, self.mbh = (frame_w + 15) // 16, (frame_h + 15) // 16
         w = np.ascontiguousarray(weights, dtype=np.float32)
         self._stream = stream if stream is not None else torch.cuda.current_stream(self.device)
         h = C.c_void_p()

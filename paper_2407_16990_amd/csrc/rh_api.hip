@@ -67,7 +67,7 @@ extern "C" rh_status rh_create(const rh_config* cfg, const float* weights, size_
 {
     if (!cfg || !weights || !out) return RH_E_INVALID;
     *out = nullptr;
-    if (cfg->frame_w < 16 || cfg->frame_h < 16 || cfg->frame_w % 16 || cfg->frame_h % 16) return RH_E_SHAPE;
+    if (cfg->frame_w < 16 || cfg->frame_h < 16) return RH_E_SHAPE;
     if (cfg->frame_w > 16 * 4095 || cfg->frame_h > 16 * 4095) return RH_E_SHAPE;
     if (cfg->max_frames < 1 || cfg->max_bins < 1 || cfg->max_bins >= (int)RH_NO_BIN) return RH_E_SHAPE;
     if (cfg->halo < 0 || cfg->bin_size < 16 || cfg->bin_size % 4 || cfg->bin_size > 4096) return RH_E_SHAPE;
@@ -81,7 +81,8 @@ extern "C" rh_status rh_create(const rh_config* cfg, const float* weights, size_
     rh_ctx* ctx = new (std::nothrow) rh_ctx();
     if (!ctx) return RH_E_NOMEM;
     ctx->cfg = *cfg; ctx->stream = (hipStream_t)hip_stream; ctx->err[0] = 0;
-    ctx->mbw = cfg->frame_w / RH_MB; ctx->mbh = cfg->frame_h / RH_MB; ctx->per = ctx->mbw * ctx->mbh;
+    // a partial macroblock at the right / bottom edge counts as one
+    ctx->mbw = (cfg->frame_w + RH_MB - 1) / RH_MB; ctx->mbh = (cfg->frame_h + RH_MB - 1) / RH_MB; ctx->per = ctx->mbw * ctx->mbh;
     ctx->T = cfg->max_box_mbs ? cfg->max_box_mbs : Tmax;
     size_t need = 0;
     if (!build_layers(cfg->net, ctx->layers, need) || need != n_floats) { delete ctx; return RH_E_SHAPE; }

@@ -68,10 +68,13 @@ __global__ __launch_bounds__(256) void k_unpack(const uint8_t* __restrict__ lr, 
     const int slot = slot_of_mb[g];
     const float* net = nullptr;
     bool turned = false;
+    int eh = B, ew = B;                                   // part of the block that lies inside the enhanced image
     if (slot >= 0) {
         const rh_mbplace p = places[slot];
-        if (p.bin != RH_NO_BIN && p.bin < n_img && p.px + RH_MB <= iw && p.py + RH_MB <= ih) {
+        if (p.bin != RH_NO_BIN && p.bin < n_img && p.px < iw && p.py < ih) {
             turned = p.rot != 0;
+            const int rows_in = (ih - p.py) * S, cols_in = (iw - p.px) * S;     // >= S
+            eh = min(B, turned ? cols_in : rows_in); ew = min(B, turned ? rows_in : cols_in);
             // upright: this lane's first pixel of row 0; turned: the block's first pixel (rows and
             // columns are exchanged when reading)
             net = enh + (((size_t)p.bin * (ih * S) + (size_t)p.py * S) * (iw * S) + (size_t)p.px * S + (turned ? 0 : gx)) * 3;
@@ -92,6 +95,8 @@ __global__ __launch_bounds__(256) void k_unpack(const uint8_t* __restrict__ lr, 
             for (int c = 0; c < 3; ++c) h[p * 3 + c] = (D - wx1[p]) * tile[row][tx[p]][c] + wx1[p] * tile[row][tx[p] + 1][c];
     };
     const int HW = W * S;
+    const int fh = min(B, H * S - my * B), fw = min(B, HW - mx * B);        // in-frame part of the block
+    const bool edge = fh < B || fw < B || eh < B || ew < B || ((HW * 3) & 3);
     uint8_t* dst = hr + (((size_t)f * H * S + (size_t)my * B) * HW + (size_t)mx * B + gx) * 3;
     int h0[12], h1[12], h2[12];                            // input rows r-1, r, r+1 (tile rows r, r+1, r+2)
     const int r0 = wave * 4;
@@ -110,6 +115,33 @@ __global__ __launch_bounds__(256) void k_unpack(const uint8_t* __restrict__ lr, 
             for (int k = 0; k < 12; ++k) {
                 const int acc = ny < 0 ? (D - wy1) * h0[k] + wy1 * h1[k] : (D - wy1) * h1[k] + wy1 * h2[k];
                 bytes[k] = (uint32_t)(acc + D * D / 2) / (uint32_t)(D * D);
+            }
+            if (edge) {
+                // Macroblock cut by the frame edge, block cut by the enhanced image's edge, or a row
+                // pitch that is not a multiple of 4 bytes: pixel by pixel, bytes only where the frame is.
+#pragma unroll
+                for (int p = 0; p < 4; ++p) {
+                    const int col = gx + p;
+                    const bool in_frame = yy < fh && col < fw, pasted = net && in_frame && yy < eh && col < ew;
+                    float ev[3] = {0.0f, 0.0f, 0.0f};
+                    if (pasted) {
+                        const float* t = turned ? net + ((size_t)col * (iw * S) + yy) * 3 : net + ((size_t)yy * (iw * S) + p) * 3;
+#pragma unroll
+                        for (int c = 0; c < 3; ++c) {
+                            ev[c] = fminf(fmaxf(__fadd_rn(q255[bytes[3 * p + c]], t[c]), 0.0f), 1.0f);
+                            bytes[3 * p + c] = (uint32_t)__fadd_rn(__fmul_rn(ev[c], 255.0f), 0.5f);
+                        }
+                    }
+                    if (net && sel) {
+                        float* sp = sel + (((size_t)slot * B + yy) * B + col) * 3;
+                        sp[0] = ev[0]; sp[1] = ev[1]; sp[2] = ev[2];
+                    }
+                    if (in_frame) {
+                        uint8_t* o = dst + (size_t)yy * HW * 3 + p * 3;
+                        o[0] = (uint8_t)bytes[3 * p]; o[1] = (uint8_t)bytes[3 * p + 1]; o[2] = (uint8_t)bytes[3 * p + 2];
+                    }
+                }
+                continue;
             }
             if (net) {                                     // placed macroblock: one branch per row of 4 pixels
                 const float* nrow = net + (size_t)yy * (iw * S) * 3;

@@ -43,8 +43,8 @@ def test_null_arguments_are_rejected_without_a_gpu():
     lib = pkg.load_library()
     h = C.c_void_p()
     assert lib.rh_create(None, None, 0, None, C.byref(h)) == 1
-    cfg = pkg.Config(100, 64, 1, 4, 64, 4, 8, 0, 0, pkg.NetDesc(0, 4, 2, 2))
+    cfg = pkg.Config(8, 64, 1, 4, 64, 4, 8, 0, 0, pkg.NetDesc(0, 4, 2, 2))
     w = np.zeros(8, dtype=np.float32)
-    assert lib.rh_create(C.byref(cfg), w.ctypes.data_as(C.c_void_p), 8, None, C.byref(h)) == 2   # 100 % 16 != 0
+    assert lib.rh_create(C.byref(cfg), w.ctypes.data_as(C.c_void_p), 8, None, C.byref(h)) == 2   # frame narrower than one macroblock
     assert lib.rh_select_regions(None, None, 1, None, 0, 0, None, None, None) == 1
     assert lib.rh_last_error(None) == b"null context"

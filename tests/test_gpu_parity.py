@@ -155,7 +155,7 @@ def test_empty_selection_and_overflow_and_errors():
     with pytest.raises(RhError):
         rh.select_regions(dev(imp), [(1, 2, 5), (0, 1, 5)])
     with pytest.raises(RhError):
-        RH(frame_w=100, frame_h=64, max_frames=1, halo=4, bin_size=64, max_bins=4, net=net, weights=blob, precision="fp32")
+        RH(frame_w=12, frame_h=64, max_frames=1, halo=4, bin_size=64, max_bins=4, net=net, weights=blob, precision="fp32")
     with pytest.raises(RhError):
         RH(frame_w=64, frame_h=64, max_frames=1, halo=30, bin_size=64, max_bins=4, net=net, weights=blob, precision="fp32")
     with pytest.raises(RhError):
@@ -368,3 +368,53 @@ def test_exact_border_fp32_topologies_with_turned_boxes(net):
 def test_exact_border_bf16(net):
     cfg = wl.replace(wl.config(3), n_frames=2, width=160, height=112, halo=6, bin_size=96, net=net)
     exact_border_check(cfg, "bf16")
+
+
+# ---- frame sides that are not multiples of 16 ----------------------------------------------------
+
+@pytest.mark.parametrize("w,h,net,precision", [
+    (168, 100, wl.Net("plain", 16, 4, 2, 0.1), "fp32"),
+    (170, 90, wl.Net("edsr", 8, 1, 3, 0.05), "fp32"),          # row pitch of the output not a multiple of 4 bytes
+    (200, 120, wl.Net("edsr", 64, 2, 4, 0.02), "bf16"),
+])
+def test_partial_macroblock_frames_whole_path(w, h, net, precision):
+    cfg = wl.replace(wl.config(1), width=w, height=h, n_frames=2, net=net, halo=5, bin_size=96, frac=0.3, precision=precision)
+    F = 2
+    frames, imp = wl.make_frames(cfg), wl.make_importance(cfg)
+    imp[:, -1, :] += 5.0; imp[:, :, -1] += 5.0                 # the cut macroblocks at the right and bottom edges
+    k = int(imp.size * 0.3)
+    segs = np.array([[0, F, k]], dtype=np.uint32)
+    blob = wl.make_weights(cfg.net, 0, precision)
+    rh = make_rh(cfg, blob, precision=precision)
+    o_plan, po, (d_frames, d_imp, o_bins) = check_select_and_plan(rh, cfg, frames, imp, segs)
+    s = cfg.net.scale
+    g_net = rh.enhance(po.bins, n=o_plan.n_bins)
+    o_net = oracle.sr_forward(cfg.net, blob, o_bins)
+    tol = 1e-5 if precision == "fp32" else 1e-2
+    assert rel_l2(g_net.cpu().numpy(), o_net) <= tol
+    sel0 = torch.full((po.places.shape[0], 16 * s, 16 * s, 3), 9.0, dtype=torch.float32, device="cuda")   # stale values must be overwritten
+    hr, sel = rh.unpack(g_net, po.places, po.counts[3:4], d_frames, want_sel=True, sel=sel0)
+    o_hr, o_sel = oracle.unpack(frames, s, o_net, o_plan.places)
+    assert hr.shape == (F, h * s, w * s, 3)
+    g_sel = sel[: len(o_plan.places)].cpu().numpy()
+    assert rel_l2(g_sel, o_sel) <= tol
+    per = cfg.mbw * cfg.mbh
+    for i, (g, box, b, px, py) in enumerate(o_plan.places.tolist()):     # the outside part of a cut block must read 0
+        y, x = divmod(g % per, cfg.mbw)
+        h_in, w_in = min(16, h - 16 * y) * s, min(16, w - 16 * x) * s
+        assert not g_sel[i, h_in:].any() and not g_sel[i, :, w_in:].any()
+    d = np.abs(hr.cpu().numpy().astype(np.int16) - o_hr.astype(np.int16))
+    B = 16 * s
+    selmask = np.kron(oracle.select(imp, segs)[0], np.ones((B, B), dtype=np.uint8)).astype(bool)[:, :h * s, :w * s]
+    assert d[~selmask].max() == 0
+    assert d.max() <= (1 if precision == "fp32" else 2)
+    # frame-based run on the same frames: identity placement with cut blocks at the edges
+    f_net = rh.enhance(d_frames)
+    places, n = rh.identity_places(F)
+    hr2, sel2 = rh.unpack(f_net, places, n, d_frames, want_sel=True)
+    of_net = oracle.sr_forward(cfg.net, blob, frames)
+    o_hr2, o_sel2 = oracle.unpack(frames, s, of_net, oracle.identity_places(F, cfg.mbh, cfg.mbw))
+    assert rel_l2(f_net.cpu().numpy(), of_net) <= tol
+    assert rel_l2(sel2.cpu().numpy(), o_sel2) <= tol
+    assert np.abs(hr2.cpu().numpy().astype(np.int16) - o_hr2.astype(np.int16)).max() <= (1 if precision == "fp32" else 2)
+    rh.close()

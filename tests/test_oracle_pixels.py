@@ -362,3 +362,48 @@ def test_exact_border_mode_equals_frame_based_everywhere(orc, topo):
         assert np.array_equal(keep[b, by:by + bh, bx:bx + bw].astype(bool), inside)
         zeros += int((~inside).sum())
     assert int((keep == 0).sum()) == zeros > 0
+
+
+def test_partial_macroblock_frames(orc):
+    """Frame sides that are not multiples of 16: the macroblock grid is ceil(H/16) x ceil(W/16).
+    (a) With every macroblock selected and the identity placement, the pasted frame is
+    clamp(bilinear/255 + SR(frame)) over the whole true-size frame, computed here without any
+    macroblock structure.  (b) The packed path zero-fills beyond the frame and pastes only the
+    in-frame part of an edge macroblock; unselected macroblocks are the bilinear base."""
+    cfg = wl.replace(wl.config(1), width=168, height=100, n_frames=2)
+    assert (cfg.mbw, cfg.mbh) == (11, 7)
+    frames, imp = wl.make_frames(cfg), wl.make_importance(cfg)
+    assert frames.shape == (2, 100, 168, 3) and imp.shape == (2, 7, 11)
+    blob = wl.make_weights(cfg.net, 0, "fp32")
+    s = cfg.net.scale
+    B = 16 * s
+    # (a) frame-based
+    net = orc.sr_forward(cfg.net, blob, frames)
+    hr, sel = orc.unpack(frames, s, net, orc.identity_places(2, cfg.mbh, cfg.mbw))
+    for f in range(2):
+        base = orc.bilinear(frames[f], s).astype(np.float64) / 255.0
+        e = np.clip(base + net[f], 0, 1)
+        q = np.floor(e * 255.0 + 0.5)
+        d = np.abs(hr[f].astype(np.float64) - q)
+        assert hr[f].shape == (200, 336, 3) and d.max() <= 1 and (d > 0).mean() < 1e-3
+    # the block of the bottom-right macroblock: in-frame part reported, the rest zero
+    last = sel[cfg.mbw * cfg.mbh - 1]
+    assert np.abs(last[:8, :16] - np.clip(orc.bilinear(frames[0], s)[192:, 320:].astype(np.float64) / 255.0 + net[0][192:, 320:], 0, 1)).max() < 1e-6
+    assert not last[8:].any() and not last[:, 16:].any()
+    # (b) packed path with edge macroblocks forced into the selection
+    imp[:, -1, :] += 5.0; imp[:, :, -1] += 5.0
+    r = orc.run_path(frames, imp, np.array([[0, 2, 60]], dtype=np.uint32), cfg.net, blob, cfg.halo, cfg.bin_size)
+    assert r.mask[:, -1, :].all() and r.mask[:, :, -1].all()
+    for (g, box, b, px, py), blk in zip(r.plan.places.tolist(), r.sel):
+        f, rem = divmod(g, cfg.mbw * cfg.mbh); y, x = divmod(rem, cfg.mbw)
+        h_in, w_in = min(16, 100 - 16 * y), min(16, 168 - 16 * x)
+        want = np.zeros((16, 16, 3), dtype=np.uint8); want[:h_in, :w_in] = frames[f, 16 * y:16 * y + h_in, 16 * x:16 * x + w_in]
+        assert np.array_equal(r.bins[b, py:py + 16, px:px + 16], want)          # zero beyond the frame
+        base = orc.bilinear(frames[f], s)[y * B:y * B + h_in * s, x * B:x * B + w_in * s].astype(np.float64) / 255.0
+        e = np.clip(base + r.net_out[b, py * s:py * s + h_in * s, px * s:px * s + w_in * s], 0, 1)
+        assert np.abs(blk[:h_in * s, :w_in * s] - e).max() < 1e-6
+        assert not blk[h_in * s:].any() and not blk[:, w_in * s:].any()
+    for f in range(2):
+        base = orc.bilinear(frames[f], s)
+        keep = ~np.kron(r.mask[f], np.ones((B, B), dtype=np.uint8)).astype(bool)[:200, :336]
+        assert np.array_equal(r.frames_hr[f][keep], base[keep])

@@ -52,11 +52,11 @@ class Config:
 
     @property
     def mbw(self) -> int:
-        return self.width // MB
+        return (self.width + MB - 1) // MB      # a partial macroblock at the right edge counts
 
     @property
     def mbh(self) -> int:
-        return self.height // MB
+        return (self.height + MB - 1) // MB
 
     @property
     def n_mbs(self) -> int:
