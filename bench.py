@@ -24,6 +24,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK = 2.5e15   # dense bf16 MFMA, FLOP/s (MI355X published)
+FP32_VALU_PEAK = 157.3e12  # fp32 vector ALUs, FLOP/s (MI355X published)
 # HBM bytes per launch of the dominant kernel class on the default workload, from the rocprofv3
 # FETCH_SIZE / WRITE_SIZE runs summarised in profiles/conv_mfma_cfg3_hbm_counters.md (scaled by
 # the plain-copy calibration); not measured live, so only reported for that workload.
@@ -166,10 +167,14 @@ def main():
     out_mpix = F * cfg.height * s * cfg.width * s * args.steps / dt / 1e6
     px_lr = n_bins * S * S
     conv_fl, conv_launches = conv_flops_per_lr_pixel(cfg.net)
+    if cfg.precision != "bf16":
+        # the fp32 path times all its layers as one class: direct convs on the vector ALUs
+        conv_fl, conv_launches = total_flops_per_lr_pixel(cfg.net), len(wl.net_layers(cfg.net))
     conv_ms, conv_n = prof["conv"]
     avg_launch_s = conv_ms / max(conv_n, 1) * 1e-3
     flop_per_launch = conv_fl * px_lr / conv_launches
     achieved = flop_per_launch / avg_launch_s if avg_launch_s > 0 else 0.0
+    PEAK = MFMA_BF16_PEAK if cfg.precision == "bf16" else FP32_VALU_PEAK
 
     result = {
         "metric": "enhanced macroblocks/s",
@@ -182,12 +187,14 @@ def main():
                    "occupy_ratio": 256.0 * k_sel / (n_bins * S * S) if n_bins else 0.0},
         "output_mpixel_per_s": out_mpix,
         "kernel_ms_per_step": {k: v[0] / args.steps for k, v in prof.items()},
-        "roofline": {"bound": "mfma", "kernel": CONV_KERNEL.get(cfg.net.channels, "k_conv_mfma"), "achieved": achieved / 1e12,
-                     "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK,
+        "roofline": {"bound": "mfma" if cfg.precision == "bf16" else "alu",
+                     "kernel": CONV_KERNEL.get(cfg.net.channels, "k_conv_mfma") if cfg.precision == "bf16" else "k_conv3x3_f32 (all layers)",
+                     "achieved": achieved / 1e12,
+                     "peak": PEAK / 1e12, "unit": "TFLOP/s", "frac": achieved / PEAK,
                      "traffic": MEASURED_TRAFFIC.get(cfg.name), "avg_launch_us": avg_launch_s * 1e6, "launches_per_step": conv_n / args.steps,
                      "flop_per_launch": flop_per_launch},
         "enhance_tflops_all_layers": total_flops_per_lr_pixel(cfg.net) * px_lr /
-                                     (sum(prof[k][0] for k in ("head", "conv", "conv_last")) / args.steps * 1e-3) / 1e12,
+                                     max(sum(prof[k][0] for k in ("head", "conv", "conv_last")) / args.steps * 1e-3, 1e-12) / 1e12,
     }
 
     # ---- the memory-bound steps: algorithmic bytes / event time, at batch size and at X batches ----

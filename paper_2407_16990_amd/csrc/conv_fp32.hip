@@ -83,6 +83,7 @@ rh_status rh_launch_enhance_fp32(rh_ctx* ctx, const uint8_t* in, int N, int H, i
     float* a = (float*)ctx->act; float* t = a + lr; float* h = t + lr; float* u1 = h + lr; float* u2 = u1 + up1;
     const std::vector<rh_layer>& L = ctx->layers;
     size_t li = 0;
+    rh_prof_scope ps(ctx, RH_PROF_CONV, (uint32_t)L.size());     // all layers of the fp32 path count as one class
     // exact-border mode (a no-op otherwise): clear the out-of-frame part of the boxes in a layer's output
 #define ZERO(buf, res) do { st = rh_zero_outside(ctx, (buf), C * (int)sizeof(float), (res), N, n_valid); if (st != RH_OK) return st; } while (0)
     if (d.topology == RH_NET_PLAIN) {
