@@ -1,7 +1,7 @@
 // Region-aware bin packing (Alg. 1) on macroblock indexes, entirely on the GPU:
 //   k_plan_label : RegionProps + Bound + Partition, one workgroup per frame (labels in LDS)
 //   k_plan_rank  : Sort by importance density (rank by counting; the order is total)
-//   k_plan_place : the serial first-fit over the ordered free-rectangle list, one workgroup,
+//   k_plan_place : the serial first-fit over the ordered free-rectangle list, one wave,
 //                  lanes test free rectangles in parallel, the list lives in LDS
 //   k_plan_emit  : placement rows for boxes and macroblocks
 #include "rh_internal.h"
@@ -10,22 +10,27 @@
 
 __global__ void k_plan_zero(uint32_t* pcount) { if (threadIdx.x < 8) pcount[threadIdx.x] = 0; }
 
-// One workgroup per frame.  LDS: lab[per], cminx[per], cmaxx[per], cmaxy[per].
+// One workgroup per frame.  LDS: lab[per], cminx[per], cmaxx[per], cmaxy[per] and, when it fits
+// (imp_in_lds), the frame's importance values: a box leader adds up to T*T of them one after the
+// other in a fixed order, which from global memory is a chain of that many load latencies.
 // A region's label is the smallest in-frame index of its macroblocks.
 __global__ __launch_bounds__(256) void k_plan_label(const uint8_t* __restrict__ mask,
                                                     const float* __restrict__ imp, int mbw, int mbh,
-                                                    int conn, int T, int sort_policy, uint32_t* __restrict__ owner_id,
+                                                    int conn, int T, int sort_policy, int imp_in_lds,
+                                                    uint32_t* __restrict__ owner_id,
                                                     rh_rawbox* __restrict__ raw, uint32_t* pcount)
 {
     extern __shared__ uint32_t sm[];
     const int per = mbw * mbh, tid = threadIdx.x, f = blockIdx.x;
     volatile uint32_t* lab = sm;
     uint32_t* cminx = sm + per; uint32_t* cmaxx = sm + 2 * per; uint32_t* cmaxy = sm + 3 * per;
+    float* simp = (float*)(sm + 4 * per);
     __shared__ int s_changed;
     const size_t base = (size_t)f * per;
     for (int i = tid; i < per; i += 256) {
         lab[i] = mask[base + i] ? (uint32_t)i : NONE;
         cminx[i] = NONE; cmaxx[i] = 0; cmaxy[i] = 0;
+        if (imp_in_lds) simp[i] = imp[base + i];
     }
     // RegionProps: iterate "take the smallest label around me, then follow it to its root"
     // until nothing changes.  Labels only decrease and always name a macroblock of the same
@@ -84,7 +89,7 @@ __global__ __launch_bounds__(256) void k_plan_label(const uint8_t* __restrict__ 
                 if (lab[j] != r) continue;
                 if (leader < 0) leader = j;
                 if (leader != i) break;                      // only the leader needs the rest
-                sum = __fadd_rn(sum, imp[base + j]);         // fp32, ascending flat index
+                sum = __fadd_rn(sum, imp_in_lds ? simp[j] : imp[base + j]);   // fp32, ascending flat index
                 x0 = min(x0, xx); x1 = max(x1, xx); y0 = min(y0, yy); y1 = max(y1, yy);
             }
             if (leader >= 0 && leader != i) break;
@@ -137,45 +142,45 @@ __global__ __launch_bounds__(256) void k_plan_rank(const rh_rawbox* __restrict__
 }
 
 // First fit (Alg. 1 main loop) with the reading of InnerFree given in the header.
-// Free rectangle j: fxy[j] = x | y<<16, fwh[j] = w | h<<16, fbin[j].  Every thread tracks the
-// list length and bin count redundantly; only the list itself is shared.
+// Free rectangle j: fxy[j] = x | y<<16, fwh[j] = w | h<<16, fbin[j].
 // box_pos[i] = {bin | turned<<16, bx | by<<16}; pcount[1] = n_bins, pcount[2] = overflow.
 // rotate: a rectangle that cannot take the box upright may take it turned (RotatePacking).
-// Barrier that orders LDS traffic only (the placement loop also issues global stores whose
-// completion nobody in the loop waits for).
-__device__ __forceinline__ void lds_sync() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
-
-__global__ __launch_bounds__(256) void k_plan_place(const rh_rawbox* __restrict__ sorted, uint32_t* pcount,
-                                                    int halo, int S, int max_bins, int free_cap, int rotate,
-                                                    uint32_t* __restrict__ box_pos)
+// The loop over the boxes is serial by definition, so its cost is the latency of one step.  It
+// runs in ONE wave: the 64 lanes test 64 free rectangles at a time and a ballot gives the first
+// fit; LDS traffic of a single wave is executed in program order, so the list needs no barrier,
+// no atomics, and every lane tracks the list length and bin count in registers.
+__global__ __launch_bounds__(64) void k_plan_place(const rh_rawbox* __restrict__ sorted, uint32_t* pcount,
+                                                   int halo, int S, int max_bins, int free_cap, int rotate,
+                                                   uint32_t* __restrict__ box_pos)
 {
     extern __shared__ uint32_t sm[];
     uint32_t* fxy = sm; uint32_t* fwh = sm + free_cap; uint32_t* fbin = sm + 2 * free_cap;
-    __shared__ uint32_t s_at;
     __shared__ uint32_t s_size[256];
-    const int tid = threadIdx.x, NT = blockDim.x;     // one wave is enough: the lists are short
+    const int lane = threadIdx.x;
     const uint32_t n = pcount[0];
     const int minside = RH_MB + 2 * halo;
     int nfree = 0, nbins = 0;
     uint32_t i = 0;
     bool overflow = false;
-    if (tid == 0) s_at = NONE;
     for (; i < n && !overflow; ++i) {
         if ((i & 255u) == 0) {                                   // stage the next 256 box sizes
-            lds_sync();
-            for (int t = tid; t < 256; t += NT)
+            for (int t = lane; t < 256; t += 64)
                 if (i + t < n) s_size[t] = sorted[i + t].wmb | ((uint32_t)sorted[i + t].hmb << 16);
         }
-        lds_sync();
         const uint32_t sz = s_size[i & 255u];
         int bw = RH_MB * (int)(sz & 0xFFFF) + 2 * halo, bh = RH_MB * (int)(sz >> 16) + 2 * halo;
-        for (int j = tid; j < nfree; j += NT) {
-            const uint32_t wh = fwh[j];
-            const int w = (int)(wh & 0xFFFF), h = (int)(wh >> 16);
-            if ((w >= bw && h >= bh) || (rotate && w >= bh && h >= bw)) { atomicMin(&s_at, (uint32_t)j); break; }
+        uint32_t at = NONE;
+        for (int base = 0; base < nfree; base += 64) {           // first rectangle, in list order, that fits
+            const int j = base + lane;
+            bool fit = false;
+            if (j < nfree) {
+                const uint32_t wh = fwh[j];
+                const int w = (int)(wh & 0xFFFF), h = (int)(wh >> 16);
+                fit = (w >= bw && h >= bh) || (rotate && w >= bh && h >= bw);
+            }
+            const unsigned long long m = __ballot(fit);
+            if (m) { at = (uint32_t)(base + __ffsll((long long)m) - 1); break; }
         }
-        lds_sync();
-        uint32_t at = s_at;
         int fx, fy, fw, fh, fb, cur_n;
         if (at == NONE) {
             if (nbins >= max_bins || nfree + 2 > free_cap) { overflow = true; break; }
@@ -187,7 +192,7 @@ __global__ __launch_bounds__(256) void k_plan_place(const rh_rawbox* __restrict_
         }
         const bool turned = !(fw >= bw && fh >= bh);         // upright whenever that fits
         if (turned) { const int t = bw; bw = bh; bh = t; }   // occupied size
-        if (tid == 0) { box_pos[2 * i] = (uint32_t)fb | (turned ? 0x10000u : 0u); box_pos[2 * i + 1] = (uint32_t)fx | ((uint32_t)fy << 16); }
+        if (lane == 0) { box_pos[2 * i] = (uint32_t)fb | (turned ? 0x10000u : 0u); box_pos[2 * i + 1] = (uint32_t)fx | ((uint32_t)fy << 16); }
         // remainder: the larger of (right strip, full height) and (bottom strip, full width),
         // plus what is left of the other
         const int ar = (fw - bw) * fh, ab = fw * (fh - bh);
@@ -202,36 +207,25 @@ __global__ __launch_bounds__(256) void k_plan_place(const rh_rawbox* __restrict_
             ni = 2;
         } else if (keep_r) { ixy[0] = Rxy; iwh[0] = Rwh; ni = 1; }
         else if (keep_b)   { ixy[0] = Bxy; iwh[0] = Bwh; ni = 1; }
+        // the survivors replace entry `at` in place: shift the tail by ni - 1
         const int delta = ni - 1, first = (int)at + 1;
-        lds_sync();                                          // all reads of entry `at` done
         if (delta > 0) {
-            for (int hi = cur_n; hi > first; hi -= NT) {
-                const int j = hi - 1 - tid;
-                const bool mv = j >= first;
-                uint32_t a = 0, b = 0, c = 0;
-                if (mv) { a = fxy[j]; b = fwh[j]; c = fbin[j]; }
-                lds_sync();
-                if (mv) { fxy[j + 1] = a; fwh[j + 1] = b; fbin[j + 1] = c; }
-                lds_sync();
+            for (int hi = cur_n; hi > first; hi -= 64) {         // from the top down: a chunk is read whole before it is written
+                const int j = hi - 1 - lane;
+                if (j >= first) { const uint32_t a = fxy[j], b = fwh[j], c = fbin[j]; fxy[j + 1] = a; fwh[j + 1] = b; fbin[j + 1] = c; }
             }
         } else if (delta < 0) {
-            for (int lo = first; lo < cur_n; lo += NT) {
-                const int j = lo + tid;
-                const bool mv = j < cur_n;
-                uint32_t a = 0, b = 0, c = 0;
-                if (mv) { a = fxy[j]; b = fwh[j]; c = fbin[j]; }
-                lds_sync();
-                if (mv) { fxy[j - 1] = a; fwh[j - 1] = b; fbin[j - 1] = c; }
-                lds_sync();
+            for (int lo = first; lo < cur_n; lo += 64) {
+                const int j = lo + lane;
+                if (j < cur_n) { const uint32_t a = fxy[j], b = fwh[j], c = fbin[j]; fxy[j - 1] = a; fwh[j - 1] = b; fbin[j - 1] = c; }
             }
         }
-        if (tid < ni) { fxy[at + tid] = ixy[tid]; fwh[at + tid] = iwh[tid]; fbin[at + tid] = fb; }
-        if (tid == 0) s_at = NONE;
+        if (lane < ni) { fxy[at + lane] = ixy[lane]; fwh[at + lane] = iwh[lane]; fbin[at + lane] = fb; }
         nfree = cur_n + delta;
     }
     // boxes that did not fit (only after an overflow)
-    for (uint32_t j = i + tid; j < n; j += NT) { box_pos[2 * j] = RH_NO_BIN; box_pos[2 * j + 1] = 0; }
-    if (tid == 0) { pcount[1] = nbins; pcount[2] = overflow ? 1u : 0u; }
+    for (uint32_t j = i + lane; j < n; j += 64) { box_pos[2 * j] = RH_NO_BIN; box_pos[2 * j + 1] = 0; }
+    if (lane == 0) { pcount[1] = nbins; pcount[2] = overflow ? 1u : 0u; }
 }
 
 __global__ __launch_bounds__(256) void k_plan_emit(const rh_rawbox* __restrict__ sorted,
@@ -276,7 +270,8 @@ __global__ __launch_bounds__(256) void k_plan_emit(const rh_rawbox* __restrict__
 rh_status rh_plan_init(rh_ctx* ctx)
 {
     // both planning kernels may need more dynamic LDS than the default limit
-    RH_HIP(ctx, hipFuncSetAttribute((const void*)k_plan_label, hipFuncAttributeMaxDynamicSharedMemorySize, ctx->per * 16));
+    RH_HIP(ctx, hipFuncSetAttribute((const void*)k_plan_label, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    ctx->per * ((size_t)ctx->per * 20 <= 150 * 1024 ? 20 : 16)));
     RH_HIP(ctx, hipFuncSetAttribute((const void*)k_plan_place, hipFuncAttributeMaxDynamicSharedMemorySize, ctx->free_cap * 12));
     return RH_OK;
 }
@@ -289,8 +284,10 @@ rh_status rh_launch_plan(rh_ctx* ctx, int F, const float* imp, const uint8_t* ma
     uint32_t* box_pos = ctx->pcount + 8;
     rh_prof_scope ps(ctx, RH_PROF_PLAN, 5);
     hipLaunchKernelGGL(k_plan_zero, dim3(1), dim3(64), 0, ctx->stream, ctx->pcount);
-    hipLaunchKernelGGL(k_plan_label, dim3(F), dim3(256), (size_t)per * 16, ctx->stream, mask, imp, ctx->mbw,
-                       ctx->mbh, ctx->cfg.connectivity, ctx->T, ctx->cfg.sort_policy, ctx->owner_id, ctx->raw, ctx->pcount);
+    const int imp_in_lds = (size_t)per * 20 <= 150 * 1024;
+    hipLaunchKernelGGL(k_plan_label, dim3(F), dim3(256), (size_t)per * (imp_in_lds ? 20 : 16), ctx->stream, mask, imp, ctx->mbw,
+                       ctx->mbh, ctx->cfg.connectivity, ctx->T, ctx->cfg.sort_policy, imp_in_lds, ctx->owner_id, ctx->raw,
+                       ctx->pcount);
     const int nblk = (total + 255) / 256;
     hipLaunchKernelGGL(k_plan_rank, dim3(nblk), dim3(256), 0, ctx->stream, ctx->raw, ctx->pcount, ctx->sorted,
                        ctx->rank_of_id);
