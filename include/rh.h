@@ -141,10 +141,12 @@ rh_status rh_select_regions(rh_ctx* ctx, const float* importance, int32_t F,
  * boxes larger than max_box_mbs cut on a grid anchored at the box's top-left, each cell shrunk
  * to the region's own MBs inside it -> sort by importance density (fp32 sum of owned
  * importance in ascending flat index, divided in fp64 by the box area in MBs), highest first,
- * ties by id -> first fit over an ordered list of free rectangles; bins are opened on demand.
+ * ties by id (rh_config.sort_policy selects large-item-first instead) -> first fit over an
+ * ordered list of free rectangles; bins are opened on demand.
  * A box lands on the free rectangle's top-left; the L-shaped remainder becomes its larger
  * strip plus the rest, rectangles with a side < 16+2*halo are dropped, survivors replace the
- * free rectangle in the list, smaller area first.  No rotation (rot = 0).
+ * free rectangle in the list, smaller area first.  Boxes stay upright (rot = 0) unless
+ * rh_config.rotate is set.
  * Stitch: bins u8 [max_bins][S][S][3]; inside a placed box the frame's pixels (zero where the
  * halo leaves the frame), zero elsewhere; only bins [0, n_bins) are written.
  * Inputs (dev): frames u8 [F][H][W][3], importance, and mask/list/n_sel from rh_select_regions.
@@ -186,7 +188,10 @@ rh_status rh_enhance_exact(rh_ctx* ctx, const uint8_t* in, int32_t N, const rh_b
  * factor s, half-pixel centres, edge clamp, exact integer arithmetic, round half up); every
  * placed MB's (16s x 16s) block is replaced by q = floor(255*e + 0.5),
  * e = clamp(base/255 + net, 0, 1) in fp32, net read from image `bin` of `enhanced`
- * (f32 [n_img][s*ih][s*iw][3]) at (s*px, s*py).  Places with bin = 0xFFFF stay bilinear.
+ * (f32 [n_img][s*ih][s*iw][3]) at (s*px, s*py), transposed back if the place is turned.
+ * Places with bin = 0xFFFF stay bilinear.  Of a block cut by the frame's right / bottom edge
+ * (frame sides that are not multiples of 16) or by the edge of the enhanced image only the
+ * part inside both is pasted; sel reports 0 for the rest.
  * places/n_places: dev, from rh_pack (n_places = &counts[3]) or rh_identity_places.
  * sel (dev, may be NULL): f32 [n_places][16s][16s][3], the unquantised e of every placed MB.
  */
@@ -209,7 +214,7 @@ rh_status rh_read_counts(rh_ctx* ctx, const uint32_t* counts, uint32_t out[4]);
  * rh_profile_read synchronises, adds up the elapsed times and launch counts since the last
  * read into ms[RH_PROF_N] / launches[RH_PROF_N] (host arrays) and resets them.
  * RH_PROF_CONV is the bf16 MFMA conv with C input and bf16 output channels (the body and the
- * upsampling convs), the kernel that dominates the path.
+ * upsampling convs), the kernel that dominates the path; with RH_FP32 it covers all layers.
  */
 enum { RH_PROF_SELECT = 0, RH_PROF_PLAN = 1, RH_PROF_GATHER = 2, RH_PROF_HEAD = 3, RH_PROF_CONV = 4,
        RH_PROF_CONV_LAST = 5, RH_PROF_UNPACK = 6, RH_PROF_N = 7 };
