@@ -190,8 +190,9 @@ rh_status rh_enhance_exact(rh_ctx* ctx, const uint8_t* in, int32_t N, const rh_b
  * e = clamp(base/255 + net, 0, 1) in fp32, net read from image `bin` of `enhanced`
  * (f32 [n_img][s*ih][s*iw][3]) at (s*px, s*py), transposed back if the place is turned.
  * Places with bin = 0xFFFF stay bilinear.  Of a block cut by the frame's right / bottom edge
- * (frame sides that are not multiples of 16) or by the edge of the enhanced image only the
- * part inside both is pasted; sel reports 0 for the rest.
+ * (frame sides that are not multiples of 16) only the part inside the frame is pasted and sel
+ * reports 0 for the rest.  A place is honoured when the in-frame part of its block lies inside
+ * the enhanced image (whole MBs: px + 16 <= iw, py + 16 <= ih); otherwise the MB stays bilinear.
  * places/n_places: dev, from rh_pack (n_places = &counts[3]) or rh_identity_places.
  * sel (dev, may be NULL): f32 [n_places][16s][16s][3], the unquantised e of every placed MB.
  */

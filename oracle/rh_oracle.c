@@ -508,9 +508,9 @@ void orc_border_keep(int H, int W, const int32_t* boxes, int n_boxes, int halo, 
  * (may be NULL = none turned) as in orc_plan.  sel (optional): fp32 [k][16s][16s][3], the
  * unquantised values.
  * H, W need not be multiples of 16: the macroblock grid is ceil(H/16) x ceil(W/16) and the part
- * of an edge macroblock that lies outside the frame is neither written nor reported (sel = 0);
- * the same holds for the part of a block that lies outside the enhanced image (the frame-based
- * run's identity placement). */
+ * of an edge macroblock that lies outside the frame is neither written nor reported (sel = 0).
+ * A place is honoured when the in-frame part of its block lies inside the enhanced image (the
+ * frame-based run's identity placement on such frames); otherwise the MB stays bilinear. */
 void orc_unpack(const uint8_t* frames_lr, int F, int H, int W, int s,
                 const double* net, int ih, int iw,
                 const int32_t* places, const int32_t* place_rot, int k, int mbw_frame, int mbh_frame,
@@ -526,13 +526,18 @@ void orc_unpack(const uint8_t* frames_lr, int F, int H, int W, int s,
         int g = pl[0], bin = pl[2], px = pl[3], py = pl[4];
         if (bin == 0xFFFF) continue;
         int f = g / per, my = (g % per) / mbw_frame, mx = g % mbw_frame;
+        int fh = imin(B, H * s - my * B), fw = imin(B, WW - mx * B);           /* in-frame part */
+        int rot = place_rot && place_rot[i];
+        if (px * s + (rot ? fh : fw) > iw * s || py * s + (rot ? fw : fh) > ih * s) {
+            if (sel) memset(sel + (size_t)i * B * B * 3, 0, sizeof(float) * B * B * 3);
+            continue;
+        }
         for (int y = 0; y < B; ++y) for (int x = 0; x < B; ++x) for (int c = 0; c < 3; ++c) {
             if (sel) sel[(((size_t)i * B + y) * B + x) * 3 + c] = 0.0f;
             if (my * B + y >= H * s || mx * B + x >= WW) continue;             /* outside the frame */
             size_t di = (size_t)f * hr + (((size_t)(my * B + y)) * WW + (mx * B + x)) * 3 + c;
             int ny = y, nx = x;
             if (place_rot && place_rot[i]) { ny = x; nx = y; }   /* turned box: transposed back */
-            if (py * s + ny >= ih * s || px * s + nx >= iw * s) continue;     /* outside the enhanced image */
             size_t si = (size_t)bin * nimg + (((size_t)(py * s + ny)) * (iw * s) + (px * s + nx)) * 3 + c;
             float base = (float)frames_hr[di] / 255.0f;
             float e = base + (float)net[si];

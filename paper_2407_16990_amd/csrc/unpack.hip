@@ -39,7 +39,11 @@ __global__ __launch_bounds__(256) void k_identity_places(rh_mbplace* __restrict_
 // out = (sum + D*D/2) / (D*D) with D = 2S.  For a placed macroblock the pixel becomes
 // floor(255 * clamp(base/255 + net, 0, 1) + 0.5) in fp32 (base/255 from a 256-entry table of
 // correctly rounded quotients).
-template <int S>
+// EDGE: frames with cut macroblocks at the right / bottom edge (sides not multiples of 16) or a row
+// pitch that is not a multiple of 4 bytes; those blocks go pixel by pixel.  A place is honoured
+// when the in-frame part of its block lies inside the enhanced image (for whole macroblocks:
+// px + 16 <= iw and py + 16 <= ih), otherwise the macroblock stays bilinear.
+template <int S, bool EDGE>
 __global__ __launch_bounds__(256) void k_unpack(const uint8_t* __restrict__ lr, int H, int W, int mbw,
                                                 const float* __restrict__ enh, int n_img, int ih, int iw,
                                                 const rh_mbplace* __restrict__ places,
@@ -68,13 +72,13 @@ __global__ __launch_bounds__(256) void k_unpack(const uint8_t* __restrict__ lr, 
     const int slot = slot_of_mb[g];
     const float* net = nullptr;
     bool turned = false;
-    int eh = B, ew = B;                                   // part of the block that lies inside the enhanced image
+    const int HW = W * S;
+    const int fh = EDGE ? min(B, H * S - my * B) : B, fw = EDGE ? min(B, HW - mx * B) : B;   // in-frame part of the block
     if (slot >= 0) {
         const rh_mbplace p = places[slot];
-        if (p.bin != RH_NO_BIN && p.bin < n_img && p.px < iw && p.py < ih) {
-            turned = p.rot != 0;
-            const int rows_in = (ih - p.py) * S, cols_in = (iw - p.px) * S;     // >= S
-            eh = min(B, turned ? cols_in : rows_in); ew = min(B, turned ? rows_in : cols_in);
+        turned = p.rot != 0;
+        const int need_w = turned ? fh : fw, need_h = turned ? fw : fh;     // extent of that part inside the bin image
+        if (p.bin != RH_NO_BIN && p.bin < n_img && p.px * S + need_w <= iw * S && p.py * S + need_h <= ih * S) {
             // upright: this lane's first pixel of row 0; turned: the block's first pixel (rows and
             // columns are exchanged when reading)
             net = enh + (((size_t)p.bin * (ih * S) + (size_t)p.py * S) * (iw * S) + (size_t)p.px * S + (turned ? 0 : gx)) * 3;
@@ -94,9 +98,7 @@ __global__ __launch_bounds__(256) void k_unpack(const uint8_t* __restrict__ lr, 
 #pragma unroll
             for (int c = 0; c < 3; ++c) h[p * 3 + c] = (D - wx1[p]) * tile[row][tx[p]][c] + wx1[p] * tile[row][tx[p] + 1][c];
     };
-    const int HW = W * S;
-    const int fh = min(B, H * S - my * B), fw = min(B, HW - mx * B);        // in-frame part of the block
-    const bool edge = fh < B || fw < B || eh < B || ew < B || ((HW * 3) & 3);
+    const bool edge = EDGE && (fh < B || fw < B || ((HW * 3) & 3));
     uint8_t* dst = hr + (((size_t)f * H * S + (size_t)my * B) * HW + (size_t)mx * B + gx) * 3;
     int h0[12], h1[12], h2[12];                            // input rows r-1, r, r+1 (tile rows r, r+1, r+2)
     const int r0 = wave * 4;
@@ -116,13 +118,13 @@ __global__ __launch_bounds__(256) void k_unpack(const uint8_t* __restrict__ lr, 
                 const int acc = ny < 0 ? (D - wy1) * h0[k] + wy1 * h1[k] : (D - wy1) * h1[k] + wy1 * h2[k];
                 bytes[k] = (uint32_t)(acc + D * D / 2) / (uint32_t)(D * D);
             }
-            if (edge) {
-                // Macroblock cut by the frame edge, block cut by the enhanced image's edge, or a row
-                // pitch that is not a multiple of 4 bytes: pixel by pixel, bytes only where the frame is.
+            if (EDGE && edge) {
+                // Macroblock cut by the frame edge, or a row pitch that is not a multiple of 4 bytes:
+                // pixel by pixel, bytes only where the frame is.
 #pragma unroll
                 for (int p = 0; p < 4; ++p) {
                     const int col = gx + p;
-                    const bool in_frame = yy < fh && col < fw, pasted = net && in_frame && yy < eh && col < ew;
+                    const bool in_frame = yy < fh && col < fw, pasted = net && in_frame;
                     float ev[3] = {0.0f, 0.0f, 0.0f};
                     if (pasted) {
                         const float* t = turned ? net + ((size_t)col * (iw * S) + yy) * 3 : net + ((size_t)yy * (iw * S) + p) * 3;
@@ -199,12 +201,16 @@ rh_status rh_launch_unpack(rh_ctx* ctx, const float* enh, int n_img, int ih, int
     rh_fill_i32(ctx, ctx->slot_of_mb, -1, (size_t)total);
     hipLaunchKernelGGL(k_slot_scatter, dim3(nb), dim3(256), 0, ctx->stream, places, n_places, total, ctx->slot_of_mb);
     const int S = ctx->cfg.net.scale;
+    const bool cut = ctx->cfg.frame_w % RH_MB || ctx->cfg.frame_h % RH_MB || ((ctx->cfg.frame_w * S * 3) & 3);
 #define LAUNCH_UNPACK(SC)                                                                                       \
-    hipLaunchKernelGGL(k_unpack<SC>, dim3((ctx->mbw + (64 / (4 * SC)) - 1) / (64 / (4 * SC)), ctx->mbh, F), dim3(256), 0, \
+    do { if (cut) LAUNCH_UNPACK_E(SC, true); else LAUNCH_UNPACK_E(SC, false); } while (0)
+#define LAUNCH_UNPACK_E(SC, E)                                                                                  \
+    hipLaunchKernelGGL((k_unpack<SC, E>), dim3((ctx->mbw + (64 / (4 * SC)) - 1) / (64 / (4 * SC)), ctx->mbh, F), dim3(256), 0, \
                        ctx->stream, lr, ctx->cfg.frame_h, ctx->cfg.frame_w, ctx->mbw, enh, n_img, ih, iw, places,  \
                        ctx->slot_of_mb, hr, sel)
     if (S == 1) LAUNCH_UNPACK(1); else if (S == 2) LAUNCH_UNPACK(2); else if (S == 3) LAUNCH_UNPACK(3); else LAUNCH_UNPACK(4);
 #undef LAUNCH_UNPACK
+#undef LAUNCH_UNPACK_E
     RH_HIP(ctx, hipGetLastError());
     return RH_OK;
 }
