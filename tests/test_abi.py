@@ -48,3 +48,21 @@ def test_null_arguments_are_rejected_without_a_gpu():
     assert lib.rh_create(C.byref(cfg), w.ctypes.data_as(C.c_void_p), 8, None, C.byref(h)) == 2   # frame narrower than one macroblock
     assert lib.rh_select_regions(None, None, 1, None, 0, 0, None, None, None) == 1
     assert lib.rh_last_error(None) == b"null context"
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py --gpus N with N > 1 exits with a message instead of printing a figure (one-GPU build)."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "one GPU" in r.stderr and not r.stdout.strip()
+
+
+def test_new_entry_points_reject_null_arguments():
+    import paper_2407_16990_amd as pkg
+    lib = pkg.load_library()
+    assert lib.rh_enhance_exact(None, None, 1, None, None, None, None) == 1
+    out = (C.c_double * 3)()
+    assert lib.rh_probe_mfma(None, 0, C.c_double(1.0), C.byref(out)) == 1
