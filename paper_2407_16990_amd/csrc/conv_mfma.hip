@@ -510,6 +510,13 @@ rh_status rh_launch_enhance_bf16(rh_ctx* ctx, const uint8_t* in, int N, int H, i
         up1 = lr * r * r; need += up1;
         if (s == 4) { up2 = up1 * 4; need += up2; }
     }
+    {   // the conv kernels address one image with 32-bit byte offsets (buffer instructions)
+        const int rmax = d.topology == RH_NET_EDSR ? s : 1;
+        const unsigned long long img_bytes = (unsigned long long)H * rmax * W * rmax * C * 2ull;
+        if (img_bytes >= (1ull << 31))
+            RH_FAIL(ctx, RH_E_SHAPE, "rh_enhance: %dx%d images need %llu bytes of bf16 activations each at x%d; the limit is 2 GiB",
+                    W, H, img_bytes, rmax);
+    }
     rh_status st = rh_ensure_workspace(ctx, need * 2);
     if (st != RH_OK) return st;
     __bf16* a = (__bf16*)ctx->act; __bf16* t = a + lr; __bf16* h = t + lr; __bf16* u1 = h + lr; __bf16* u2 = u1 + up1;

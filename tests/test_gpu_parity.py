@@ -161,6 +161,14 @@ def test_empty_selection_and_overflow_and_errors():
     with pytest.raises(RhError):
         RH(frame_w=64, frame_h=64, max_frames=1, halo=4, bin_size=64, max_bins=4, net=net, weights=blob[:-1], precision="fp32")
     rh.close()
+    # bf16 path: an image whose activations would pass 2 GiB is refused before anything is launched or allocated
+    net64 = wl.Net("edsr", 64, 1, 4, 0.02)
+    rh2 = RH(frame_w=64, frame_h=64, max_frames=1, halo=4, bin_size=64, max_bins=4, net=net64,
+             weights=wl.make_weights(net64, 0, "bf16"), precision="bf16")
+    with pytest.raises(RhError) as ei:
+        rh2.enhance(torch.zeros((1, 1100, 1100, 3), dtype=torch.uint8, device="cuda"))   # 4400 x 4400 x 128 B > 2 GiB
+    assert "2 GiB" in str(ei.value)
+    rh2.close()
 
 
 def test_frame_based_run_fp32_matches_oracle():
