@@ -164,6 +164,10 @@ rh_status rh_pack(rh_ctx* ctx, const uint8_t* frames, int32_t F, const float* im
  * [N][s*H][s*W][3].  Used for the packed bins and, with whole frames, for the frame-based
  * comparison run.  n_valid (dev u32[1], may be NULL): when given, only images [0, *n_valid)
  * are computed (pass &counts[1] to avoid a host round trip).  H, W >= 3.
+ * The context's activation workspace only grows: a call that needs more than every earlier call
+ * synchronises the stream and reallocates it (sized by N, not by *n_valid); later calls of the
+ * same or a smaller size allocate nothing.  RH_BF16: one image's activations at the network's
+ * highest internal resolution must stay below 2 GiB (RH_E_SHAPE otherwise).
  */
 rh_status rh_enhance(rh_ctx* ctx, const uint8_t* in, int32_t N, int32_t H, int32_t W,
                      float* out, const uint32_t* n_valid);
