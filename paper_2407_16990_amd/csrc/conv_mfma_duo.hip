@@ -29,6 +29,9 @@
 #include "conv_mfma_common.h"
 
 #define PW 34
+#ifndef DUO_DEAL_CHUNKS
+#define DUO_DEAL_CHUNKS 1
+#endif
 
 #ifdef RH_PHASE_TIMING
 __device__ unsigned long long rh_dbg2[36];
@@ -78,8 +81,19 @@ __global__ __launch_bounds__(512) void k_conv_mfma_duo(conv_args a)
     const int tiles_x = (a.W + 31) / 32, tiles_y = (a.H + 15) / 16;
     const int tiles_img = tiles_x * tiles_y;
     const int n_tiles = n_img * tiles_img;
-    const int G = gridDim.x;
-    const int wg = (G % 8 == 0) ? (blockIdx.x % 8) * (G / 8) + blockIdx.x / 8 : blockIdx.x;
+    // Tile order.  Workgroups go to the 8 XCDs round-robin; XCD x takes a contiguous run of tile
+    // lanes so that neighbouring tiles (shared halo pixels) meet in one L2.
+    // Layers with several output chunks (the upsampling convs): when the grid allows it the chunks
+    // are dealt to workgroups instead of looped over - the n_chunks workgroups of one XCD that
+    // share a tile lane process the same tiles at about the same time, each with its own chunk's
+    // weights resident, so the input is fetched from HBM once and the other reads hit L2
+    // (looping chunks outermost reads the whole input once per chunk).
+    const bool deal = DUO_DEAL_CHUNKS && a.n_chunks > 1 && gridDim.x % (8 * a.n_chunks) == 0;
+    const int G = deal ? gridDim.x / a.n_chunks : gridDim.x;                  // tile lanes
+    const int xcd = blockIdx.x % 8, local = blockIdx.x / 8;
+    const int wg = deal ? xcd * (G / 8) + local / a.n_chunks
+                        : ((G % 8 == 0) ? xcd * (G / 8) + local : (int)blockIdx.x);
+    const int chunk_begin = deal ? local % a.n_chunks : 0, chunk_end = deal ? chunk_begin + 1 : a.n_chunks;
     const int iters = n_tiles > wg ? (n_tiles - wg + G - 1) / G : 0;          // same for all 512 threads
     const int ps = a.ps;
     const uint32_t in_img_bytes = (uint32_t)a.H * a.W * PIXB;
@@ -133,7 +147,7 @@ __global__ __launch_bounds__(512) void k_conv_mfma_duo(conv_args a)
                                                  tile < n_tiles ? in_img_bytes : 0u, RSRC_FLAGS);
     };
 
-    for (int chunk = 0; chunk < a.n_chunks; ++chunk) {
+    for (int chunk = chunk_begin; chunk < chunk_end; ++chunk) {
         __syncthreads();                                   // all 8 waves: previous chunk completely done
         {   // the chunk's weights and the first patch of both teams: all loads are issued before
             // the first LDS store waits for any of them
