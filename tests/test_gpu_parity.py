@@ -426,3 +426,24 @@ def test_partial_macroblock_frames_whole_path(w, h, net, precision):
     assert rel_l2(sel2.cpu().numpy(), o_sel2) <= tol
     assert np.abs(hr2.cpu().numpy().astype(np.int16) - o_hr2.astype(np.int16)).max() <= (1 if precision == "fp32" else 2)
     rh.close()
+
+
+# ---- rh_enhance on odd image shapes ----------------------------------------------------------------
+
+@pytest.mark.parametrize("precision,net", [("bf16", wl.Net("edsr", 64, 1, 4, 0.02)), ("bf16", wl.Net("edsr", 64, 1, 3, 0.02)),
+                                           ("bf16", wl.Net("res", 32, 1, 2, 0.03)), ("fp32", wl.Net("edsr", 8, 1, 2, 0.05))])
+def test_enhance_small_and_ragged_images(precision, net):
+    """rh_enhance takes any H, W >= 3: images smaller than one tile, one pixel over a tile edge, prime sizes."""
+    cfg = wl.replace(wl.config(1), net=net, precision=precision)
+    blob = wl.make_weights(net, 3, precision)
+    rh = make_rh(cfg, blob, precision=precision)
+    rng = np.random.default_rng(11)
+    tol = 1e-5 if precision == "fp32" else 1e-2
+    for (n, h, w) in [(2, 3, 3), (1, 5, 7), (3, 17, 33), (1, 16, 32), (2, 31, 65), (1, 9, 130)]:
+        imgs = rng.integers(0, 256, size=(n, h, w, 3), dtype=np.uint8)
+        got = rh.enhance(dev(imgs)).cpu().numpy()
+        want = oracle.sr_forward(net, blob, imgs)
+        e = rel_l2(got, want)
+        print(f"[{net.topology}{net.channels}x{net.scale}/{precision}] {n}x{h}x{w}: rel-L2 {e:.3e}", flush=True)
+        assert got.shape == want.shape and e <= tol
+    rh.close()
