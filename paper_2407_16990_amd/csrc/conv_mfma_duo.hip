@@ -66,6 +66,7 @@ __global__ __launch_bounds__(512) void k_conv_mfma_duo(conv_args a)
     constexpr int WBYTES = 9 * KS * MT * 1024, PATCHB = PH * PW * PIXB, NSTEP = 3 * KS, CQ = 64;
     constexpr int NMAIN = PH, NHP = PH * 2 * NCH, NHALO = 1, NPRE = NMAIN + NHALO;      // 16-byte patch pieces per thread
     static_assert(NHP <= 256, "halo pieces must fit one per thread");
+    static_assert(MID >= 1 && MID <= NSTEP - 1, "the compute phase must hold exactly two barriers");
     // MID: the compute phase's first barrier comes after MID of the 12 steps; it pairs with the end
     // of the other team's loads + rounding + skip add + stores
     constexpr int NCHO = 8, OPIXB = 128, NOUT = RW * 32 * NCHO / 64, PPJ = 8, JPR = 4;   // output pieces per lane
@@ -356,12 +357,12 @@ static hipError_t launch_duo(hipStream_t stream, const conv_args& a, int grid)
 
 hipError_t rh_launch_conv_duo(hipStream_t stream, const conv_args& a, int grid, bool skip, bool relu)
 {
-    // first barrier of the compute phase after 11 of the 12 steps (measured best for all variants)
+    // first barrier of the compute phase after 10 of the 12 steps (A/B on one box: 0.7 % better than 11, 9 is worse)
 #ifndef DUO_MID_SKIP
-#define DUO_MID_SKIP 11
+#define DUO_MID_SKIP 10
 #endif
 #ifndef DUO_MID_PLAIN
-#define DUO_MID_PLAIN 11
+#define DUO_MID_PLAIN 10
 #endif
     if (skip) return launch_duo<true, false, DUO_MID_SKIP>(stream, a, grid);
     if (relu) return launch_duo<false, true, DUO_MID_PLAIN>(stream, a, grid);
