@@ -479,7 +479,7 @@ static rh_status conv(rh_ctx* ctx, const rh_layer& L, const __bf16* in, void* ou
     a.dbg = getenv("RH_DBG") ? atoi(getenv("RH_DBG")) : 0;
 #endif
     a.relu = relu; a.ps = L.ps; a.n_chunks = last ? 1 : L.ps * L.ps; a.cout_real = L.cout; a.s_final = s_final;
-    const int grid = 256;
+    const int grid = ctx->n_cu;            // persistent kernels: one workgroup per compute unit (256 on MI355X)
     const int MT = last ? L.cout_pad / 32 : L.cin / 32;
     hipError_t e;
     // bf16-output convs come as (ReLU, no skip), (skip, no ReLU) or (neither)

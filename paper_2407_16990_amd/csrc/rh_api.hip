@@ -96,6 +96,8 @@ extern "C" rh_status rh_create(const rh_config* cfg, const float* weights, size_
     rh_status st = RH_OK;
     hipError_t e = hipGetDevice(&ctx->device);
 #define A(call) if (e == hipSuccess) e = (call)
+    A(hipDeviceGetAttribute(&ctx->n_cu, hipDeviceAttributeMultiprocessorCount, ctx->device));
+    if (e == hipSuccess && ctx->n_cu < 1) ctx->n_cu = 1;
     A(dalloc(&ctx->w_f32, n_floats));
     A(hipMemcpy(ctx->w_f32, weights, n_floats * sizeof(float), hipMemcpyHostToDevice));
     A(dalloc(&ctx->frame_seg, cfg->max_frames)); A(dalloc(&ctx->seg_par, 4 * (size_t)cfg->max_frames));

@@ -43,6 +43,7 @@ struct rh_ctx {
     uint32_t prof_launches[RH_PROF_N];
     hipStream_t stream;
     int device;
+    int n_cu;               // compute units of the device: the persistent conv kernels launch one workgroup each
     int mbw, mbh, per;      // macroblock grid of one frame
     int T;                  // partition size in MBs
     int free_cap;           // capacity of the free-rectangle list (entries)
