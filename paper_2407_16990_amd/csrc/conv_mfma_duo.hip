@@ -29,6 +29,12 @@
 #include "conv_mfma_common.h"
 
 #define PW 34
+#ifndef DUO_SEED_IN_COMPUTE
+#define DUO_SEED_IN_COMPUTE 1
+#endif
+#ifndef DUO_SKIP_IN_COMPUTE
+#define DUO_SKIP_IN_COMPUTE 1
+#endif
 #ifndef DUO_DEAL_CHUNKS
 #define DUO_DEAL_CHUNKS 1
 #endif
@@ -66,6 +72,10 @@ __global__ __launch_bounds__(512) void k_conv_mfma_duo(conv_args a)
     constexpr int WBYTES = 9 * KS * MT * 1024, PATCHB = PH * PW * PIXB, NSTEP = 3 * KS, CQ = 64;
     constexpr int NMAIN = PH, NHP = PH * 2 * NCH, NHALO = 1, NPRE = NMAIN + NHALO;      // 16-byte patch pieces per thread
     static_assert(NHP <= 256, "halo pieces must fit one per thread");
+    // The accumulators start from the bias.  The skip variant's drain phase is the longer of the two
+    // phases, so there the seeding belongs to the compute phase; otherwise it is done in the drain phase.
+    constexpr bool SEED_IN_COMPUTE = DUO_SEED_IN_COMPUTE && SKIP;
+    constexpr bool SKIP_IN_COMPUTE = DUO_SKIP_IN_COMPUTE;
     static_assert(MID >= 1 && MID <= NSTEP - 1, "the compute phase must hold exactly two barriers");
     // MID: the compute phase's first barrier comes after MID of the 12 steps; it pairs with the end
     // of the other team's loads + rounding + skip add + stores
@@ -187,12 +197,18 @@ __global__ __launch_bounds__(512) void k_conv_mfma_duo(conv_args a)
                     for (int r = 0; r < RW; ++r) { acc[r][m][4 * q] = bv.x; acc[r][m][4 * q + 1] = bv.y; acc[r][m][4 * q + 2] = bv.z; acc[r][m][4 * q + 3] = bv.w; }
                 }
         };
-        seed_acc();
+        if constexpr (!SEED_IN_COMPUTE) seed_acc();
         PH2_INIT;
         if (team == 1) idle_phase();
         for (int it = 0; it < iters; ++it) {
             PH2(0);
+            const int tile = wg + it * G, ntile = tile + G;
+            int n, y0, x0; tile_origin(tile, n, y0, x0);
+            __amdgpu_buffer_rsrc_t rsk = __builtin_amdgcn_make_buffer_rsrc(
+                (void*)((uint8_t*)a.skip + (size_t)n * out_img_bytes), 0, SKIP ? out_img_bytes : 0u, RSRC_FLAGS);
+            uint4 sk[SKIP ? NOUT : 1];
             // ---------------- compute phase ----------------
+            if constexpr (SEED_IN_COMPUTE) seed_acc();
             const uint8_t* wlane = lds_w + (lane << 4);
             const uint8_t* prow = lds_p + (wave * RW) * (PW * PIXB);
             bf16x8 A0[3][MT], A1[3][MT], B0[NR], B1[NR];
@@ -243,6 +259,11 @@ __global__ __launch_bounds__(512) void k_conv_mfma_duo(conv_args a)
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
+                if constexpr (SKIP && SKIP_IN_COMPUTE && st < NOUT) {
+                    const i32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsk, out_off(st, y0, x0, 0, 0), 0, 0);
+                    sk[st] = make_uint4(v[0], v[1], v[2], v[3]);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
                 if constexpr (st == MID - 1 || st == NSTEP - 1) {   // the two barriers of the compute phase
                     PH2(1 + st / 4 * 0);
                     asm volatile("s_barrier" ::: "memory");
@@ -258,29 +279,28 @@ __global__ __launch_bounds__(512) void k_conv_mfma_duo(conv_args a)
             __builtin_amdgcn_s_setprio(0);
 
             // ---------------- drain phase ----------------
-            const int tile = wg + it * G, ntile = tile + G;
-            int n, y0, x0; tile_origin(tile, n, y0, x0);
             int nn, ny0, nx0; tile_origin(ntile, nn, ny0, nx0);
             __amdgpu_buffer_rsrc_t rin = in_rsrc(ntile, ntile < n_tiles ? nn : 0);
-            __amdgpu_buffer_rsrc_t rsk = __builtin_amdgcn_make_buffer_rsrc(
-                (void*)((uint8_t*)a.skip + (size_t)n * out_img_bytes), 0, SKIP ? out_img_bytes : 0u, RSRC_FLAGS);
             __amdgpu_buffer_rsrc_t rout = __builtin_amdgcn_make_buffer_rsrc(
                 (void*)((uint8_t*)a.out + (size_t)n * out_img_bytes), 0, out_img_bytes, RSRC_FLAGS);
-            uint4 sk[SKIP ? NOUT : 1];
-            // All global loads of the team are issued here, by waves that are not feeding the
-            // matrix pipe: this tile's skip values (used after the wave-local wait) and the next
-            // tile's patch (stored to LDS at the end of the phase).  The CU's one address unit
+            // The global loads of the next tile's patch (stored to LDS at the end of the phase) are
+            // issued here, by waves that are not feeding the matrix pipe.  The skip variant's
+            // drain phase is the longer of the two phases: there the tile's skip values are loaded
+            // during its own compute phase instead (one load after each of the first 8 steps), which
+            // costs the matrix pipe a few issue slots but takes their issue time and their whole
+            // latency off the critical phase.  The CU's one address unit
             // takes about 16 cycles per 64 x 16-byte instruction and all four waves of the team
             // arrive together, so a wave that issues its loads back to back is held for 60-90
             // cycles by each of them: the loads are dealt out one or two at a time between the
             // 16 units of rounding work instead.
-            constexpr int NLD = NPRE + (SKIP ? NOUT : 0), NUNIT = MT * 4 * RW;
+            constexpr bool SKIP_HERE = SKIP && !SKIP_IN_COMPUTE;
+            constexpr int NLD = NPRE + (SKIP_HERE ? NOUT : 0), NUNIT = MT * 4 * RW;
             auto issue_load = [&](int i) __attribute__((always_inline)) {
-                if (SKIP && i < NOUT) {
+                if (SKIP_HERE && i < NOUT) {
                     const i32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsk, out_off(i, y0, x0, 0, 0), 0, 0);
                     sk[i] = make_uint4(v[0], v[1], v[2], v[3]);
                 } else {
-                    load_piece(i - (SKIP ? NOUT : 0), rin, ny0, nx0);
+                    load_piece(i - (SKIP_HERE ? NOUT : 0), rin, ny0, nx0);
                 }
             };
             uint8_t* stg = lds_p + wave * (RW * 32 * OPIXB);
@@ -305,7 +325,7 @@ __global__ __launch_bounds__(512) void k_conv_mfma_duo(conv_args a)
                         *(uint2*)(stg + (r * 32 + lx) * OPIXB + (((m * 4 + q) ^ okey) << 4) + hi * 8) = pk;
                         __builtin_amdgcn_sched_barrier(0);
                     }
-            seed_acc();
+            if constexpr (!SEED_IN_COMPUTE) seed_acc();
             PH2(3);
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");     // the slice is private to the wave: no barrier
             PH2(4);
