@@ -82,7 +82,10 @@ __global__ __launch_bounds__(512) void k_conv_mfma_duo(conv_args a)
     constexpr int NCHO = 8, OPIXB = 128, NOUT = RW * 32 * NCHO / 64, PPJ = 8, JPR = 4;   // output pieces per lane
 
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-    const int tid = threadIdx.x, team = tid >> 8, ttid = tid & 255, lane = tid & 63, wave = (tid >> 6) & 3;
+    // team and wave are uniform over a wave: taken through readfirstlane so that the compiler keeps
+    // everything derived from them (tile rows, row validity, descriptors) in scalar registers
+    const int tid = threadIdx.x, ttid = tid & 255, lane = tid & 63;
+    const int team = __builtin_amdgcn_readfirstlane(tid >> 8), wave = __builtin_amdgcn_readfirstlane((tid >> 6) & 3);
     const int lx = lane & 31, hi = lane >> 5;
     uint8_t* lds_w = lds;
     uint8_t* lds_p = lds + WBYTES + team * PATCHB;
