@@ -24,7 +24,8 @@ __global__ __launch_bounds__(256) void k_head_mfma(const uint8_t* __restrict__ i
     __shared__ __attribute__((aligned(16))) uint16_t s_lut[256];          // bf16(x / 255)
     __shared__ __attribute__((aligned(16))) uint16_t s_rec[PH * 32 * 16]; // expanded records
     __shared__ __attribute__((aligned(16))) uint8_t s_stg[4 * 2 * 32 * OPIXB];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lx = lane & 31, hi = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63, lx = lane & 31, hi = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);          // uniform over the wave: keeps row indices scalar
 
     const int n_img = n_valid ? min((int)*n_valid, N) : N;
     const int tiles_x = (W + 31) / 32, tiles_y = (H + HEAD_TH - 1) / HEAD_TH, tiles_img = tiles_x * tiles_y;

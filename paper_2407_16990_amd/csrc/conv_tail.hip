@@ -23,7 +23,8 @@ __global__ __launch_bounds__(256) void k_conv_tail3(conv_args a, int tpb /* cons
     constexpr int KS = CIN / 16, PIXB = CIN * 2, PH = TH + 2, NQ = PH * TAIL_PW, NT = (NQ + 31) / 32, TPW = (NT + 3) / 4;
     constexpr int NPP = PIXB / 16, NPL = (NQ * NPP + 255) / 256;       // pieces per pixel, pieces per thread
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];      // NT * 32 rows of TAIL_PITCH bytes
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lx = lane & 31, hi = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63, lx = lane & 31, hi = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);          // uniform over the wave: keeps row indices scalar
 
     const int n_img = a.n_valid ? min((int)*a.n_valid, a.N) : a.N;
     const int tiles_x = (a.W + 31) / 32, tiles_y = (a.H + TH - 1) / TH, tiles_img = tiles_x * tiles_y;
