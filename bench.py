@@ -28,7 +28,7 @@ FP32_VALU_PEAK = 157.3e12  # fp32 vector ALUs, FLOP/s (MI355X published)
 # HBM bytes per launch of the dominant kernel class on the default workload, from the rocprofv3
 # FETCH_SIZE / WRITE_SIZE runs summarised in profiles/conv_mfma_cfg3_hbm_counters.md (scaled by
 # the plain-copy calibration); not measured live, so only reported for that workload.
-MEASURED_TRAFFIC = {"cfg3_16x480x272_edsr64_x4_bf16": 497.0e6}
+MEASURED_TRAFFIC = {"cfg3_16x480x272_edsr64_x4_bf16": 499.0e6}
 CONV_KERNEL = {64: "k_conv_mfma_duo<SKIP,RELU,10> (bf16-output 64-channel convs: ReLU, skip-add and plain instantiations)",
                32: "k_conv_mfma<32,1,16,false,SKIP,RELU> (bf16-output 32-channel convs)"}
 
