@@ -97,9 +97,9 @@ __global__ __launch_bounds__(256) void k_head_mfma(const uint8_t* __restrict__ i
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 float v0 = acc[m][4 * q], v1 = acc[m][4 * q + 1], v2 = acc[m][4 * q + 2], v3 = acc[m][4 * q + 3];
-                if (relu) { v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); v2 = fmaxf(v2, 0.f); v3 = fmaxf(v3, 0.f); }
                 uint2 pk;
                 pk.x = pack_bf16x2(v0, v1); pk.y = pack_bf16x2(v2, v3);
+                if (relu) { pk.x = relu_bf16x2(pk.x); pk.y = relu_bf16x2(pk.y); }
                 *(uint2*)(stg + (r * 32 + lx) * OPIXB + (((m * 4 + q) ^ okey) << 4) + hi * 8) = pk;
             }
     }

@@ -331,9 +331,9 @@ __global__ __launch_bounds__(256, MINB) void k_conv_mfma(conv_args a)
 #pragma unroll
                         for (int r = 0; r < RW; ++r) {
                             float v0 = acc[r][m][4 * q + 0], v1 = acc[r][m][4 * q + 1], v2 = acc[r][m][4 * q + 2], v3 = acc[r][m][4 * q + 3];
-                            if constexpr (RELU) { v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); v2 = fmaxf(v2, 0.f); v3 = fmaxf(v3, 0.f); }
                             uint2 pk;
                             pk.x = pack_bf16x2(v0, v1); pk.y = pack_bf16x2(v2, v3);
+                            if constexpr (RELU) { pk.x = relu_bf16x2(pk.x); pk.y = relu_bf16x2(pk.y); }
                             *(uint2*)(stg + (r * 32 + lx) * OPIXB + (((m * 4 + q) ^ okey) << 4) + hi * 8) = pk;
                         }
                 lds_barrier();                             // (D) staged values visible

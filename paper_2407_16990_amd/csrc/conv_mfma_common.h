@@ -32,6 +32,18 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b)
     return *(uint32_t*)&r;
 }
 
+// ReLU of two packed bf16 values: a negative float has its sign bit set, i.e. is a negative
+// 16-bit integer, and max(x, 0) on the integers leaves the others unchanged (-0 becomes +0).
+// One packed instruction per pair, against two v_max_f32 per value for fmaxf on the fp32 inputs
+// (the compiler adds a canonicalising max, also when the ReLU is written as a median of three).
+__device__ __forceinline__ uint32_t relu_bf16x2(uint32_t u)
+{
+    typedef short s16x2 __attribute__((ext_vector_type(2)));
+    const s16x2 z = {0, 0};
+    const s16x2 r = __builtin_elementwise_max(*(const s16x2*)&u, z);
+    return *(const uint32_t*)&r;
+}
+
 // Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every
 // outstanding global load and store of the wave, which would expose the latency of the patch
 // prefetch, the skip reads and the output stores once per tile.

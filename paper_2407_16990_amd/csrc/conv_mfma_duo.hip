@@ -318,13 +318,9 @@ __global__ __launch_bounds__(512) void k_conv_mfma_duo(conv_args a)
 #pragma unroll
                         for (int i = u * NLD / NUNIT; i < (u + 1) * NLD / NUNIT; ++i) issue_load(i);
                         float v0 = acc[r][m][4 * q + 0], v1 = acc[r][m][4 * q + 1], v2 = acc[r][m][4 * q + 2], v3 = acc[r][m][4 * q + 3];
-                        if constexpr (RELU) {       // one v_med3 each (fmaxf would add a canonicalising v_max)
-                            const float inf = __builtin_inff();
-                            v0 = __builtin_amdgcn_fmed3f(v0, 0.f, inf); v1 = __builtin_amdgcn_fmed3f(v1, 0.f, inf);
-                            v2 = __builtin_amdgcn_fmed3f(v2, 0.f, inf); v3 = __builtin_amdgcn_fmed3f(v3, 0.f, inf);
-                        }
                         uint2 pk;
                         pk.x = pack_bf16x2(v0, v1); pk.y = pack_bf16x2(v2, v3);
+                        if constexpr (RELU) { pk.x = relu_bf16x2(pk.x); pk.y = relu_bf16x2(pk.y); }   // rounding keeps the sign
                         *(uint2*)(stg + (r * 32 + lx) * OPIXB + (((m * 4 + q) ^ okey) << 4) + hi * 8) = pk;
                         __builtin_amdgcn_sched_barrier(0);
                     }
