@@ -458,12 +458,12 @@ template <int CIN, int MT, int TH, bool F32OUT, bool SKIP, bool RELU, int MINB =
 static hipError_t launch_conv(rh_ctx* ctx, const conv_args& a, int grid)
 {
     constexpr int lds = 9 * (CIN / 16) * MT * 1024 + (TH + 2) * PW * CIN * 2;
-    static bool attr_done = false;
-    if (!attr_done) {
+    static bool attr_done[RH_MAX_DEVICES] = {};            // the attribute is per device
+    if (!attr_done[ctx->device]) {
         hipError_t e = hipFuncSetAttribute((const void*)k_conv_mfma<CIN, MT, TH, F32OUT, SKIP, RELU, MINB>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (e != hipSuccess) return e;
-        attr_done = true;
+        attr_done[ctx->device] = true;
     }
     hipLaunchKernelGGL((k_conv_mfma<CIN, MT, TH, F32OUT, SKIP, RELU, MINB>), dim3(grid), dim3(256), lds, ctx->stream, a);
     return hipSuccess;
@@ -483,11 +483,11 @@ static rh_status conv(rh_ctx* ctx, const rh_layer& L, const __bf16* in, void* ou
     const int MT = last ? L.cout_pad / 32 : L.cin / 32;
     hipError_t e;
     // bf16-output convs come as (ReLU, no skip), (skip, no ReLU) or (neither)
-    if (last && L.tail3 && s_final == 1) e = rh_launch_conv_tail3(ctx->stream, a, L.cin);
+    if (last && L.tail3 && s_final == 1) e = rh_launch_conv_tail3(ctx->stream, ctx->device, a, L.cin);
     else if (last && L.tail3) RH_FAIL(ctx, RH_E_UNIMPLEMENTED, "3-channel last conv with a pixel shuffle");
     else if (L.cin == 64) {
         if (last) e = (MT == 2) ? launch_conv<64, 2, 16, true, false, false>(ctx, a, grid) : launch_conv<64, 1, 8, true, false, false, 2>(ctx, a, 2 * grid);
-        else e = rh_launch_conv_duo(ctx->stream, a, grid, skip != nullptr, relu != 0);    // two-team kernel
+        else e = rh_launch_conv_duo(ctx->stream, ctx->device, a, grid, skip != nullptr, relu != 0);    // two-team kernel
     } else {
         if (last) e = (MT == 2) ? launch_conv<32, 2, 16, true, false, false>(ctx, a, grid) : launch_conv<32, 1, 16, true, false, false>(ctx, a, grid);
         else if (skip) e = launch_conv<32, 1, 16, false, true, false>(ctx, a, grid);

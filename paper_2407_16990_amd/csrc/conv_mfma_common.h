@@ -56,9 +56,9 @@ __device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u 
 #define OOB_OFF 0x80000000u              // beyond any descriptor used here (images are < 2 GiB)
 
 // two-team kernel for the 64-channel bf16-output convs (conv_mfma_duo.hip)
-hipError_t rh_launch_conv_duo(hipStream_t stream, const conv_args& a, int grid, bool skip, bool relu);
+hipError_t rh_launch_conv_duo(hipStream_t stream, int device, const conv_args& a, int grid, bool skip, bool relu);
 // last conv with 3 output channels and no pixel shuffle (conv_tail.hip)
-hipError_t rh_launch_conv_tail3(hipStream_t stream, const conv_args& a, int cin);
+hipError_t rh_launch_conv_tail3(hipStream_t stream, int device, const conv_args& a, int cin);
 // first conv 3 -> C on the matrix cores (conv_head.hip)
 hipError_t rh_launch_head_mfma(hipStream_t stream, int C, const uint8_t* in, const uint4* wp, const float* bias, __bf16* out,
                                int N, int H, int W, int relu, const uint32_t* n_valid);

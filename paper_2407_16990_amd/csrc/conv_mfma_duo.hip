@@ -361,20 +361,20 @@ __global__ __launch_bounds__(512) void k_conv_mfma_duo(conv_args a)
 }
 
 template <bool SKIP, bool RELU, int MID>
-static hipError_t launch_duo(hipStream_t stream, const conv_args& a, int grid)
+static hipError_t launch_duo(hipStream_t stream, int device, const conv_args& a, int grid)
 {
     constexpr int lds = 9 * 4 * 2 * 1024 + 2 * 10 * PW * 128 + 256;
-    static bool attr_done = false;
-    if (!attr_done) {
+    static bool attr_done[RH_MAX_DEVICES] = {};            // the attribute is per device
+    if (!attr_done[device]) {
         hipError_t e = hipFuncSetAttribute((const void*)k_conv_mfma_duo<SKIP, RELU, MID>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (e != hipSuccess) return e;
-        attr_done = true;
+        attr_done[device] = true;
     }
     hipLaunchKernelGGL((k_conv_mfma_duo<SKIP, RELU, MID>), dim3(grid), dim3(512), lds, stream, a);
     return hipGetLastError();
 }
 
-hipError_t rh_launch_conv_duo(hipStream_t stream, const conv_args& a, int grid, bool skip, bool relu)
+hipError_t rh_launch_conv_duo(hipStream_t stream, int device, const conv_args& a, int grid, bool skip, bool relu)
 {
     // first barrier of the compute phase after 10 of the 12 steps (A/B on one box: 0.7 % better than 11, 9 is worse)
 #ifndef DUO_MID_SKIP
@@ -383,7 +383,7 @@ hipError_t rh_launch_conv_duo(hipStream_t stream, const conv_args& a, int grid, 
 #ifndef DUO_MID_PLAIN
 #define DUO_MID_PLAIN 10
 #endif
-    if (skip) return launch_duo<true, false, DUO_MID_SKIP>(stream, a, grid);
-    if (relu) return launch_duo<false, true, DUO_MID_PLAIN>(stream, a, grid);
-    return launch_duo<false, false, DUO_MID_PLAIN>(stream, a, grid);
+    if (skip) return launch_duo<true, false, DUO_MID_SKIP>(stream, device, a, grid);
+    if (relu) return launch_duo<false, true, DUO_MID_PLAIN>(stream, device, a, grid);
+    return launch_duo<false, false, DUO_MID_PLAIN>(stream, device, a, grid);
 }

@@ -114,14 +114,14 @@ __global__ __launch_bounds__(256) void k_conv_tail3(conv_args a, int tpb /* cons
 }
 
 template <int CIN, int TH>
-static hipError_t launch_tail(hipStream_t stream, const conv_args& a)
+static hipError_t launch_tail(hipStream_t stream, int device, const conv_args& a)
 {
     constexpr int NQ = (TH + 2) * TAIL_PW, NT = (NQ + 31) / 32, lds = NT * 32 * TAIL_PITCH;
-    static bool attr_done = false;
-    if (!attr_done) {
+    static bool attr_done[RH_MAX_DEVICES] = {};            // the attribute is per device
+    if (!attr_done[device]) {
         hipError_t e = hipFuncSetAttribute((const void*)k_conv_tail3<CIN, TH>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (e != hipSuccess) return e;
-        attr_done = true;
+        attr_done[device] = true;
     }
     const long long tiles = (long long)a.N * ((a.H + TH - 1) / TH) * ((a.W + 31) / 32);
     // several consecutive tiles per workgroup once there are enough tiles to fill the chip
@@ -135,9 +135,9 @@ static hipError_t launch_tail(hipStream_t stream, const conv_args& a)
 
 // a.wp: [CIN/16][64 lanes][8] bf16 with row m = lane % 32 = tap*3 + co (rows 27..31 zero) and
 // ci = 16*ks + 8*(lane/32) + e;  a.bias: 3 floats.
-hipError_t rh_launch_conv_tail3(hipStream_t stream, const conv_args& a, int cin)
+hipError_t rh_launch_conv_tail3(hipStream_t stream, int device, const conv_args& a, int cin)
 {
-    if (cin == 64) return launch_tail<64, 8>(stream, a);
-    if (cin == 32) return launch_tail<32, 8>(stream, a);
+    if (cin == 64) return launch_tail<64, 8>(stream, device, a);
+    if (cin == 32) return launch_tail<32, 8>(stream, device, a);
     return hipErrorInvalidValue;
 }

@@ -269,10 +269,11 @@ __global__ __launch_bounds__(256) void k_plan_emit(const rh_rawbox* __restrict__
 
 rh_status rh_plan_init(rh_ctx* ctx)
 {
-    // both planning kernels may need more dynamic LDS than the default limit
-    RH_HIP(ctx, hipFuncSetAttribute((const void*)k_plan_label, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    ctx->per * ((size_t)ctx->per * 20 <= 150 * 1024 ? 20 : 16)));
-    RH_HIP(ctx, hipFuncSetAttribute((const void*)k_plan_place, hipFuncAttributeMaxDynamicSharedMemorySize, ctx->free_cap * 12));
+    // Both planning kernels may need more dynamic LDS than the default limit.  The attribute belongs
+    // to the kernel, not to the context: it is raised to what the largest admissible context needs
+    // (rh_create bounds both sizes below 150 KB), so contexts of different sizes can coexist.
+    RH_HIP(ctx, hipFuncSetAttribute((const void*)k_plan_label, hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024));
+    RH_HIP(ctx, hipFuncSetAttribute((const void*)k_plan_place, hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024));
     return RH_OK;
 }
 

@@ -96,6 +96,7 @@ extern "C" rh_status rh_create(const rh_config* cfg, const float* weights, size_
     rh_status st = RH_OK;
     hipError_t e = hipGetDevice(&ctx->device);
 #define A(call) if (e == hipSuccess) e = (call)
+    if (e == hipSuccess && (ctx->device < 0 || ctx->device >= RH_MAX_DEVICES)) { delete ctx; return RH_E_DEVICE; }
     A(hipDeviceGetAttribute(&ctx->n_cu, hipDeviceAttributeMultiprocessorCount, ctx->device));
     if (e == hipSuccess && ctx->n_cu < 1) ctx->n_cu = 1;
     A(dalloc(&ctx->w_f32, n_floats));

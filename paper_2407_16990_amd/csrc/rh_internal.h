@@ -9,6 +9,7 @@
 
 #define RH_MB 16
 #define RH_NO_BIN 0xFFFFu
+#define RH_MAX_DEVICES 64     // device indexes a context may live on (per-device launch attributes)
 
 struct rh_layer {
     int cin, cout;          // true channel counts

@@ -77,6 +77,22 @@ def test_metadata_and_bytes_at_full_size(ci):
     rh.close()
 
 
+def test_contexts_of_different_sizes_coexist():
+    """A small context created after a large one must not shrink what the large one may launch:
+    the planning kernels' shared-memory limit belongs to the kernel, not to a context."""
+    big, small = wl.config(5), wl.config(1)
+    net = wl.Net("plain", 4, 2, 2)
+    blob = wl.make_weights(net, 0, "fp32")
+    rh_big = make_rh(wl.replace(big, net=wl.Net("plain", 4, 2, big.net.scale)),
+                     wl.make_weights(wl.Net("plain", 4, 2, big.net.scale), 0, "fp32"), precision="fp32")
+    rh_small = make_rh(wl.replace(small, net=net), blob, precision="fp32")
+    check_select_and_plan(rh_small, small, wl.make_frames(small), wl.make_importance(small), wl.make_segments(small))
+    check_select_and_plan(rh_big, big, wl.make_frames(big), wl.make_importance(big), wl.make_segments(big))
+    check_select_and_plan(rh_small, small, wl.make_frames(small), wl.make_importance(small), wl.make_segments(small))
+    rh_big.close()
+    rh_small.close()
+
+
 @pytest.mark.parametrize("frac,kind", [(0.05, "clustered"), (0.5, "clustered"), (1.0, "clustered"),
                                        (0.1, "uniform"), (0.2, "uniform"), (0.5, "uniform")])
 def test_sweep_metadata(frac, kind):
