@@ -20,6 +20,11 @@
  * the packing heuristic has no printed example in the paper: plan equality is
  * "parity unpinned" with respect to the paper and pinned only to the
  * determinism rules documented in the design notes.
+ *
+ * The inverse-area operator of the temporal importance reuse (Sec. 3.2.2, orc_phi at the end of
+ * the file) is pinned by hand cases and a library labelling routine
+ * (tests/test_oracle_temporal.py); its formula is a reading of the paper, which prints none:
+ * "parity unpinned" with respect to the paper.
  */
 #include <math.h>
 #include <stdint.h>
@@ -548,4 +553,54 @@ void orc_unpack(const uint8_t* frames_lr, int F, int H, int W, int s,
             frames_hr[di] = (uint8_t)floorf(q);
         }
     }
+}
+
+/* ------------------------------------------------------------------------ */
+/* Temporal importance reuse (Sec. 3.2.2): the inverse-area operator Phi on the luma residual
+ * of each frame.  The paper names the operator and what it responds to (small changed objects,
+ * where the plain area feature responds to large ones) but prints no formula; the reading taken:
+ *   1. a pixel has changed when |residual| > tau;
+ *   2. blobs are the 8-connected components of the changed pixels of one frame (the same
+ *      neighbourhood as the region labelling of Alg. 1);
+ *   3. Phi = sum over blobs with area >= min_area of 1 / area.
+ * Phi is kept as an integer in units of 2^-32, each term floor(2^32 / area): the frame choice
+ * that follows compares sums of these values, and integer sums do not depend on the order the
+ * blobs are met in.  res: int16 [F][H][W].  phi_q32: uint64 [F].  n_blobs (optional): int32 [F],
+ * the number of blobs counted (after the min_area filter).
+ * Plain flood fill with an explicit stack, one frame after the other. */
+void orc_phi(const int16_t* res, int F, int H, int W, int tau, int min_area,
+             uint64_t* phi_q32, int32_t* n_blobs)
+{
+    size_t per = (size_t)H * W;
+    uint8_t* seen = (uint8_t*)malloc(per ? per : 1);
+    int32_t* stack = (int32_t*)malloc(sizeof(int32_t) * (per ? per : 1));
+    for (int f = 0; f < F; ++f) {
+        const int16_t* r = res + f * per;
+        memset(seen, 0, per);
+        uint64_t phi = 0;
+        int32_t nb = 0;
+        for (int y0 = 0; y0 < H; ++y0) for (int x0 = 0; x0 < W; ++x0) {
+            size_t p0 = (size_t)y0 * W + x0;
+            if (seen[p0] || abs((int)r[p0]) <= tau) continue;
+            int top = 0;
+            long area = 0;
+            stack[top++] = (int32_t)p0; seen[p0] = 1;
+            while (top) {
+                int32_t p = stack[--top];
+                ++area;
+                int y = p / W, x = p % W;
+                for (int dy = -1; dy <= 1; ++dy) for (int dx = -1; dx <= 1; ++dx) {
+                    int yy = y + dy, xx = x + dx;
+                    if ((dy == 0 && dx == 0) || yy < 0 || yy >= H || xx < 0 || xx >= W) continue;
+                    size_t q = (size_t)yy * W + xx;
+                    if (seen[q] || abs((int)r[q]) <= tau) continue;
+                    seen[q] = 1; stack[top++] = (int32_t)q;
+                }
+            }
+            if (area >= min_area) { phi += ((uint64_t)1 << 32) / (uint64_t)area; ++nb; }
+        }
+        phi_q32[f] = phi;
+        if (n_blobs) n_blobs[f] = nb;
+    }
+    free(seen); free(stack);
 }

@@ -240,3 +240,45 @@ def make_segments(cfg: Config, n_frames: int | None = None) -> np.ndarray:
         fr = rng.uniform(*cfg.frac_range)
         segs.append([s * fps, (s + 1) * fps, int(np.floor(fr * fps * per))])
     return np.array(segs, dtype=np.uint32)
+
+
+def make_residuals(width: int, height: int, n_streams: int, frames_per_stream: int, seed: int = 0,
+                   noise_sigma: float = 3.0, n_objects=(2, 8), scene_change_prob: float = 0.05) -> np.ndarray:
+    """Synthetic luma residuals of decoded chunks, int16 [n_streams * frames_per_stream, H, W].
+
+    Stands in for the codec's Y residual of the paper's 360p streams (Sec. 3.2.2), which are not
+    available: low-amplitude noise everywhere (quantisation error), a few small moving objects
+    per stream whose residual is strong where they moved (rectangles of 3..40 pixels a side that
+    drift, appear and vanish over the chunk), now and then a frame in which a large part of the
+    picture changes (a cut or a pan), and isolated strong pixels.  Streams differ in how busy
+    they are.  Holds none of the method's arithmetic.
+    """
+    rng = np.random.Generator(np.random.PCG64(77_000 + seed))
+    F = n_streams * frames_per_stream
+    res = np.rint(rng.normal(0.0, noise_sigma, size=(F, height, width))).astype(np.int16)
+    for s in range(n_streams):
+        k = int(rng.integers(n_objects[0], n_objects[1] + 1))
+        pos = rng.uniform([0, 0], [width, height], size=(k, 2))
+        vel = rng.normal(0.0, 2.0 + 3.0 * rng.random(), size=(k, 2))
+        size = rng.integers(3, 41, size=(k, 2))
+        alive = rng.random(k) < 0.7
+        for t in range(frames_per_stream):
+            f = s * frames_per_stream + t
+            flip = rng.random(k) < 0.08
+            alive = np.where(flip, ~alive, alive)
+            pos = (pos + vel) % [width, height]
+            for j in range(k):
+                if not alive[j]:
+                    continue
+                x0, y0 = int(pos[j, 0]), int(pos[j, 1])
+                x1, y1 = min(width, x0 + int(size[j, 0])), min(height, y0 + int(size[j, 1]))
+                amp = rng.integers(25, 90)
+                tex = rng.random((y1 - y0, x1 - x0)) < 0.85          # objects are not solid masks
+                res[f, y0:y1, x0:x1] += (tex * amp * rng.choice([-1, 1])).astype(np.int16)
+            if rng.random() < scene_change_prob:
+                y0 = int(rng.integers(0, height // 2)); x0 = int(rng.integers(0, width // 2))
+                res[f, y0:y0 + height // 2, x0:x0 + width // 2] += np.int16(rng.integers(30, 70))
+            n_hot = int(rng.integers(0, 30))
+            ys, xs = rng.integers(0, height, n_hot), rng.integers(0, width, n_hot)
+            res[f, ys, xs] += np.int16(60)
+    return np.clip(res, -255, 255).astype(np.int16)
