@@ -213,8 +213,61 @@ rh_status rh_identity_places(rh_ctx* ctx, int32_t F, rh_mbplace* places, uint32_
 rh_status rh_read_counts(rh_ctx* ctx, const uint32_t* counts, uint32_t out[4]);
 
 /*
- * Measurement aid (not part of the method): when enabled, the kernel launches of the four
- * calls are bracketed by HIP events on the context's stream, one event pair around each run of
+ * Temporal importance reuse (Sec. 3.2.2): predict the importance map only on the frames of a chunk
+ * where a cheap feature of the codec's luma residual changes most, and let the other frames reuse
+ * the map of such a frame.  Three calls, all asynchronous on the context's stream.
+ *
+ * rh_temporal_phi: the inverse-area operator Phi of every frame.  The paper names the operator and
+ * what it reacts to (small changed objects) without a formula; as built: a pixel has changed when
+ * |residual| > tau, blobs are the 8-connected sets of changed pixels of one frame, and
+ * Phi = sum over blobs of at least min_area pixels of 1/area, kept exactly as the integer
+ * sum of floor(2^32 / area) (order-independent, so the frame choice below is reproducible).
+ *   res_y (dev): int16 [F][frame_h][frame_w], the Y residual of each frame, F <= max_frames of
+ *   the context.  tau >= 0, min_area >= 1.  phi (dev out): uint64 [F].
+ * Uses the context's workspace (8 bytes per pixel; grows like rh_enhance's); F*frame_h*frame_w must
+ * stay below 2^31 (RH_E_SHAPE).
+ */
+rh_status rh_temporal_phi(rh_ctx* ctx, const int16_t* res_y, int32_t F, int32_t tau, int32_t min_area,
+                          uint64_t* phi);
+
+/*
+ * rh_temporal_select: the frame choice.  stream_off (host): int32 [n_streams + 1], ascending,
+ * stream s owns frames [stream_off[s], stream_off[s+1]) of the batch (at least 1, at most 2048
+ * frames each; stream_off[0] = 0, stream_off[n_streams] = F; n_streams <= 1024).  Per stream, with
+ * S_i = |Phi_{i+1} - Phi_i| L1-normalised over the chunk, frame f sits at position
+ * P_f = S_0 + ... + S_{f-1} of the cumulative distribution (all 0 when nothing changed); [0,1] is
+ * cut into N_s equal intervals, frame f lies in interval min(N_s - 1, floor(N_s * P_f)), and in
+ * every interval that holds a frame the frame nearest the interval's midpoint (the earliest of
+ * equally near ones) is predicted while the others reuse it.  The budget n_total (frames to
+ * predict over all streams, n_streams <= n_total <= 65535) is shared out as one frame per stream
+ * plus the rest in proportion to the streams' total change sum_i S_i before normalisation
+ * (largest remainders, ties to the lower stream, equal shares if nothing changed anywhere).
+ * All comparisons are exact integer arithmetic; F * (frame_h/2 + 1) * (frame_w/2 + 1) must stay
+ * below 2^31 so that no sum of changes can pass 2^63 (RH_E_SHAPE otherwise).
+ *   phi (dev): uint64 [F] as written by rh_temporal_phi.
+ *   alloc (dev out): uint32 [n_streams], N_s.   selected (dev out): u8 [F], 1 = predict this frame.
+ *   reuse_from (dev out): uint32 [F], the batch-wide index of the frame whose map frame f uses
+ *   (itself for a predicted frame; never a frame of another stream).
+ *   n_selected (dev out): uint32 [1], number of frames to predict (<= n_total: an interval that
+ *   holds no frame selects nothing).
+ */
+rh_status rh_temporal_select(rh_ctx* ctx, const uint64_t* phi, const int32_t* stream_off, int32_t n_streams,
+                             int32_t n_total, uint32_t* alloc, uint8_t* selected, uint32_t* reuse_from,
+                             uint32_t* n_selected);
+
+/*
+ * rh_temporal_spread: the reuse itself.  importance (dev, in/out): f32 [F][MBH][MBW] holding valid
+ * maps at the predicted frames; every other frame f receives a copy of frame reuse_from[f]'s map.
+ * The result is what rh_select_regions takes.  selected / reuse_from as written by
+ * rh_temporal_select (entries that point outside [0, F) or at a frame that is not predicted leave
+ * frame f untouched).
+ */
+rh_status rh_temporal_spread(rh_ctx* ctx, float* importance, int32_t F, const uint8_t* selected,
+                             const uint32_t* reuse_from);
+
+/*
+ * Measurement aid (not part of the method): when enabled, the kernel launches of the
+ * calls above are bracketed by HIP events on the context's stream, one event pair around each run of
  * consecutive launches of a class (no event is placed between back-to-back launches).
  * rh_profile_read synchronises, adds up the elapsed times and launch counts since the last
  * read into ms[RH_PROF_N] / launches[RH_PROF_N] (host arrays) and resets them.
@@ -222,7 +275,7 @@ rh_status rh_read_counts(rh_ctx* ctx, const uint32_t* counts, uint32_t out[4]);
  * upsampling convs), the kernel that dominates the path; with RH_FP32 it covers all layers.
  */
 enum { RH_PROF_SELECT = 0, RH_PROF_PLAN = 1, RH_PROF_GATHER = 2, RH_PROF_HEAD = 3, RH_PROF_CONV = 4,
-       RH_PROF_CONV_LAST = 5, RH_PROF_UNPACK = 6, RH_PROF_N = 7 };
+       RH_PROF_CONV_LAST = 5, RH_PROF_UNPACK = 6, RH_PROF_TEMPORAL = 7, RH_PROF_N = 8 };
 rh_status rh_profile_enable(rh_ctx* ctx, int32_t on);
 rh_status rh_profile_read(rh_ctx* ctx, double* ms, uint32_t* launches);
 

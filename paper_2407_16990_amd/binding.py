@@ -18,7 +18,7 @@ MODE = {"topk": 0, "threshold": 1}
 STATUS = ["RH_OK", "RH_E_INVALID", "RH_E_SHAPE", "RH_E_CAPACITY", "RH_E_DEVICE", "RH_E_NOMEM", "RH_E_STATE",
           "RH_E_UNIMPLEMENTED"]
 
-PROF_CLASSES = ["select", "plan", "gather", "head", "conv", "conv_last", "unpack"]
+PROF_CLASSES = ["select", "plan", "gather", "head", "conv", "conv_last", "unpack", "temporal"]
 PROF_N = len(PROF_CLASSES)
 
 BOX_DTYPE = np.dtype([("frame", "<u4"), ("mbx0", "<u2"), ("mby0", "<u2"), ("wmb", "u1"), ("hmb", "u1"),
@@ -83,6 +83,9 @@ def load_library():
     L.rh_unpack.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, i32, vp, vp]
     L.rh_identity_places.argtypes = [vp, i32, vp, vp]
     L.rh_read_counts.argtypes = [vp, vp, C.POINTER(C.c_uint32 * 4)]
+    L.rh_temporal_phi.argtypes = [vp, vp, i32, i32, i32, vp]
+    L.rh_temporal_select.argtypes = [vp, vp, C.POINTER(i32), i32, i32, vp, vp, vp, vp]
+    L.rh_temporal_spread.argtypes = [vp, vp, i32, vp, vp]
     L.rh_profile_enable.argtypes = [vp, i32]
     L.rh_profile_read.argtypes = [vp, C.POINTER(C.c_double * PROF_N), C.POINTER(C.c_uint32 * PROF_N)]
     L.rh_probe_mfma.argtypes = [vp, C.c_int32, C.c_double, C.POINTER(C.c_double * 3)]
@@ -217,6 +220,35 @@ class RH:
         n = torch.zeros(1, dtype=torch.int32, device=self.device)
         self._check(self.lib.rh_identity_places(self.h, F, _ptr(places), _ptr(n)))
         return places, n
+
+    def temporal_phi(self, res_y: torch.Tensor, tau: int, min_area: int = 1, out: torch.Tensor | None = None):
+        """res_y int16 [F,H,W] -> Phi in units of 2^-32, int64 [F] (the bits of the library's uint64)."""
+        assert res_y.dtype == torch.int16 and res_y.is_contiguous()
+        F = res_y.shape[0]
+        assert tuple(res_y.shape[1:]) == (self.cfg.frame_h, self.cfg.frame_w)
+        if out is None:
+            out = torch.empty(F, dtype=torch.int64, device=self.device)
+        self._check(self.lib.rh_temporal_phi(self.h, _ptr(res_y), F, int(tau), int(min_area), _ptr(out)))
+        return out
+
+    def temporal_select(self, phi: torch.Tensor, stream_off, n_total: int):
+        """-> (alloc int32 [n_streams], selected u8 [F], reuse_from int32 [F], n_selected int32 [1])."""
+        ns = len(stream_off) - 1
+        off = (C.c_int32 * (ns + 1))(*[int(v) for v in stream_off])
+        F = phi.shape[0]
+        alloc = torch.zeros(max(ns, 1), dtype=torch.int32, device=self.device)
+        selected = torch.zeros(F, dtype=torch.uint8, device=self.device)
+        reuse = torch.zeros(F, dtype=torch.int32, device=self.device)
+        n_sel = torch.zeros(1, dtype=torch.int32, device=self.device)
+        self._check(self.lib.rh_temporal_select(self.h, _ptr(phi), off, ns, int(n_total), _ptr(alloc), _ptr(selected),
+                                                _ptr(reuse), _ptr(n_sel)))
+        return alloc, selected, reuse, n_sel
+
+    def temporal_spread(self, importance: torch.Tensor, selected: torch.Tensor, reuse_from: torch.Tensor):
+        """In place: frames that are not predicted take the map of the frame they reuse."""
+        assert importance.dtype == torch.float32 and importance.is_contiguous()
+        self._check(self.lib.rh_temporal_spread(self.h, _ptr(importance), importance.shape[0], _ptr(selected), _ptr(reuse_from)))
+        return importance
 
     def read_counts(self, counts: torch.Tensor):
         out = (C.c_uint32 * 4)()

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librh.so")
 SOURCES = ["rh_api.hip", "select.hip", "plan.hip", "pack.hip", "unpack.hip", "conv_fp32.hip", "conv_mfma.hip",
-           "conv_mfma_duo.hip", "conv_tail.hip", "conv_head.hip", "probe.hip"]
+           "conv_mfma_duo.hip", "conv_tail.hip", "conv_head.hip", "probe.hip", "temporal.hip"]
 
 
 def build(verbose: bool = False) -> str:

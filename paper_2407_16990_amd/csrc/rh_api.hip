@@ -57,7 +57,7 @@ extern "C" void rh_destroy(rh_ctx* ctx)
     for (hipEvent_t e : ctx->prof_pool) (void)hipEventDestroy(e);
     void* ptrs[] = {ctx->w_f32, ctx->wpack, ctx->bpack, ctx->frame_seg, ctx->seg_par, ctx->seg_T, ctx->seg_budget,
                     ctx->frame_nsel, ctx->frame_ties, ctx->owner_id, ctx->rank_of_id, ctx->raw, ctx->sorted,
-                    ctx->pcount, ctx->slot_of_mb, ctx->act};
+                    ctx->pcount, ctx->slot_of_mb, ctx->tr_off, ctx->tr_A, ctx->tr_T, ctx->act};
     for (void* p : ptrs) if (p) (void)hipFree(p);
     delete ctx;
 }
@@ -107,6 +107,7 @@ extern "C" rh_status rh_create(const rh_config* cfg, const float* weights, size_
     A(dalloc(&ctx->owner_id, total)); A(dalloc(&ctx->rank_of_id, total));
     A(dalloc(&ctx->raw, total)); A(dalloc(&ctx->sorted, total));
     A(dalloc(&ctx->pcount, 8 + 2 * total)); A(dalloc(&ctx->slot_of_mb, total));
+    A(dalloc(&ctx->tr_off, (size_t)cfg->max_frames + 1)); A(dalloc(&ctx->tr_A, cfg->max_frames)); A(dalloc(&ctx->tr_T, cfg->max_frames));
 #undef A
     if (e != hipSuccess) {
         snprintf(ctx->err, sizeof(ctx->err), "rh_create: %s", hipGetErrorString(e));
@@ -205,6 +206,49 @@ extern "C" rh_status rh_select_regions(rh_ctx* ctx, const float* importance, int
     rh_status st = rh_upload_segments(ctx, segs, nseg, F);
     if (st != RH_OK) return st;
     return rh_launch_select(ctx, importance, F, nseg, mode, mask, list, n_sel);
+}
+
+extern "C" rh_status rh_temporal_phi(rh_ctx* ctx, const int16_t* res_y, int32_t F, int32_t tau, int32_t min_area,
+                                     uint64_t* phi)
+{
+    if (!ctx) return RH_E_INVALID;
+    if (!res_y || !phi) RH_FAIL(ctx, RH_E_INVALID, "rh_temporal_phi: null argument");
+    if (F < 1 || F > ctx->cfg.max_frames) RH_FAIL(ctx, RH_E_CAPACITY, "rh_temporal_phi: F=%d outside [1,%d]", F, ctx->cfg.max_frames);
+    if (tau < 0 || min_area < 1) RH_FAIL(ctx, RH_E_INVALID, "rh_temporal_phi: tau=%d must be >= 0 and min_area=%d >= 1", tau, min_area);
+    return rh_launch_temporal_phi(ctx, res_y, F, tau, min_area, phi);
+}
+
+extern "C" rh_status rh_temporal_select(rh_ctx* ctx, const uint64_t* phi, const int32_t* stream_off, int32_t n_streams,
+                                        int32_t n_total, uint32_t* alloc, uint8_t* selected, uint32_t* reuse_from,
+                                        uint32_t* n_selected)
+{
+    if (!ctx) return RH_E_INVALID;
+    if (!phi || !stream_off || !alloc || !selected || !reuse_from || !n_selected)
+        RH_FAIL(ctx, RH_E_INVALID, "rh_temporal_select: null argument");
+    if (n_streams < 1 || n_streams > 1024) RH_FAIL(ctx, RH_E_CAPACITY, "rh_temporal_select: %d streams outside [1,1024]", n_streams);
+    if (n_total < n_streams || n_total > 65535)
+        RH_FAIL(ctx, RH_E_INVALID, "rh_temporal_select: a budget of %d frames is outside [%d streams, 65535]", n_total, n_streams);
+    if (stream_off[0] != 0) RH_FAIL(ctx, RH_E_INVALID, "rh_temporal_select: stream_off[0] must be 0");
+    for (int s = 0; s < n_streams; ++s) {
+        const long n = (long)stream_off[s + 1] - stream_off[s];
+        if (n < 1 || n > 2048) RH_FAIL(ctx, RH_E_INVALID, "rh_temporal_select: stream %d has %ld frames, outside [1,2048]", s, n);
+    }
+    const int F = stream_off[n_streams];
+    if (F > ctx->cfg.max_frames) RH_FAIL(ctx, RH_E_CAPACITY, "rh_temporal_select: %d frames exceed max_frames=%d", F, ctx->cfg.max_frames);
+    // Phi <= 2^32 * (most blobs a frame can hold); all sums of changes must stay below 2^63
+    const uint64_t blobs = (uint64_t)(ctx->cfg.frame_h / 2 + 1) * (uint64_t)(ctx->cfg.frame_w / 2 + 1);
+    if ((uint64_t)F * blobs >= (1ull << 31))
+        RH_FAIL(ctx, RH_E_SHAPE, "rh_temporal_select: %d frames of %dx%d could overflow the 64-bit sums", F, ctx->cfg.frame_w, ctx->cfg.frame_h);
+    return rh_launch_temporal_select(ctx, phi, stream_off, n_streams, n_total, alloc, selected, reuse_from, n_selected);
+}
+
+extern "C" rh_status rh_temporal_spread(rh_ctx* ctx, float* importance, int32_t F, const uint8_t* selected,
+                                        const uint32_t* reuse_from)
+{
+    if (!ctx) return RH_E_INVALID;
+    if (!importance || !selected || !reuse_from) RH_FAIL(ctx, RH_E_INVALID, "rh_temporal_spread: null argument");
+    if (F < 1 || F > ctx->cfg.max_frames) RH_FAIL(ctx, RH_E_CAPACITY, "rh_temporal_spread: F=%d outside [1,%d]", F, ctx->cfg.max_frames);
+    return rh_launch_temporal_spread(ctx, importance, F, selected, reuse_from);
 }
 
 extern "C" rh_status rh_pack(rh_ctx* ctx, const uint8_t* frames, int32_t F, const float* importance,

@@ -70,6 +70,10 @@ struct rh_ctx {
     uint32_t* pcount;       // [8] plan counters: 0 n_raw boxes
     // unpack scratch
     int32_t* slot_of_mb;    // [total MBs] index into places or -1
+    // temporal reuse scratch (dev)
+    int32_t* tr_off;        // [max_frames + 1] first frame of each stream
+    uint64_t* tr_A;         // [max_frames] cumulative change before each frame
+    uint64_t* tr_T;         // [max_frames] total change of each stream
     // exact-border mode: the boxes of the bins being enhanced (set for the duration of one
     // rh_enhance_exact call, null otherwise)
     const rh_box* bz_boxes;
@@ -108,6 +112,11 @@ rh_status rh_launch_unpack(rh_ctx*, const float* enh, int n_img, int ih, int iw,
                            const rh_mbplace* places, const uint32_t* n_places,
                            const uint8_t* lr, int F, uint8_t* hr, float* sel);
 rh_status rh_launch_identity_places(rh_ctx*, int F, rh_mbplace* places, uint32_t* n_places);
+rh_status rh_launch_temporal_phi(rh_ctx*, const int16_t* res, int F, int tau, int min_area, uint64_t* phi);
+rh_status rh_launch_temporal_select(rh_ctx*, const uint64_t* phi, const int32_t* stream_off, int n_streams,
+                                    int n_total, uint32_t* alloc, uint8_t* selected, uint32_t* reuse_from,
+                                    uint32_t* n_selected);
+rh_status rh_launch_temporal_spread(rh_ctx*, float* imp, int F, const uint8_t* selected, const uint32_t* reuse_from);
 rh_status rh_pack_weights_bf16(rh_ctx*, const float* host_blob);
 rh_status rh_upload_segments(rh_ctx*, const rh_segment* segs, int nseg, int F);
 rh_status rh_plan_init(rh_ctx*);
