@@ -86,6 +86,10 @@ def main():
     ap.add_argument("--mem-batch", type=int, default=16, metavar="X",
                     help="also time the memory-bound steps (pack gather, unpack) on X copies of the batch, where "
                          "they are large enough to be bandwidth- rather than launch-bound (0 = skip)")
+    ap.add_argument("--no-temporal", action="store_true",
+                    help="skip the temporal importance reuse leg (Sec. 3.2.2; reported beside the path, not in `value`)")
+    ap.add_argument("--temporal-streams", type=int, default=10, help="streams of the temporal leg's chunk")
+    ap.add_argument("--temporal-frames", type=int, default=30, help="frames per stream of the temporal leg's chunk")
     ap.add_argument("--sync-counts", action="store_true",
                     help="read the bin count back to the host after rh_pack (one synchronisation per step) and "
                          "enhance exactly that many bins, instead of passing the device-side count")
@@ -243,6 +247,51 @@ def main():
             "pack_gather": {"bytes": xpb, "us": xprof["gather"][0] / reps * 1e3, "GB/s": xpb / (xprof["gather"][0] / reps * 1e-3) / 1e9},
             "unpack": {"bytes": xub, "us": xprof["unpack"][0] / reps * 1e3, "GB/s": xub / (xprof["unpack"][0] / reps * 1e-3) / 1e9}}
         del rhx, xf, xi, xhr, xnet, xpo
+
+    if not args.no_temporal:
+        # Temporal importance reuse (Sec. 3.2.2) on one chunk of every stream: which frames get a
+        # predicted importance map.  It runs before the path and is reported beside it.
+        ns, fps = args.temporal_streams, args.temporal_frames
+        tF, tau, min_area = ns * fps, 12, 2
+        budget = max(ns, tF // 5)
+        res = wl.make_residuals(cfg.width, cfg.height, ns, fps, seed=cfg.index)
+        rht = RH(frame_w=cfg.width, frame_h=cfg.height, max_frames=tF, halo=cfg.halo, bin_size=cfg.bin_size,
+                 max_bins=4, net=cfg.net, weights=blob, precision=cfg.precision)
+        d_res = torch.from_numpy(res).cuda()
+        t_imp = torch.zeros((tF, rht.mbh, rht.mbw), dtype=torch.float32, device="cuda")
+        off = [fps * i for i in range(ns + 1)]
+        d_phi = torch.empty(tF, dtype=torch.int64, device="cuda")
+        reps, t_us = 10, {}
+        for it in range(2):                                           # first round untimed
+            rht.profile_enable(it == 1)
+            for _ in range(reps):
+                rht.temporal_phi(d_res, tau, min_area, out=d_phi)
+            if it: t_us["phi"] = rht.profile_read()["temporal"][0] / reps * 1e3
+            for _ in range(reps):
+                t_alloc, t_sel, t_reuse, t_n = rht.temporal_select(d_phi, off, budget)
+            if it: t_us["select"] = rht.profile_read()["temporal"][0] / reps * 1e3
+            for _ in range(reps):
+                rht.temporal_spread(t_imp, t_sel, t_reuse)
+            if it: t_us["spread"] = rht.profile_read()["temporal"][0] / reps * 1e3
+        n_pred = int(t_n.cpu()[0])
+        phi_bytes = tF * cfg.height * cfg.width * 2 + tF * 8          # residuals read once, Phi written
+        spread_bytes = (tF - n_pred) * rht.mbh * rht.mbw * 4 * 2
+        result["temporal_reuse"] = {
+            "workload": f"{ns} streams x {fps} frames of {cfg.width}x{cfg.height} luma residuals, tau={tau}, min_area={min_area}, budget={budget}",
+            "frames": tF, "frames_predicted": n_pred, "us": t_us,
+            "phi": {"bound": "hbm", "bytes": phi_bytes, "GB/s": phi_bytes / (t_us["phi"] * 1e-6) / 1e9, "peak": 8000.0,
+                    "frac": phi_bytes / (t_us["phi"] * 1e-6) / 1e9 / 8000.0},
+            "spread_GB/s": spread_bytes / max(t_us["spread"] * 1e-6, 1e-12) / 1e9}
+        if not args.no_cpu_baseline:
+            from oracle import temporal as OT
+            sub = res[: min(tF, 60)]
+            t0 = time.perf_counter()
+            o_phi, _ = OT.phi(sub, tau, min_area)
+            t1 = time.perf_counter()
+            assert np.array_equal(d_phi.cpu().numpy().view(np.uint64)[: len(sub)], o_phi), "temporal leg: Phi differs from the oracle"
+            result["temporal_reuse"]["cpu_oracle"] = {"phi_us_per_frame": (t1 - t0) / len(sub) * 1e6, "cores": 1,
+                                                      "sample": f"{len(sub)} frames"}
+        del rht, d_res
 
     if args.policy_study > 0:
         pols = {"density": dict(), "density+rotate": dict(rotate=True), "area": dict(sort_policy="area"),

@@ -224,7 +224,7 @@ rh_status rh_read_counts(rh_ctx* ctx, const uint32_t* counts, uint32_t out[4]);
  * sum of floor(2^32 / area) (order-independent, so the frame choice below is reproducible).
  *   res_y (dev): int16 [F][frame_h][frame_w], the Y residual of each frame, F <= max_frames of
  *   the context.  tau >= 0, min_area >= 1.  phi (dev out): uint64 [F].
- * Uses the context's workspace (8 bytes per pixel; grows like rh_enhance's); F*frame_h*frame_w must
+ * Uses the context's workspace (16 bytes per pixel; grows like rh_enhance's); F*frame_h*frame_w must
  * stay below 2^31 (RH_E_SHAPE).
  */
 rh_status rh_temporal_phi(rh_ctx* ctx, const int16_t* res_y, int32_t F, int32_t tau, int32_t min_area,

@@ -3,20 +3,26 @@
 // that reuse them.
 //
 // Phi of a frame = sum over the 8-connected blobs of changed pixels (|residual| > tau) of
-// floor(2^32 / area): blob labelling by union-find on a label array in the workspace.
-//   k_tr_init    one wave per 64-pixel row segment: a changed pixel starts with the index of the
-//                leftmost pixel of its horizontal run inside the segment as its label
-//   k_tr_merge   joins runs across segment borders and with the row above, only where two runs
-//                first meet (the other contacts of the same two runs are implied by these)
-//   k_tr_count   every changed pixel finds its root; one atomic add per distinct root in a wave
-//   k_tr_phi     roots add floor(2^32 / area) to their frame's Phi (a wave-level sum, then one
-//                64-bit atomic per wave)
-// All sums are integer, so the result does not depend on the order in which lanes arrive.
+// floor(2^32 / area).  Blobs are labelled in two levels, so that the residual is read once and
+// everything after that touches only a small part of the pixels:
+//   k_tr_reset   clears Phi and the list counters
+//   k_tr_init    one workgroup per tile of 64 x 32 pixels labels the tile in LDS by union-find
+//                (runs of a row start joined; rows are joined where two runs first meet) and
+//                counts the pixels of every piece.  To memory go: for every piece its root
+//                pixel (label = itself, area = pixel count, appended to the frame's root list)
+//                and for every changed pixel on the tile's border its label = the piece's root
+//                (appended to the frame's border list).  Other pixels leave no trace.
+//   k_tr_merge   walks the border lists and joins the pieces that touch across tile borders
+//                (lock-free union-find on the labels in memory; the trees are a few tiles deep)
+//   k_tr_count   walks the root lists: a piece that is no longer a root adds its area to its root
+//   k_tr_phi     walks the root lists: every remaining root is one blob and adds
+//                floor(2^32 / area) to its frame's Phi
+// One list and one counter per frame: a single counter for the batch would serialise the
+// appends of all waves at one address.  All sums are integer, so the result does not depend on
+// the order in which lanes arrive or in which the lists were filled.
 #include "rh_internal.h"
 
-#define TR_NONE 0xFFFFFFFFu
-
-struct tr_geom { int H, W, tiles_x; uint32_t per; };
+struct tr_geom { int H, W; uint32_t per; };
 
 __device__ __forceinline__ int tr_changed(const int16_t* __restrict__ res, size_t frame_base, int y, int x,
                                            int H, int W, int tau)
@@ -26,36 +32,160 @@ __device__ __forceinline__ int tr_changed(const int16_t* __restrict__ res, size_
     return (v < 0 ? -v : v) > tau;
 }
 
+__global__ void k_tr_reset(unsigned long long* phi, int F, uint32_t* n_border, uint32_t* n_roots)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < F) { phi[i] = 0; n_border[i] = 0; n_roots[i] = 0; }
+}
+
+#define TR_ROWS 8                  // rows per wave in k_tr_init
+#define TR_TILE_H (4 * TR_ROWS)    // a workgroup labels a tile of 64 x 32 pixels
+
+__device__ __forceinline__ uint32_t tr_lds_find(uint32_t* lab, uint32_t x)
+{
+    for (;;) {                                                   // lab[x] <= x and only decreases
+        const uint32_t p = __hip_atomic_load(&lab[x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        if (p == x) return x;
+        x = p;
+    }
+}
+
+__device__ __forceinline__ void tr_lds_union(uint32_t* lab, uint32_t a, uint32_t b)
+{
+    for (;;) {                                                   // as tr_union below, on the tile's labels in LDS
+        a = tr_lds_find(lab, a);
+        b = tr_lds_find(lab, b);
+        if (a == b) return;
+        if (a < b) { const uint32_t t = a; a = b; b = t; }
+        const uint32_t old = atomicMin(&lab[a], b);
+        if (old == a) return;
+        a = old;
+    }
+}
+
+// Lanes of tile row ly whose pixel can touch another tile: the top and bottom rows, the first and
+// last column.  These pixels get a label in memory, because k_tr_merge may name them.
+__device__ __forceinline__ uint64_t tr_edge(int ly)
+{
+    return (ly == 0 || ly == TR_TILE_H - 1) ? ~0ull : 0x8000000000000001ull;
+}
+
 __global__ __launch_bounds__(256) void k_tr_init(const int16_t* __restrict__ res, tr_geom g, int tau,
                                                  uint32_t* __restrict__ label, uint32_t* __restrict__ area,
-                                                 unsigned long long* __restrict__ phi)
+                                                 uint32_t* __restrict__ border, uint32_t* n_border,
+                                                 uint32_t* __restrict__ roots, uint32_t* n_roots)
 {
-    const int lane = threadIdx.x & 63, row = blockIdx.y * 4 + (threadIdx.x >> 6);
-    const int f = blockIdx.z, x = blockIdx.x * 64 + lane;
-    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) phi[f] = 0;
-    if (row >= g.H) return;                                      // whole waves leave together
+    __shared__ uint32_t s_lab[TR_TILE_H * 64];
+    __shared__ uint32_t s_cnt[TR_TILE_H * 64];
+    __shared__ unsigned long long s_mask[TR_TILE_H];
+    const int lane = threadIdx.x & 63, ly0 = (threadIdx.x >> 6) * TR_ROWS;
+    const int tx0 = blockIdx.x * 64, ty0 = blockIdx.y * TR_TILE_H;
+    const int f = blockIdx.z, x = tx0 + lane;
     const size_t base = (size_t)f * g.per;
-    const int fg = tr_changed(res, base, row, x, g.H, g.W, tau);
-    const uint64_t m = __ballot(fg);
-    if (x >= g.W) return;
-    const uint32_t p = (uint32_t)(base + (size_t)row * g.W + x);
-    uint32_t l = TR_NONE;
-    if (fg) {
-        const uint64_t gaps_below = ~m & ((1ull << lane) - 1ull);           // unchanged pixels left of this lane
-        const int start = gaps_below ? 64 - __clzll((long long)gaps_below) : 0;
-        l = p - (uint32_t)(lane - start);
+    const uint64_t below = (1ull << lane) - 1ull;
+    int fg[TR_ROWS];
+    uint64_t m[TR_ROWS];
+#pragma unroll
+    for (int j = 0; j < TR_ROWS; ++j) fg[j] = tr_changed(res, base, ty0 + ly0 + j, x, g.H, g.W, tau);   // 0 outside the frame
+    uint32_t mine = 0;                                           // changed pixels of this wave's rows
+#pragma unroll
+    for (int j = 0; j < TR_ROWS; ++j) {
+        m[j] = __ballot(fg[j]);
+        mine += (uint32_t)__popcll(m[j]);
+        if (lane == 0) s_mask[ly0 + j] = m[j];
+        if (fg[j]) {
+            const uint64_t gaps_below = ~m[j] & below;           // unchanged pixels left of this lane
+            const int start = gaps_below ? 64 - __clzll((long long)gaps_below) : 0;
+            s_lab[(ly0 + j) * 64 + lane] = (uint32_t)((ly0 + j) * 64 + start);   // leftmost pixel of the run
+            s_cnt[(ly0 + j) * 64 + lane] = 0;
+        }
     }
-    label[p] = l;
-    area[p] = 0;
+    if (!__syncthreads_or(mine != 0)) return;                    // nothing changed in this tile (most tiles)
+    // contacts with the row above inside the tile; pixels of one run are joined already, so a
+    // contact only counts where the left neighbour did not make the same one
+#pragma unroll
+    for (int j = 0; j < TR_ROWS; ++j) {
+        const int ly = ly0 + j;
+        if (ly == 0 || !fg[j]) continue;
+        const uint64_t up = s_mask[ly - 1];
+        const int w = lane > 0 && ((m[j] >> (lane - 1)) & 1), nn = (int)((up >> lane) & 1);
+        const int nw = lane > 0 && ((up >> (lane - 1)) & 1), ne = lane < 63 && ((up >> (lane + 1)) & 1);
+        const uint32_t me = (uint32_t)(ly * 64 + lane);
+        if (nn) { if (!(w && nw)) tr_lds_union(s_lab, me, me - 64); }
+        else {
+            if (nw && !w) tr_lds_union(s_lab, me, me - 65);
+            if (ne) tr_lds_union(s_lab, me, me - 63);
+        }
+    }
+    __syncthreads();
+    // pixel counts of the pieces: one LDS atomic per distinct root of a row
+    uint32_t root[TR_ROWS];
+    uint32_t nb = 0;                                             // border pixels of this wave's rows
+#pragma unroll
+    for (int j = 0; j < TR_ROWS; ++j) {
+        root[j] = 0;
+        if (fg[j]) root[j] = tr_lds_find(s_lab, (uint32_t)((ly0 + j) * 64 + lane));
+        uint64_t pending = m[j];
+        while (pending) {                                        // wave-uniform
+            const int leader = __ffsll((long long)pending) - 1;
+            const uint32_t r0 = (uint32_t)__shfl((int)root[j], leader);
+            const uint64_t same = __ballot(fg[j] && root[j] == r0);
+            if (lane == leader) atomicAdd(&s_cnt[r0], (uint32_t)__popcll(same));
+            pending &= ~same;
+        }
+        const uint64_t edge = tr_edge(ly0 + j);
+        nb += (uint32_t)__popcll(m[j] & edge);
+    }
+    __syncthreads();
+    if (mine == 0) return;                                       // the same for the whole wave, and no barrier follows
+    uint64_t mr[TR_ROWS];                                        // which lanes hold the root of a piece
+    uint32_t nr = 0;
+#pragma unroll
+    for (int j = 0; j < TR_ROWS; ++j) {
+        mr[j] = __ballot(fg[j] && root[j] == (uint32_t)((ly0 + j) * 64 + lane));
+        nr += (uint32_t)__popcll(mr[j]);
+    }
+    // room in the frame's two lists: both atomics are in flight together, their latency is what
+    // a workgroup of this kernel mostly waits for
+    uint32_t slot_b = 0, slot_r = 0;
+    if (lane == 0) {
+        if (nb) slot_b = atomicAdd(&n_border[f], nb);
+        if (nr) slot_r = atomicAdd(&n_roots[f], nr);
+    }
+    slot_b = (uint32_t)__shfl((int)slot_b, 0);
+    slot_r = (uint32_t)__shfl((int)slot_r, 0);
+#pragma unroll
+    for (int j = 0; j < TR_ROWS; ++j) {
+        const uint32_t p = (uint32_t)(base + (size_t)(ty0 + ly0 + j) * g.W + x);
+        // border pixels: label = the piece's root, as a pixel index of the batch
+        const uint64_t edge = tr_edge(ly0 + j), mb = m[j] & edge;
+        if (fg[j] && ((edge >> lane) & 1)) {
+            label[p] = (uint32_t)(base + (size_t)(ty0 + (int)(root[j] >> 6)) * g.W + tx0 + (int)(root[j] & 63));
+            border[base + slot_b + (uint32_t)__popcll(mb & below)] = p;   // frame f's lists start at f * per
+        }
+        slot_b += (uint32_t)__popcll(mb);
+        // roots of the pieces: label = itself, area = the piece's pixel count
+        if ((mr[j] >> lane) & 1) {
+            label[p] = p;
+            area[p] = s_cnt[(ly0 + j) * 64 + lane];
+            roots[base + slot_r + (uint32_t)__popcll(mr[j] & below)] = p;
+        }
+        slot_r += (uint32_t)__popcll(mr[j]);
+    }
 }
 
 __device__ __forceinline__ uint32_t tr_find(uint32_t* label, uint32_t x)
 {
-    // labels only ever decrease and label[x] <= x, so this walk ends at a root
+    // Labels only ever decrease and label[x] <= x, so this walk ends at a root.  On the way every
+    // visited pixel is pointed at its grandparent (still an ancestor, still smaller), which keeps
+    // the chains that later walks meet short.
     for (;;) {
         const uint32_t p = __hip_atomic_load(&label[x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (p == x) return x;
-        x = p;
+        const uint32_t gp = __hip_atomic_load(&label[p], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (gp == p) return p;
+        atomicMin(&label[x], gp);
+        x = gp;
     }
 }
 
@@ -74,72 +204,62 @@ __device__ __forceinline__ void tr_union(uint32_t* label, uint32_t a, uint32_t b
     }
 }
 
+// The three list kernels run a fixed grid (x: workgroups of one frame, y: frame); every thread
+// strides over its frame's list.
 __global__ __launch_bounds__(256) void k_tr_merge(const int16_t* __restrict__ res, tr_geom g, int tau,
-                                                  uint32_t* label)
+                                                  uint32_t* label, const uint32_t* __restrict__ border,
+                                                  const uint32_t* __restrict__ n_border)
 {
-    const int lane = threadIdx.x & 63, y = blockIdx.y * 4 + (threadIdx.x >> 6);
-    const int f = blockIdx.z, x = blockIdx.x * 64 + lane;
-    if (y >= g.H || x >= g.W) return;
-    const size_t base = (size_t)f * g.per;
-    if (!tr_changed(res, base, y, x, g.H, g.W, tau)) return;
-    const uint32_t p = (uint32_t)(base + (size_t)y * g.W + x);
-    const int w = tr_changed(res, base, y, x - 1, g.H, g.W, tau);
-    const int n = tr_changed(res, base, y - 1, x, g.H, g.W, tau);
-    const int nw = tr_changed(res, base, y - 1, x - 1, g.H, g.W, tau);
-    const int ne = tr_changed(res, base, y - 1, x + 1, g.H, g.W, tau);
-    // a run that goes on from the previous 64-pixel segment
-    if (w && lane == 0) tr_union(label, p, p - 1);
-    // the row above: pixels of one run are joined already, so a contact only counts where the
-    // left neighbour did not make the same one
-    if (n) { if (!(w && nw)) tr_union(label, p, p - (uint32_t)g.W); }
-    else {
-        if (nw && !w) tr_union(label, p, p - (uint32_t)g.W - 1);
-        if (ne) tr_union(label, p, p - (uint32_t)g.W + 1);
+    const uint32_t f = blockIdx.y, n = n_border[f], stride = gridDim.x * 256;
+    border += (size_t)f * g.per;
+    for (uint32_t i = blockIdx.x * 256 + threadIdx.x; i < n; i += stride) {
+        const uint32_t p = border[i];
+        const uint32_t r = p - f * g.per;
+        const int y = (int)(r / (uint32_t)g.W), x = (int)(r - (uint32_t)y * (uint32_t)g.W);
+        const size_t base = (size_t)f * g.per;
+        const int lx = x & 63, ly = y % TR_TILE_H;
+        if (lx != 0 && lx != 63 && ly != 0) continue;            // bottom-row pixels are listed only because they carry a label
+        const int w = tr_changed(res, base, y, x - 1, g.H, g.W, tau), nn = tr_changed(res, base, y - 1, x, g.H, g.W, tau);
+        const int nw = tr_changed(res, base, y - 1, x - 1, g.H, g.W, tau), ne = tr_changed(res, base, y - 1, x + 1, g.H, g.W, tau);
+        // The rule k_tr_init uses inside a tile (runs are joined, so a contact with the row above
+        // counts only where the left neighbour did not make the same one), applied to the
+        // contacts that cross a tile border; the neighbour then lies on its own tile's border
+        // and has a label.
+        if (w && lx == 0) tr_union(label, p, p - 1);
+        if (nn) { if (ly == 0 && !(w && nw)) tr_union(label, p, p - (uint32_t)g.W); }
+        else {
+            if (nw && !w && (ly == 0 || lx == 0)) tr_union(label, p, p - (uint32_t)g.W - 1);
+            if (ne && (ly == 0 || lx == 63)) tr_union(label, p, p - (uint32_t)g.W + 1);
+        }
     }
 }
 
-__global__ __launch_bounds__(256) void k_tr_count(tr_geom g, uint32_t* label, uint32_t* area)
+__global__ __launch_bounds__(256) void k_tr_count(tr_geom g, uint32_t* label, uint32_t* area, const uint32_t* __restrict__ roots,
+                                                  const uint32_t* __restrict__ n_roots)
 {
-    const int lane = threadIdx.x & 63, y = blockIdx.y * 4 + (threadIdx.x >> 6);
-    const int f = blockIdx.z, x = blockIdx.x * 64 + lane;
-    if (y >= g.H) return;
-    uint32_t root = TR_NONE;
-    int fg = 0;
-    if (x < g.W) {
-        const uint32_t p = (uint32_t)((size_t)f * g.per + (size_t)y * g.W + x);
-        if (label[p] != TR_NONE) { fg = 1; root = tr_find(label, p); }
-    }
-    uint64_t pending = __ballot(fg);
-    while (pending) {                                            // one round per distinct root of the wave
-        const int leader = __ffsll((long long)pending) - 1;
-        const uint32_t r0 = (uint32_t)__shfl((int)root, leader);
-        const uint64_t same = __ballot(fg && root == r0);
-        if (lane == leader) atomicAdd(&area[r0], (uint32_t)__popcll(same));
-        pending &= ~same;
+    const uint32_t n = n_roots[blockIdx.y], stride = gridDim.x * 256;
+    roots += (size_t)blockIdx.y * g.per;
+    for (uint32_t i = blockIdx.x * 256 + threadIdx.x; i < n; i += stride) {
+        const uint32_t p = roots[i];
+        const uint32_t r = tr_find(label, p);
+        // only final roots are added to, and a final root adds nothing: area[p] is not written here
+        if (r != p) atomicAdd(&area[r], area[p]);
     }
 }
 
 __global__ __launch_bounds__(256) void k_tr_phi(tr_geom g, const uint32_t* __restrict__ label,
                                                 const uint32_t* __restrict__ area, uint32_t min_area,
+                                                const uint32_t* __restrict__ roots, const uint32_t* __restrict__ n_roots,
                                                 unsigned long long* phi)
 {
-    const int lane = threadIdx.x & 63, y = blockIdx.y * 4 + (threadIdx.x >> 6);
-    const int f = blockIdx.z, x = blockIdx.x * 64 + lane;
-    if (y >= g.H) return;
-    unsigned long long c = 0;
-    if (x < g.W) {
-        const uint32_t p = (uint32_t)((size_t)f * g.per + (size_t)y * g.W + x);
-        if (label[p] == p) {
-            const uint32_t a = area[p];
-            if (a >= min_area) c = (1ull << 32) / a;
-        }
+    const uint32_t n = n_roots[blockIdx.y], stride = gridDim.x * 256;
+    roots += (size_t)blockIdx.y * g.per;
+    for (uint32_t i = blockIdx.x * 256 + threadIdx.x; i < n; i += stride) {
+        const uint32_t p = roots[i];
+        if (label[p] != p) continue;                             // what is still a root is one blob
+        const uint32_t a = area[p];
+        if (a >= min_area) atomicAdd(&phi[blockIdx.y], (1ull << 32) / a);
     }
-    if (__ballot(c != 0) == 0) return;
-    for (int o = 32; o; o >>= 1) {
-        const uint32_t lo = (uint32_t)__shfl_down((int)(uint32_t)c, o), hi = (uint32_t)__shfl_down((int)(uint32_t)(c >> 32), o);
-        c += ((unsigned long long)hi << 32) | lo;
-    }
-    if (lane == 0) atomicAdd(&phi[f], c);
 }
 
 rh_status rh_launch_temporal_phi(rh_ctx* ctx, const int16_t* res, int F, int tau, int min_area, uint64_t* phi)
@@ -147,18 +267,26 @@ rh_status rh_launch_temporal_phi(rh_ctx* ctx, const int16_t* res, int F, int tau
     const int H = ctx->cfg.frame_h, W = ctx->cfg.frame_w;
     const size_t px = (size_t)F * H * W;
     if (px >= 0x7FFFFFFFull) RH_FAIL(ctx, RH_E_SHAPE, "rh_temporal_phi: %zu pixels exceed the 32-bit label range", px);
-    rh_status st = rh_ensure_workspace(ctx, px * 8);
+    if (F > 65535) RH_FAIL(ctx, RH_E_CAPACITY, "rh_temporal_phi: F=%d exceeds 65535 frames per call", F);
+    rh_status st = rh_ensure_workspace(ctx, px * 16 + (size_t)F * 8);
     if (st != RH_OK) return st;
     uint32_t* label = (uint32_t*)ctx->act;
     uint32_t* area = label + px;
-    tr_geom g{H, W, (W + 63) / 64, (uint32_t)((size_t)H * W)};
-    const dim3 grid(g.tiles_x, (H + 3) / 4, F), block(256);
-    rh_prof_scope ps(ctx, RH_PROF_TEMPORAL, 4);
-    hipLaunchKernelGGL(k_tr_init, grid, block, 0, ctx->stream, res, g, tau, label, area, (unsigned long long*)phi);
-    hipLaunchKernelGGL(k_tr_merge, grid, block, 0, ctx->stream, res, g, tau, label);
-    hipLaunchKernelGGL(k_tr_count, grid, block, 0, ctx->stream, g, label, area);
-    hipLaunchKernelGGL(k_tr_phi, grid, block, 0, ctx->stream, g, (const uint32_t*)label, (const uint32_t*)area,
-                       (uint32_t)min_area, (unsigned long long*)phi);
+    uint32_t* border = area + px;
+    uint32_t* roots = border + px;
+    uint32_t* n_border = roots + px;
+    uint32_t* n_roots = n_border + F;
+    tr_geom g{H, W, (uint32_t)((size_t)H * W)};
+    const dim3 grid((W + 63) / 64, (H + TR_TILE_H - 1) / TR_TILE_H, F), block(256);
+    rh_prof_scope ps(ctx, RH_PROF_TEMPORAL, 5);
+    hipLaunchKernelGGL(k_tr_reset, dim3((F + 255) / 256), block, 0, ctx->stream, (unsigned long long*)phi, F, n_border, n_roots);
+    hipLaunchKernelGGL(k_tr_init, grid, block, 0, ctx->stream, res, g, tau, label, area, border, n_border, roots, n_roots);
+    hipLaunchKernelGGL(k_tr_merge, dim3(16, F), block, 0, ctx->stream, res, g, tau, label, (const uint32_t*)border,
+                       (const uint32_t*)n_border);
+    hipLaunchKernelGGL(k_tr_count, dim3(8, F), block, 0, ctx->stream, g, label, area, (const uint32_t*)roots,
+                       (const uint32_t*)n_roots);
+    hipLaunchKernelGGL(k_tr_phi, dim3(8, F), block, 0, ctx->stream, g, (const uint32_t*)label, (const uint32_t*)area,
+                       (uint32_t)min_area, (const uint32_t*)roots, (const uint32_t*)n_roots, (unsigned long long*)phi);
     RH_HIP(ctx, hipGetLastError());
     return RH_OK;
 }
