@@ -78,6 +78,7 @@ __global__ __launch_bounds__(256) void k_tr_init(const int16_t* __restrict__ res
     __shared__ uint32_t s_lab[TR_TILE_H * 64];
     __shared__ uint32_t s_cnt[TR_TILE_H * 64];
     __shared__ unsigned long long s_mask[TR_TILE_H];
+    __shared__ __attribute__((aligned(16))) uint32_t s_mine[4];
     const int lane = threadIdx.x & 63, ly0 = (threadIdx.x >> 6) * TR_ROWS;
     const int tx0 = blockIdx.x * 64, ty0 = blockIdx.y * TR_TILE_H;
     const int f = blockIdx.z, x = tx0 + lane;
@@ -100,7 +101,12 @@ __global__ __launch_bounds__(256) void k_tr_init(const int16_t* __restrict__ res
             s_cnt[(ly0 + j) * 64 + lane] = 0;
         }
     }
-    if (!__syncthreads_or(mine != 0)) return;                    // nothing changed in this tile (most tiles)
+    if (lane == 0) s_mine[threadIdx.x >> 6] = mine;
+    __syncthreads();
+    {   // nothing changed in this tile (most tiles): all four waves leave
+        const uint4 all = *(const uint4*)s_mine;
+        if ((all.x | all.y | all.z | all.w) == 0) return;
+    }
     // contacts with the row above inside the tile; pixels of one run are joined already, so a
     // contact only counts where the left neighbour did not make the same one
 #pragma unroll
