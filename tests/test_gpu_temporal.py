@@ -48,7 +48,7 @@ def test_phi_on_synthetic_residuals_at_full_size(w, h, streams, fps):
 
 
 @pytest.mark.parametrize("density", [0.0, 0.02, 0.2, 0.45, 0.6, 0.9, 1.0])
-@pytest.mark.parametrize("w,h", [(53, 37), (64, 16), (130, 67), (257, 33)])
+@pytest.mark.parametrize("w,h", [(16, 16), (19, 17), (53, 37), (64, 16), (130, 67), (257, 33)])
 def test_phi_random_masks_ragged_sizes(density, w, h):
     rng = np.random.default_rng(int(density * 100) + w)
     res = ((rng.random((5, h, w)) < density) * rng.integers(20, 200, (5, h, w))).astype(np.int16)
