@@ -39,7 +39,10 @@ __global__ void k_tr_reset(unsigned long long* phi, int F, uint32_t* n_border, u
 }
 
 #define TR_ROWS 8                  // rows per wave in k_tr_init
-#define TR_TILE_H (4 * TR_ROWS)    // a workgroup labels a tile of 64 x 32 pixels
+#ifndef TR_WAVES
+#define TR_WAVES 4                 // waves per workgroup of k_tr_init
+#endif
+#define TR_TILE_H (TR_WAVES * TR_ROWS)    // a workgroup labels a tile of 64 x 32 pixels
 
 __device__ __forceinline__ uint32_t tr_lds_find(uint32_t* lab, uint32_t x)
 {
@@ -70,7 +73,8 @@ __device__ __forceinline__ uint64_t tr_edge(int ly)
     return (ly == 0 || ly == TR_TILE_H - 1) ? ~0ull : 0x8000000000000001ull;
 }
 
-__global__ __launch_bounds__(256) void k_tr_init(const int16_t* __restrict__ res, tr_geom g, int tau,
+template <bool WIDE>
+__global__ __launch_bounds__(64 * TR_WAVES) void k_tr_init(const int16_t* __restrict__ res, tr_geom g, int tau,
                                                  uint32_t* __restrict__ label, uint32_t* __restrict__ area,
                                                  uint32_t* __restrict__ border, uint32_t* n_border,
                                                  uint32_t* __restrict__ roots, uint32_t* n_roots)
@@ -79,6 +83,7 @@ __global__ __launch_bounds__(256) void k_tr_init(const int16_t* __restrict__ res
     __shared__ uint32_t s_cnt[TR_TILE_H * 64];
     __shared__ unsigned long long s_mask[TR_TILE_H];
     __shared__ __attribute__((aligned(16))) uint32_t s_mine[4];
+    __shared__ __attribute__((aligned(16))) int16_t s_res[WIDE ? TR_TILE_H * 64 : 8];
     const int lane = threadIdx.x & 63, ly0 = (threadIdx.x >> 6) * TR_ROWS;
     const int tx0 = blockIdx.x * 64, ty0 = blockIdx.y * TR_TILE_H;
     const int f = blockIdx.z, x = tx0 + lane;
@@ -86,8 +91,26 @@ __global__ __launch_bounds__(256) void k_tr_init(const int16_t* __restrict__ res
     const uint64_t below = (1ull << lane) - 1ull;
     int fg[TR_ROWS];
     uint64_t m[TR_ROWS];
+    if constexpr (WIDE) {
+        // The tile's residuals come in as 16-byte pieces (one per thread: row t/8, pixels 8*(t%8)..+7)
+        // and every lane then picks its pixels out of LDS: one memory instruction per wave instead
+        // of one per row.  Needs W % 8 == 0 and a 16-byte aligned tensor (pieces are then wholly
+        // inside or outside a row).
+        static_assert(TR_WAVES == 4, "one 16-byte piece per thread covers a 64 x 32 tile");
+        const int prow = ty0 + (int)(threadIdx.x >> 3), px = tx0 + (int)(threadIdx.x & 7) * 8;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (prow < g.H && px < g.W) v = *(const uint4*)(res + base + (size_t)prow * g.W + px);
+        ((uint4*)s_res)[threadIdx.x] = v;
+        __syncthreads();
 #pragma unroll
-    for (int j = 0; j < TR_ROWS; ++j) fg[j] = tr_changed(res, base, ty0 + ly0 + j, x, g.H, g.W, tau);   // 0 outside the frame
+        for (int j = 0; j < TR_ROWS; ++j) {
+            const int r = s_res[(ly0 + j) * 64 + lane];
+            fg[j] = (r < 0 ? -r : r) > tau;                      // zero-filled outside the frame
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < TR_ROWS; ++j) fg[j] = tr_changed(res, base, ty0 + ly0 + j, x, g.H, g.W, tau);   // 0 outside the frame
+    }
     uint32_t mine = 0;                                           // changed pixels of this wave's rows
 #pragma unroll
     for (int j = 0; j < TR_ROWS; ++j) {
@@ -103,9 +126,11 @@ __global__ __launch_bounds__(256) void k_tr_init(const int16_t* __restrict__ res
     }
     if (lane == 0) s_mine[threadIdx.x >> 6] = mine;
     __syncthreads();
-    {   // nothing changed in this tile (most tiles): all four waves leave
-        const uint4 all = *(const uint4*)s_mine;
-        if ((all.x | all.y | all.z | all.w) == 0) return;
+    {   // nothing changed in this tile (most tiles): all waves leave
+        uint32_t any = 0;
+#pragma unroll
+        for (int i = 0; i < TR_WAVES; ++i) any |= s_mine[i];
+        if (any == 0) return;
     }
     // contacts with the row above inside the tile; pixels of one run are joined already, so a
     // contact only counts where the left neighbour did not make the same one
@@ -286,7 +311,10 @@ rh_status rh_launch_temporal_phi(rh_ctx* ctx, const int16_t* res, int F, int tau
     const dim3 grid((W + 63) / 64, (H + TR_TILE_H - 1) / TR_TILE_H, F), block(256);
     rh_prof_scope ps(ctx, RH_PROF_TEMPORAL, 5);
     hipLaunchKernelGGL(k_tr_reset, dim3((F + 255) / 256), block, 0, ctx->stream, (unsigned long long*)phi, F, n_border, n_roots);
-    hipLaunchKernelGGL(k_tr_init, grid, block, 0, ctx->stream, res, g, tau, label, area, border, n_border, roots, n_roots);
+    if (TR_WAVES == 4 && W % 8 == 0 && ((uintptr_t)res & 15) == 0)
+        hipLaunchKernelGGL(k_tr_init<true>, grid, dim3(64 * TR_WAVES), 0, ctx->stream, res, g, tau, label, area, border, n_border, roots, n_roots);
+    else
+        hipLaunchKernelGGL(k_tr_init<false>, grid, dim3(64 * TR_WAVES), 0, ctx->stream, res, g, tau, label, area, border, n_border, roots, n_roots);
     hipLaunchKernelGGL(k_tr_merge, dim3(16, F), block, 0, ctx->stream, res, g, tau, label, (const uint32_t*)border,
                        (const uint32_t*)n_border);
     hipLaunchKernelGGL(k_tr_count, dim3(8, F), block, 0, ctx->stream, g, label, area, (const uint32_t*)roots,
