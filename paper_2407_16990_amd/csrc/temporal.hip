@@ -73,6 +73,10 @@ __device__ __forceinline__ uint64_t tr_edge(int ly)
     return (ly == 0 || ly == TR_TILE_H - 1) ? ~0ull : 0x8000000000000001ull;
 }
 
+// The border pixels from which k_tr_merge starts a join: those of the bottom row are only ever the
+// other end of one.
+__device__ __forceinline__ uint64_t tr_listed(int ly) { return ly == 0 ? ~0ull : 0x8000000000000001ull; }
+
 template <bool WIDE>
 __global__ __launch_bounds__(64 * TR_WAVES) void k_tr_init(const int16_t* __restrict__ res, tr_geom g, int tau,
                                                  uint32_t* __restrict__ label, uint32_t* __restrict__ area,
@@ -164,8 +168,7 @@ __global__ __launch_bounds__(64 * TR_WAVES) void k_tr_init(const int16_t* __rest
             if (lane == leader) atomicAdd(&s_cnt[r0], (uint32_t)__popcll(same));
             pending &= ~same;
         }
-        const uint64_t edge = tr_edge(ly0 + j);
-        nb += (uint32_t)__popcll(m[j] & edge);
+        nb += (uint32_t)__popcll(m[j] & tr_listed(ly0 + j));
     }
     __syncthreads();
     if (mine == 0) return;                                       // the same for the whole wave, and no barrier follows
@@ -189,10 +192,10 @@ __global__ __launch_bounds__(64 * TR_WAVES) void k_tr_init(const int16_t* __rest
     for (int j = 0; j < TR_ROWS; ++j) {
         const uint32_t p = (uint32_t)(base + (size_t)(ty0 + ly0 + j) * g.W + x);
         // border pixels: label = the piece's root, as a pixel index of the batch
-        const uint64_t edge = tr_edge(ly0 + j), mb = m[j] & edge;
+        const uint64_t edge = tr_edge(ly0 + j), listed = tr_listed(ly0 + j), mb = m[j] & listed;
         if (fg[j] && ((edge >> lane) & 1)) {
             label[p] = (uint32_t)(base + (size_t)(ty0 + (int)(root[j] >> 6)) * g.W + tx0 + (int)(root[j] & 63));
-            border[base + slot_b + (uint32_t)__popcll(mb & below)] = p;   // frame f's lists start at f * per
+            if ((listed >> lane) & 1) border[base + slot_b + (uint32_t)__popcll(mb & below)] = p;   // frame f's lists start at f * per
         }
         slot_b += (uint32_t)__popcll(mb);
         // roots of the pieces: label = itself, area = the piece's pixel count
@@ -243,20 +246,24 @@ __global__ __launch_bounds__(256) void k_tr_merge(const int16_t* __restrict__ re
 {
     const uint32_t f = blockIdx.y, n = n_border[f], stride = gridDim.x * 256;
     border += (size_t)f * g.per;
-    for (uint32_t i = blockIdx.x * 256 + threadIdx.x; i < n; i += stride) {
-        const uint32_t p = border[i];
+    // two work items per listed pixel (0: the join to the left, 1: the joins upwards), so that no
+    // thread has more than two joins - each a chain of dependent memory round trips - in a row
+    for (uint32_t i2 = blockIdx.x * 256 + threadIdx.x; i2 < 2 * n; i2 += stride) {
+        const uint32_t p = border[i2 >> 1];
         const uint32_t r = p - f * g.per;
         const int y = (int)(r / (uint32_t)g.W), x = (int)(r - (uint32_t)y * (uint32_t)g.W);
         const size_t base = (size_t)f * g.per;
         const int lx = x & 63, ly = y % TR_TILE_H;
-        if (lx != 0 && lx != 63 && ly != 0) continue;            // bottom-row pixels are listed only because they carry a label
-        const int w = tr_changed(res, base, y, x - 1, g.H, g.W, tau), nn = tr_changed(res, base, y - 1, x, g.H, g.W, tau);
-        const int nw = tr_changed(res, base, y - 1, x - 1, g.H, g.W, tau), ne = tr_changed(res, base, y - 1, x + 1, g.H, g.W, tau);
         // The rule k_tr_init uses inside a tile (runs are joined, so a contact with the row above
         // counts only where the left neighbour did not make the same one), applied to the
         // contacts that cross a tile border; the neighbour then lies on its own tile's border
         // and has a label.
-        if (w && lx == 0) tr_union(label, p, p - 1);
+        if ((i2 & 1) == 0) {
+            if (lx == 0 && tr_changed(res, base, y, x - 1, g.H, g.W, tau)) tr_union(label, p, p - 1);
+            continue;
+        }
+        const int w = tr_changed(res, base, y, x - 1, g.H, g.W, tau), nn = tr_changed(res, base, y - 1, x, g.H, g.W, tau);
+        const int nw = tr_changed(res, base, y - 1, x - 1, g.H, g.W, tau), ne = tr_changed(res, base, y - 1, x + 1, g.H, g.W, tau);
         if (nn) { if (ly == 0 && !(w && nw)) tr_union(label, p, p - (uint32_t)g.W); }
         else {
             if (nw && !w && (ly == 0 || lx == 0)) tr_union(label, p, p - (uint32_t)g.W - 1);
