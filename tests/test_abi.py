@@ -20,7 +20,8 @@ def test_library_exports_every_declared_symbol():
     lib = pkg.load_library()
     names = declared_functions()
     assert {"rh_create", "rh_destroy", "rh_select_regions", "rh_pack", "rh_enhance", "rh_unpack",
-            "rh_read_counts", "rh_last_error", "rh_budget", "rh_identity_places", "rh_set_stream"} <= set(names)
+            "rh_read_counts", "rh_last_error", "rh_budget", "rh_identity_places", "rh_set_stream",
+            "rh_temporal_phi", "rh_temporal_select", "rh_temporal_spread"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
@@ -66,3 +67,6 @@ def test_new_entry_points_reject_null_arguments():
     assert lib.rh_enhance_exact(None, None, 1, None, None, None, None) == 1
     out = (C.c_double * 3)()
     assert lib.rh_probe_mfma(None, 0, C.c_double(1.0), C.byref(out)) == 1
+    assert lib.rh_temporal_phi(None, None, 1, 0, 1, None) == 1
+    assert lib.rh_temporal_select(None, None, None, 1, 1, None, None, None, None) == 1
+    assert lib.rh_temporal_spread(None, None, 1, None, None) == 1
