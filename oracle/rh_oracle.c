@@ -19,7 +19,7 @@
  * second opinions, and a hand-traced placement example.  The plan produced by
  * the packing heuristic has no printed example in the paper: plan equality is
  * "parity unpinned" with respect to the paper and pinned only to the
- * determinism rules documented in the design notes.
+ * determinism rules stated at orc_plan (tie-breaks, list order, split of the free remainder).
  *
  * The inverse-area operator of the temporal importance reuse (Sec. 3.2.2, orc_phi at the end of
  * the file) is pinned by hand cases and a library labelling routine

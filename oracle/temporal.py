@@ -17,7 +17,7 @@ arithmetic on Python ints, written as the definitions read:
 
 The paper gives the normalisation, the equal cuts of the CDF and the proportional share; which
 value is taken inside an interval, how the share is rounded, and that no stream may go without
-a prediction are readings, listed with the others in the design notes.  No value of these is
+a prediction are readings of this implementation.  No value of these is
 printed in the paper: the functions are pinned by closed-form cases in tests/test_oracle_temporal.py.
 """
 from __future__ import annotations
