@@ -479,6 +479,7 @@ static rh_status conv(rh_ctx* ctx, const rh_layer& L, const __bf16* in, void* ou
     a.dbg = getenv("RH_DBG") ? atoi(getenv("RH_DBG")) : 0;
 #endif
     a.relu = relu; a.ps = L.ps; a.n_chunks = last ? 1 : L.ps * L.ps; a.cout_real = L.cout; a.s_final = s_final;
+    a.rev = (ctx->conv_parity ^= 1);       // alternate the direction from one conv to the next
     const int grid = ctx->n_cu;            // persistent kernels: one workgroup per compute unit (256 on MI355X)
     const int MT = last ? L.cout_pad / 32 : L.cin / 32;
     hipError_t e;
@@ -520,6 +521,7 @@ rh_status rh_launch_enhance_bf16(rh_ctx* ctx, const uint8_t* in, int N, int H, i
     rh_status st = rh_ensure_workspace(ctx, need * 2);
     if (st != RH_OK) return st;
     __bf16* a = (__bf16*)ctx->act; __bf16* t = a + lr; __bf16* h = t + lr; __bf16* u1 = h + lr; __bf16* u2 = u1 + up1;
+    ctx->conv_parity = 0;                  // the head conv walks forward, the first conv after it backward
     const std::vector<rh_layer>& L = ctx->layers;
     size_t li = 0;
     const int head_relu = d.topology == RH_NET_PLAIN;

@@ -18,6 +18,7 @@ struct conv_args {
     int N, H, W;
     int relu, ps, n_chunks;  // bf16 output mode
     int cout_real, s_final;  // fp32 output mode
+    int rev;                 // 1: walk the tiles from the last to the first (k_conv_mfma_duo)
 #ifdef RH_PHASE_TIMING
     int dbg;                 // bit0: no patch loads, bit1: no output stores, bit2: no MFMA loop
 #endif

@@ -125,6 +125,11 @@ __global__ __launch_bounds__(512) void k_conv_mfma_duo(conv_args a)
 
     // origin of team's half of tile number `tile` (rows y0..y0+7), image index n
     auto tile_origin = [&](int tile, int& n, int& y0, int& x0) __attribute__((always_inline)) {
+        // Consecutive layers walk the tensor in opposite directions: what a layer touched last (the
+        // end of its input and output) is what the next layer touches first, while it is still in
+        // the memory-side cache.  Walking every layer front to back through buffers that together
+        // exceed that cache evicts each line just before it is needed again.
+        if (a.rev && tile < n_tiles) tile = n_tiles - 1 - tile;
         n = tile / tiles_img;
         const int tr = tile - n * tiles_img, ty = tr / tiles_x, tx = tr - ty * tiles_x;
         y0 = ty * 16 + team * TH; x0 = tx * 32;

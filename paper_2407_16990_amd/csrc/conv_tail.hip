@@ -41,7 +41,10 @@ __global__ __launch_bounds__(256) void k_conv_tail3(conv_args a, int tpb /* cons
     for (int ks = 0; ks < KS; ++ks) { const uint4 v = a.wp[ks * 64 + lane]; A[ks] = *(const bf16x8*)&v; }
     const float b0 = a.bias[0], b1 = a.bias[1], b2 = a.bias[2];
 
-    for (int tile = tile0; tile < tile0 + tpb && tile < n_tiles; ++tile) {   // trip count uniform over the workgroup
+    for (int tile_i = tile0; tile_i < tile0 + tpb && tile_i < n_tiles; ++tile_i) {   // trip count uniform over the workgroup
+    // a.rev: walk the tensor from its end, where the layer before (walking the other way) has just
+    // written it and it still sits in the memory-side cache
+    const int tile = a.rev ? n_tiles - 1 - tile_i : tile_i;
     const int n = tile / tiles_img, tr = tile - n * tiles_img, ty = tr / tiles_x, tx = tr - ty * tiles_x;
     const int y0 = ty * TH, x0 = tx * 32;
 

@@ -78,6 +78,7 @@ struct rh_ctx {
     // rh_enhance_exact call, null otherwise)
     const rh_box* bz_boxes;
     const uint32_t* bz_counts;
+    int conv_parity;        // direction of the next bf16 conv's tile walk (alternates)
     // enhance workspace (grow-only)
     void* act;
     size_t act_bytes;
