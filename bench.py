@@ -210,7 +210,11 @@ def main():
 
     boxes_host = RH.boxes_np(po.boxes, n_boxes)
     pb, ub = mem_bytes(n_bins, boxes_host, k_sel, F)
+    sel_bytes = lambda nf, nsel: nf * rh.mbh * rh.mbw * 5 + nsel * 4          # 4 B read + 1 B mask per MB, 4 B per selected MB
+    sb = sel_bytes(F, k_sel)
     result["memory_steps"] = {
+        "select": {"bytes": sb, "us": prof["select"][0] / args.steps * 1e3, "GB/s": sb / (prof["select"][0] / args.steps * 1e-3) / 1e9,
+                   "note": "latency-bound: tens of kilobytes"},
         "pack_gather": {"bytes": pb, "us": prof["gather"][0] / args.steps * 1e3, "GB/s": pb / (prof["gather"][0] / args.steps * 1e-3) / 1e9},
         "unpack": {"bytes": ub, "us": prof["unpack"][0] / args.steps * 1e3, "GB/s": ub / (prof["unpack"][0] / args.steps * 1e-3) / 1e9},
         "hbm_peak_GB/s": 8000.0}
@@ -244,6 +248,8 @@ def main():
         xpb, xub = mem_bytes(xc[1], xboxes, xc[3], F * X)
         result["memory_steps"][f"x{X}"] = {
             "frames": F * X, "n_bins": xc[1],
+            "select": {"bytes": sel_bytes(F * X, xc[3]), "us": xprof["select"][0] / reps * 1e3,
+                       "GB/s": sel_bytes(F * X, xc[3]) / (xprof["select"][0] / reps * 1e-3) / 1e9},
             "pack_gather": {"bytes": xpb, "us": xprof["gather"][0] / reps * 1e3, "GB/s": xpb / (xprof["gather"][0] / reps * 1e-3) / 1e9},
             "unpack": {"bytes": xub, "us": xprof["unpack"][0] / reps * 1e3, "GB/s": xub / (xprof["unpack"][0] / reps * 1e-3) / 1e9}}
         del rhx, xf, xi, xhr, xnet, xpo
