@@ -11,9 +11,12 @@ __global__ __launch_bounds__(256) void k_bins_zero(uint4* __restrict__ bins, con
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) bins[i] = z;
 }
 
-// A work unit is an 8-row band of one box (as stored in the bin); workgroups stride over the units, each wave copies
-// 2 rows, lanes run along the row's bytes (contiguous in both the frame and the bin).  Box
-// rectangles of one bin are disjoint, so no two units write the same byte.
+// A work unit is a band of 4 * GATHER_RPW rows of one box (as stored in the bin); workgroups stride over the
+// units, each wave copies GATHER_RPW rows, lanes run along the row's bytes (contiguous in both the frame
+// and the bin).  Box rectangles of one bin are disjoint, so no two units write the same byte.
+#ifndef GATHER_RPW
+#define GATHER_RPW 2
+#endif
 __global__ __launch_bounds__(256) void k_gather(const uint8_t* __restrict__ frames, const rh_box* __restrict__ boxes,
                                                 const uint32_t* __restrict__ counts, int H, int W, int halo, int S,
                                                 int bands, uint8_t* __restrict__ bins)
@@ -32,8 +35,8 @@ __global__ __launch_bounds__(256) void k_gather(const uint8_t* __restrict__ fram
             // turned box: bin row i holds box column i, so a row's bytes come from one source
             // column (strided reads; turned boxes are the exception)
 #pragma unroll
-            for (int rr = 0; rr < 2; ++rr) {
-                const int i = (u % bands) * 8 + wave * 2 + rr;     // bin row = box column
+            for (int rr = 0; rr < GATHER_RPW; ++rr) {
+                const int i = (u % bands) * (4 * GATHER_RPW) + wave * GATHER_RPW + rr;     // bin row = box column
                 if (i >= bw) continue;
                 const int sx = sx0 + i;
                 uint8_t* drow = dst + (size_t)i * S * 3;
@@ -45,14 +48,43 @@ __global__ __launch_bounds__(256) void k_gather(const uint8_t* __restrict__ fram
             continue;
         }
 #pragma unroll
-        for (int rr = 0; rr < 2; ++rr) {
-            const int j = (u % bands) * 8 + wave * 2 + rr;
+        for (int rr = 0; rr < GATHER_RPW; ++rr) {
+            const int j = (u % bands) * (4 * GATHER_RPW) + wave * GATHER_RPW + rr;
             if (j >= bh) continue;
             const int sy = sy0 + j;
             const bool row_in = sy >= 0 && sy < H;
             const uint8_t* srow = src + ((long)sy * W + sx0) * 3;
             uint8_t* drow = dst + (size_t)j * S * 3;
-            for (int c = lane; c < row_bytes; c += 64) drow[c] = (row_in && c >= x_lo && c < x_hi) ? srow[c] : (uint8_t)0;
+            // The row goes out as aligned 4-byte stores (plus up to 3 single bytes at either end).
+            // Source and destination are misaligned against each other by an arbitrary amount, so
+            // a destination word is funnelled out of the two aligned source words that hold its
+            // bytes; each of those contains at least one byte of the row, hence lies in mapped
+            // memory.  Words that straddle the frame's left or right edge are put together byte by
+            // byte (bytes outside the frame are zero).
+            const int head = (int)((4u - (unsigned)((uintptr_t)drow & 3u)) & 3u);
+            const int nd = (row_bytes - head) >> 2, tail0 = head + 4 * nd;
+            if (lane < head + (row_bytes - tail0)) {
+                const int c = lane < head ? lane : tail0 + (lane - head);
+                drow[c] = (row_in && c >= x_lo && c < x_hi) ? srow[c] : (uint8_t)0;
+            }
+            for (int i = lane; i < nd; i += 64) {
+                const int c = head + 4 * i;
+                uint32_t v = 0;
+                if (row_in) {
+                    if (c >= x_lo && c + 4 <= x_hi) {
+                        const uintptr_t sa = (uintptr_t)(srow + c);
+                        const uint32_t* p = (const uint32_t*)(sa & ~(uintptr_t)3);
+                        const uint32_t w0 = p[0];
+                        const unsigned sh = (unsigned)(sa & 3);
+                        v = sh ? __builtin_amdgcn_alignbyte(p[1], w0, sh) : w0;
+                    } else {
+#pragma unroll
+                        for (int q = 0; q < 4; ++q)
+                            if (c + q >= x_lo && c + q < x_hi) v |= (uint32_t)srow[c + q] << (8 * q);
+                    }
+                }
+                *(uint32_t*)(drow + c) = v;
+            }
         }
     }
 }
@@ -119,7 +151,7 @@ rh_status rh_launch_gather(rh_ctx* ctx, const uint8_t* frames, int F, const rh_b
     const size_t bin_vec = (size_t)S * S * 3 / 16;
     rh_prof_scope ps(ctx, RH_PROF_GATHER, 2);
     hipLaunchKernelGGL(k_bins_zero, dim3(1024), dim3(256), 0, ctx->stream, (uint4*)bins, counts, bin_vec);
-    const int bands = (RH_MB * ctx->T + 2 * ctx->cfg.halo + 7) / 8;
+    const int bands = (RH_MB * ctx->T + 2 * ctx->cfg.halo + 4 * GATHER_RPW - 1) / (4 * GATHER_RPW);
     hipLaunchKernelGGL(k_gather, dim3(4096), dim3(256), 0, ctx->stream, frames, boxes, counts, ctx->cfg.frame_h,
                        ctx->cfg.frame_w, ctx->cfg.halo, S, bands, bins);
     RH_HIP(ctx, hipGetLastError());
