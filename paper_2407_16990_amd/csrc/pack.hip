@@ -47,44 +47,59 @@ __global__ __launch_bounds__(256) void k_gather(const uint8_t* __restrict__ fram
             }
             continue;
         }
+        // Upright box: the band's rows go out as aligned 4-byte stores (plus up to 3 single bytes at
+        // either end of a row).  Source and destination are misaligned against each other by an
+        // arbitrary amount, so a destination word is funnelled out of the two aligned source words
+        // that hold its bytes; each of those contains at least one byte of the row, hence lies in
+        // mapped memory.  Words that straddle the frame's left or right edge are put together byte
+        // by byte (bytes outside the frame are zero).  The words of the whole band are dealt to the
+        // 256 threads, and a thread requests all of its words before it stores the first: the
+        // kernel lives on the number of loads in flight.
+        const int j0 = (u % bands) * (4 * GATHER_RPW), nrow = min(4 * GATHER_RPW, bh - j0);
+        if (nrow <= 0) continue;
+        const int head = (int)((4u - (unsigned)((uintptr_t)dst & 3u)) & 3u);     // the same for every row: the row pitch is a multiple of 4
+        const int nd = (row_bytes - head) >> 2, tail0 = head + 4 * nd, nends = head + (row_bytes - tail0);
+        const int tid = threadIdx.x;
+        if (tid < nrow * nends) {                                                 // the few bytes at the rows' ends
+            const int r = tid / nends, e = tid - r * nends, c = e < head ? e : tail0 + (e - head);
+            const int sy = sy0 + j0 + r;
+            const bool ok = sy >= 0 && sy < H && c >= x_lo && c < x_hi;
+            dst[(size_t)(j0 + r) * S * 3 + c] = ok ? src[((long)sy * W + sx0) * 3 + c] : (uint8_t)0;
+        }
+        constexpr int WPT = 3;                                                    // words per thread and pass
+        const int total = nrow * nd;
+        for (int t0 = 0; t0 < total; t0 += WPT * 256) {
+            uint32_t lo[WPT], hi[WPT]; int off[WPT]; unsigned sh[WPT]; bool funnel[WPT];
 #pragma unroll
-        for (int rr = 0; rr < GATHER_RPW; ++rr) {
-            const int j = (u % bands) * (4 * GATHER_RPW) + wave * GATHER_RPW + rr;
-            if (j >= bh) continue;
-            const int sy = sy0 + j;
-            const bool row_in = sy >= 0 && sy < H;
-            const uint8_t* srow = src + ((long)sy * W + sx0) * 3;
-            uint8_t* drow = dst + (size_t)j * S * 3;
-            // The row goes out as aligned 4-byte stores (plus up to 3 single bytes at either end).
-            // Source and destination are misaligned against each other by an arbitrary amount, so
-            // a destination word is funnelled out of the two aligned source words that hold its
-            // bytes; each of those contains at least one byte of the row, hence lies in mapped
-            // memory.  Words that straddle the frame's left or right edge are put together byte by
-            // byte (bytes outside the frame are zero).
-            const int head = (int)((4u - (unsigned)((uintptr_t)drow & 3u)) & 3u);
-            const int nd = (row_bytes - head) >> 2, tail0 = head + 4 * nd;
-            if (lane < head + (row_bytes - tail0)) {
-                const int c = lane < head ? lane : tail0 + (lane - head);
-                drow[c] = (row_in && c >= x_lo && c < x_hi) ? srow[c] : (uint8_t)0;
-            }
-            for (int i = lane; i < nd; i += 64) {
-                const int c = head + 4 * i;
-                uint32_t v = 0;
-                if (row_in) {
-                    if (c >= x_lo && c + 4 <= x_hi) {
-                        const uintptr_t sa = (uintptr_t)(srow + c);
+            for (int k = 0; k < WPT; ++k) {
+                const int t = t0 + k * 256 + tid;
+                funnel[k] = false; lo[k] = 0; hi[k] = 0; sh[k] = 0; off[k] = 0;
+                if (t < total) {
+                    const int r = t / nd, i = t - r * nd, c = head + 4 * i, sy = sy0 + j0 + r;
+                    off[k] = (j0 + r) * S * 3 + c;
+                    const bool row_in = sy >= 0 && sy < H;
+                    const uint8_t* sp = src + ((long)sy * W + sx0) * 3 + c;
+                    if (row_in && c >= x_lo && c + 4 <= x_hi) {
+                        const uintptr_t sa = (uintptr_t)sp;
                         const uint32_t* p = (const uint32_t*)(sa & ~(uintptr_t)3);
-                        const uint32_t w0 = p[0];
-                        const unsigned sh = (unsigned)(sa & 3);
-                        v = sh ? __builtin_amdgcn_alignbyte(p[1], w0, sh) : w0;
-                    } else {
+                        sh[k] = (unsigned)(sa & 3);
+                        lo[k] = p[0];
+                        if (sh[k]) hi[k] = p[1];
+                        funnel[k] = true;
+                    } else {                                  // outside the frame, or across its edge: rare, stored at once
+                        uint32_t w = 0;
+                        if (row_in) {
 #pragma unroll
-                        for (int q = 0; q < 4; ++q)
-                            if (c + q >= x_lo && c + q < x_hi) v |= (uint32_t)srow[c + q] << (8 * q);
+                            for (int q = 0; q < 4; ++q)
+                                if (c + q >= x_lo && c + q < x_hi) w |= (uint32_t)sp[q] << (8 * q);
+                        }
+                        *(uint32_t*)(dst + off[k]) = w;
                     }
                 }
-                *(uint32_t*)(drow + c) = v;
             }
+#pragma unroll
+            for (int k = 0; k < WPT; ++k)
+                if (funnel[k]) *(uint32_t*)(dst + off[k]) = sh[k] ? __builtin_amdgcn_alignbyte(hi[k], lo[k], sh[k]) : lo[k];
         }
     }
 }
