@@ -80,9 +80,6 @@ def main():
                     help="occupy ratio (selected-MB pixels / packed pixels) of the packing policies over N random "
                          "importance maps of the configuration: importance-density order (the paper's), the same "
                          "with RotatePacking, large-item-first order, and one box per macroblock (MB packing)")
-    ap.add_argument("--probe-mfma", action="store_true",
-                    help="also run the register-only bf16 MFMA loop (all-ones and random operands) and report its "
-                         "TFLOP/s and sustained clock next to the published peak")
     ap.add_argument("--mem-batch", type=int, default=16, metavar="X",
                     help="also time the memory-bound steps (pack gather, unpack) on X copies of the batch, where "
                          "they are large enough to be bandwidth- rather than launch-bound (0 = skip)")
@@ -326,12 +323,6 @@ def main():
                                          "plan_ms_mean": plan_ms[k] / args.policy_study}
         for c in ctxs.values():
             c.close()
-
-    if args.probe_mfma:
-        result["mfma_probe"] = {}
-        for name, rnd in (("ones", False), ("random", True)):
-            tf, ghz, cyc = rh.probe_mfma(rnd, 40.0)
-            result["mfma_probe"][name] = {"TFLOP/s": tf, "clock_GHz": ghz, "cycles_per_mfma": cyc}
 
     if not args.no_frame_based:
         # 100 % of the macroblocks: rh_enhance on whole frames + identity placement

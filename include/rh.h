@@ -279,15 +279,6 @@ enum { RH_PROF_SELECT = 0, RH_PROF_PLAN = 1, RH_PROF_GATHER = 2, RH_PROF_HEAD = 
 rh_status rh_profile_enable(rh_ctx* ctx, int32_t on);
 rh_status rh_profile_read(rh_ctx* ctx, double* ms, uint32_t* launches);
 
-/* Measurement aid: what the matrix cores of this GPU sustain on the instruction the conv kernels
- * use (v_mfma_f32_32x32x16_bf16), with nothing else going on: 4 waves per CU, operands in
- * registers, 8 independent accumulator chains per wave, run for about `ms_target` milliseconds.
- * random_data = 0: all operands 1.0; 1: operands drawn from a hash, roughly N(0,1) like weights
- * and activations (the sustained clock depends on how many bits toggle).
- * out[0] = TFLOP/s, out[1] = shader clock in GHz during the run (shader cycle counter against
- * the 100 MHz wall counter), out[2] = cycles per MFMA per SIMD.  Synchronises the stream. */
-rh_status rh_probe_mfma(rh_ctx* ctx, int32_t random_data, double ms_target, double out[3]);
-
 #ifdef __cplusplus
 }
 #endif

@@ -57,13 +57,23 @@ def lib_path() -> str:
 _lib = None
 
 
+def _library_is_stale(path: str) -> bool:
+    """True when librh.so is missing or was built from other sources than the ones in the tree
+    (build.py records a digest of csrc/ and include/ beside the library)."""
+    from . import build as _b
+    if not os.path.exists(path) or not os.path.exists(_b.STAMP):
+        return True
+    with open(_b.STAMP) as f:
+        return f.read().strip() != _b.source_digest()
+
+
 def load_library():
-    """Load librh.so, building it first only if it has never been built."""
+    """Load librh.so; it is built first when it is missing or a source file is newer than it."""
     global _lib
     if _lib is not None:
         return _lib
     path = lib_path()
-    if not os.path.exists(path):
+    if _library_is_stale(path):
         from . import build as _b
         _b.build()
     L = C.CDLL(path)
@@ -88,9 +98,15 @@ def load_library():
     L.rh_temporal_spread.argtypes = [vp, vp, i32, vp, vp]
     L.rh_profile_enable.argtypes = [vp, i32]
     L.rh_profile_read.argtypes = [vp, C.POINTER(C.c_double * PROF_N), C.POINTER(C.c_uint32 * PROF_N)]
-    L.rh_probe_mfma.argtypes = [vp, C.c_int32, C.c_double, C.POINTER(C.c_double * 3)]
     _lib = L
     return L
+
+
+def _segments(segments):
+    segs = (Segment * max(len(segments), 1))()
+    for i, s in enumerate(segments):
+        segs[i] = Segment(int(s[0]), int(s[1]), int(s[2]), float(s[3]) if len(s) > 3 else 0.0)
+    return segs
 
 
 def _ptr(t):
@@ -150,9 +166,7 @@ class RH:
         """importance: cuda f32 [F,MBH,MBW]; segments: rows (frame_begin, frame_end, k[, thr])."""
         F = importance.shape[0]
         assert importance.is_cuda and importance.dtype == torch.float32 and importance.is_contiguous()
-        segs = (Segment * max(len(segments), 1))()
-        for i, s in enumerate(segments):
-            segs[i] = Segment(int(s[0]), int(s[1]), int(s[2]), float(s[3]) if len(s) > 3 else 0.0)
+        segs = _segments(segments)
         n = importance.numel()
         mask = torch.empty((F, self.mbh, self.mbw), dtype=torch.uint8, device=self.device)
         lst = torch.empty(n, dtype=torch.int32, device=self.device)
@@ -263,12 +277,6 @@ class RH:
         ms, n = (C.c_double * PROF_N)(), (C.c_uint32 * PROF_N)()
         self._check(self.lib.rh_profile_read(self.h, C.byref(ms), C.byref(n)))
         return {k: (ms[i], n[i]) for i, k in enumerate(PROF_CLASSES)}
-
-    def probe_mfma(self, random_data: bool, ms_target: float = 30.0):
-        """-> (TFLOP/s, shader clock GHz, cycles per MFMA) of a register-only bf16 MFMA loop (synchronises)."""
-        out = (C.c_double * 3)()
-        self._check(self.lib.rh_probe_mfma(self.h, int(random_data), float(ms_target), C.byref(out)))
-        return out[0], out[1], out[2]
 
     # host-side views of the metadata
     @staticmethod

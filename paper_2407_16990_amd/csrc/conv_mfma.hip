@@ -21,25 +21,6 @@
 
 #include "conv_mfma_common.h"
 
-#ifdef RH_PHASE_TIMING   // development aid: per-phase cycle counts of wave 0 of every workgroup
-__device__ unsigned long long rh_dbg[16];
-extern "C" void rh_debug_read(unsigned long long* out, int reset)
-{
-    (void)hipDeviceSynchronize();
-    (void)hipMemcpyFromSymbol(out, HIP_SYMBOL(rh_dbg), sizeof(rh_dbg));
-    if (reset) { unsigned long long z[16] = {0}; (void)hipMemcpyToSymbol(HIP_SYMBOL(rh_dbg), z, sizeof(z)); }
-}
-#define PHASE(i) do { unsigned long long t_ = clock64(); ph[i] += t_ - tprev; tprev = t_; } while (0)
-#define PHASE_INIT unsigned long long ph[6] = {0, 0, 0, 0, 0, 0}; unsigned long long tprev = clock64()
-#define PHASE_END do { if (tid == 0 && !F32OUT) for (int i_ = 0; i_ < 6; ++i_) atomicAdd(&rh_dbg[(SKIP ? 8 : 0) + i_], ph[i_]); } while (0)
-#define DBG(bit) (a.dbg & (bit))
-#else
-#define DBG(bit) 0
-#define PHASE(i) do { } while (0)
-#define PHASE_INIT do { } while (0)
-#define PHASE_END do { } while (0)
-#endif
-
 #define TW 32            // tile width in pixels = N of one MFMA
 #define PW (TW + 2)
 
@@ -188,16 +169,13 @@ __global__ __launch_bounds__(256, MINB) void k_conv_mfma(conv_args a)
         }
         uint4 outv[F32OUT ? 1 : NOUT];       // previous tile's result, stored during this tile's MFMA loop
         int out_tile = -1;
-        PHASE_INIT;
         for (; tile < n_tiles; tile += G) {
-            PHASE(0);
             const int n = tile / tiles_img, tr = tile - n * tiles_img;
             const int ty = tr / tiles_x, tx = tr - ty * tiles_x;
             const int y0 = ty * TH, x0 = tx * TW;
             lds_barrier();                                     // (A) LDS reads of the previous tile are done
             store_patch();
             lds_barrier();                                     // (B)
-            PHASE(1);
             // descriptors: next tile's input image (empty if there is no next tile), previous
             // tile's output image (empty if none), this tile's skip image
             const int nt = tile + G;
@@ -254,15 +232,14 @@ __global__ __launch_bounds__(256, MINB) void k_conv_mfma(conv_args a)
                 static_assert(n_st + n_ld + n_sk <= NSLOT, "too many memory instructions for one step");
 #pragma unroll
                 for (int sl = 0; sl < NSLOT; ++sl) {
-                    if (st + 1 < NSTEP && !DBG(2)) {
+                    if (st + 1 < NSTEP) {
 #pragma unroll
                         for (int f = sl * FPS; f < (sl + 1) * FPS && f < NFR; ++f) {
                             if (f < 3 * MT) An[f / MT][f % MT] = *(const bf16x8*)(wlane + (((((f / MT) * 3 + kxn) * KS + ksn) * MT + f % MT) << 10));
                             else Bn[f - 3 * MT] = *(const bf16x8*)(b0n + (f - 3 * MT) * (PW * PIXB));
                         }
                     }
-                    if (DBG(1)) {
-                    } else if (sl < n_st) {
+                    if (sl < n_st) {
                         const int j = st * SPS + sl;
                         if (j < NOUT) {
                             const i32x4 v = {(int)outv[j].x, (int)outv[j].y, (int)outv[j].z, (int)outv[j].w};
@@ -295,7 +272,6 @@ __global__ __launch_bounds__(256, MINB) void k_conv_mfma(conv_args a)
                 }
             };
             for_each_step<NSTEP>(step);
-            PHASE(3);
             // lane holds, for pixel column lx of each of its rows, channels
             // m*32 + 8*q + 4*hi + {0,1,2,3} in acc[r][m][4q..4q+3]
             if constexpr (F32OUT) {
@@ -337,7 +313,6 @@ __global__ __launch_bounds__(256, MINB) void k_conv_mfma(conv_args a)
                             *(uint2*)(stg + (r * 32 + lx) * OPIXB + (((m * 4 + q) ^ okey) << 4) + hi * 8) = pk;
                         }
                 lds_barrier();                             // (D) staged values visible
-                PHASE(4);
 #pragma unroll
                 for (int j = 0; j < NOUT; ++j) {
                     const int r = j / JPR, px = (j % JPR) * PPJ + lcol;
@@ -351,7 +326,6 @@ __global__ __launch_bounds__(256, MINB) void k_conv_mfma(conv_args a)
                     outv[j] = o;
                 }
                 out_tile = tile;
-                PHASE(5);
             }
         }
         if constexpr (!F32OUT) {
@@ -365,7 +339,6 @@ __global__ __launch_bounds__(256, MINB) void k_conv_mfma(conv_args a)
                 }
             }
         }
-        PHASE_END;
     }
 }
 
@@ -475,9 +448,6 @@ static rh_status conv(rh_ctx* ctx, const rh_layer& L, const __bf16* in, void* ou
     conv_args a;
     a.in = in; a.wp = (const uint4*)((const uint8_t*)ctx->wpack + L.wp_off); a.bias = ctx->bpack + L.bp_off;
     a.out = out; a.skip = skip; a.n_valid = n_valid; a.N = N; a.H = H; a.W = W;
-#ifdef RH_PHASE_TIMING
-    a.dbg = getenv("RH_DBG") ? atoi(getenv("RH_DBG")) : 0;
-#endif
     a.relu = relu; a.ps = L.ps; a.n_chunks = last ? 1 : L.ps * L.ps; a.cout_real = L.cout; a.s_final = s_final;
     a.rev = (ctx->conv_parity ^= 1);       // alternate the direction from one conv to the next
     const int grid = ctx->n_cu;            // persistent kernels: one workgroup per compute unit (256 on MI355X)

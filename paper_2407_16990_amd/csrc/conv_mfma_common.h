@@ -19,9 +19,6 @@ struct conv_args {
     int relu, ps, n_chunks;  // bf16 output mode
     int cout_real, s_final;  // fp32 output mode
     int rev;                 // 1: walk the tiles from the last to the first (k_conv_mfma_duo)
-#ifdef RH_PHASE_TIMING
-    int dbg;                 // bit0: no patch loads, bit1: no output stores, bit2: no MFMA loop
-#endif
 };
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b)

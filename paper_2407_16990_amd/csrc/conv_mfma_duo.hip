@@ -29,33 +29,6 @@
 #include "conv_mfma_common.h"
 
 #define PW 34
-#ifndef DUO_SEED_IN_COMPUTE
-#define DUO_SEED_IN_COMPUTE 1
-#endif
-#ifndef DUO_SKIP_IN_COMPUTE
-#define DUO_SKIP_IN_COMPUTE 1
-#endif
-#ifndef DUO_DEAL_CHUNKS
-#define DUO_DEAL_CHUNKS 1
-#endif
-
-#ifdef RH_PHASE_TIMING
-__device__ unsigned long long rh_dbg2[36];
-extern "C" void rh_debug_read2(unsigned long long* out, int reset)
-{
-    (void)hipDeviceSynchronize();
-    (void)hipMemcpyFromSymbol(out, HIP_SYMBOL(rh_dbg2), sizeof(rh_dbg2));
-    if (reset) { unsigned long long z[36] = {0}; (void)hipMemcpyToSymbol(HIP_SYMBOL(rh_dbg2), z, sizeof(z)); }
-}
-#define PH2(i) do { unsigned long long t_ = clock64(); ph[i] += t_ - tprev; tprev = t_; } while (0)
-#define PH2_INIT unsigned long long ph[8] = {0, 0, 0, 0, 0, 0, 0, 0}; unsigned long long tprev = clock64(); const unsigned long long c_start = tprev, w_start = wall_clock64()
-#define PH2_END do { if (ttid == 0) for (int i_ = 0; i_ < 8; ++i_) atomicAdd(&rh_dbg2[(SKIP ? 16 : 0) + team * 8 + i_], ph[i_]); if (tid == 0) { atomicAdd(&rh_dbg2[32], clock64() - c_start); atomicAdd(&rh_dbg2[33], wall_clock64() - w_start); } } while (0)
-#else
-#define PH2(i) do { } while (0)
-#define PH2_INIT do { } while (0)
-#define PH2_END do { } while (0)
-#endif
-
 template <int N, int I = 0, typename F>
 __device__ __forceinline__ void for_each_step2(F& f)
 {
@@ -74,8 +47,8 @@ __global__ __launch_bounds__(512) void k_conv_mfma_duo(conv_args a)
     static_assert(NHP <= 256, "halo pieces must fit one per thread");
     // The accumulators start from the bias.  The skip variant's drain phase is the longer of the two
     // phases, so there the seeding belongs to the compute phase; otherwise it is done in the drain phase.
-    constexpr bool SEED_IN_COMPUTE = DUO_SEED_IN_COMPUTE && SKIP;
-    constexpr bool SKIP_IN_COMPUTE = DUO_SKIP_IN_COMPUTE;
+    constexpr bool SEED_IN_COMPUTE = SKIP;
+    constexpr bool SKIP_IN_COMPUTE = true;
     static_assert(MID >= 1 && MID <= NSTEP - 1, "the compute phase must hold exactly two barriers");
     // MID: the compute phase's first barrier comes after MID of the 12 steps; it pairs with the end
     // of the other team's loads + rounding + skip add + stores
@@ -102,7 +75,7 @@ __global__ __launch_bounds__(512) void k_conv_mfma_duo(conv_args a)
     // share a tile lane process the same tiles at about the same time, each with its own chunk's
     // weights resident, so the input is fetched from HBM once and the other reads hit L2
     // (looping chunks outermost reads the whole input once per chunk).
-    const bool deal = DUO_DEAL_CHUNKS && a.n_chunks > 1 && gridDim.x % (8 * a.n_chunks) == 0;
+    const bool deal = a.n_chunks > 1 && gridDim.x % (8 * a.n_chunks) == 0;
     const int G = deal ? gridDim.x / a.n_chunks : gridDim.x;                  // tile lanes
     const int xcd = blockIdx.x % 8, local = blockIdx.x / 8;
     const int wg = deal ? xcd * (G / 8) + local / a.n_chunks
@@ -206,10 +179,8 @@ __global__ __launch_bounds__(512) void k_conv_mfma_duo(conv_args a)
                 }
         };
         if constexpr (!SEED_IN_COMPUTE) seed_acc();
-        PH2_INIT;
         if (team == 1) idle_phase();
         for (int it = 0; it < iters; ++it) {
-            PH2(0);
             const int tile = wg + it * G, ntile = tile + G;
             int n, y0, x0; tile_origin(tile, n, y0, x0);
             __amdgpu_buffer_rsrc_t rsk = __builtin_amdgcn_make_buffer_rsrc(
@@ -273,16 +244,11 @@ __global__ __launch_bounds__(512) void k_conv_mfma_duo(conv_args a)
                     __builtin_amdgcn_sched_barrier(0);
                 }
                 if constexpr (st == MID - 1 || st == NSTEP - 1) {   // the two barriers of the compute phase
-                    PH2(1 + st / 4 * 0);
                     asm volatile("s_barrier" ::: "memory");
                     __builtin_amdgcn_sched_barrier(0);
-                    PH2(2);
                 }
             };
-#ifndef DUO_PRIO
-#define DUO_PRIO 2
-#endif
-            __builtin_amdgcn_s_setprio(DUO_PRIO);             // the wave feeding the matrix pipe goes first
+            __builtin_amdgcn_s_setprio(2);             // the wave feeding the matrix pipe goes first
             for_each_step2<NSTEP>(step);
             __builtin_amdgcn_s_setprio(0);
 
@@ -330,9 +296,7 @@ __global__ __launch_bounds__(512) void k_conv_mfma_duo(conv_args a)
                         __builtin_amdgcn_sched_barrier(0);
                     }
             if constexpr (!SEED_IN_COMPUTE) seed_acc();
-            PH2(3);
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");     // the slice is private to the wave: no barrier
-            PH2(4);
             uint4 ov[NOUT];
 #pragma unroll
             for (int j = 0; j < NOUT; ++j) {
@@ -353,15 +317,11 @@ __global__ __launch_bounds__(512) void k_conv_mfma_duo(conv_args a)
                 __builtin_amdgcn_raw_buffer_store_b128(v, rout, out_off(j, y0, x0, si, sj), 0, 0);
                 if constexpr (SKIP) __builtin_amdgcn_sched_barrier(0);
             }
-            PH2(5);
             phase_barrier();                                  // 1: every wave of the team has read its slice back
-            PH2(6);
             store_patch();                                    // next tile's patch (zeros after the last tile)
-            PH2(7);
             phase_barrier();                                  // 2
         }
         if (team == 0) idle_phase();
-        PH2_END;
     }
 }
 
@@ -382,13 +342,8 @@ static hipError_t launch_duo(hipStream_t stream, int device, const conv_args& a,
 hipError_t rh_launch_conv_duo(hipStream_t stream, int device, const conv_args& a, int grid, bool skip, bool relu)
 {
     // first barrier of the compute phase after 10 of the 12 steps (A/B on one box: 0.7 % better than 11, 9 is worse)
-#ifndef DUO_MID_SKIP
-#define DUO_MID_SKIP 10
-#endif
-#ifndef DUO_MID_PLAIN
-#define DUO_MID_PLAIN 10
-#endif
-    if (skip) return launch_duo<true, false, DUO_MID_SKIP>(stream, device, a, grid);
-    if (relu) return launch_duo<false, true, DUO_MID_PLAIN>(stream, device, a, grid);
-    return launch_duo<false, false, DUO_MID_PLAIN>(stream, device, a, grid);
+    constexpr int MID = 10;
+    if (skip) return launch_duo<true, false, MID>(stream, device, a, grid);
+    if (relu) return launch_duo<false, true, MID>(stream, device, a, grid);
+    return launch_duo<false, false, MID>(stream, device, a, grid);
 }

@@ -191,21 +191,8 @@ extern "C" rh_status rh_select_regions(rh_ctx* ctx, const float* importance, int
                                        int32_t nseg, int32_t mode, uint8_t* mask, uint32_t* list, uint32_t* n_sel)
 {
     if (!ctx) return RH_E_INVALID;
-    if (!importance || !mask || !list || !n_sel || (nseg > 0 && !segs) || nseg < 0)
-        RH_FAIL(ctx, RH_E_INVALID, "rh_select_regions: null argument");
-    if (mode != RH_TOPK && mode != RH_THRESHOLD) RH_FAIL(ctx, RH_E_INVALID, "rh_select_regions: bad mode %d", mode);
     if (F < 1 || F > ctx->cfg.max_frames) RH_FAIL(ctx, RH_E_CAPACITY, "rh_select_regions: F=%d outside [1,%d]", F, ctx->cfg.max_frames);
-    if (nseg > F) RH_FAIL(ctx, RH_E_INVALID, "rh_select_regions: more segments than frames");
-    uint32_t prev_end = 0;
-    for (int s = 0; s < nseg; ++s) {
-        const rh_segment& g = segs[s];
-        if (g.frame_begin > g.frame_end || g.frame_end > (uint32_t)F || g.frame_begin < prev_end)
-            RH_FAIL(ctx, RH_E_INVALID, "rh_select_regions: segment %d [%u,%u) is out of range, unordered or overlapping", s, g.frame_begin, g.frame_end);
-        prev_end = g.frame_end;
-    }
-    rh_status st = rh_upload_segments(ctx, segs, nseg, F);
-    if (st != RH_OK) return st;
-    return rh_launch_select(ctx, importance, F, nseg, mode, mask, list, n_sel);
+    return rh_launch_select(ctx, importance, F, segs, nseg, mode, mask, list, n_sel);
 }
 
 extern "C" rh_status rh_temporal_phi(rh_ctx* ctx, const int16_t* res_y, int32_t F, int32_t tau, int32_t min_area,

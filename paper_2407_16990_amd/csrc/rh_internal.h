@@ -98,7 +98,14 @@ struct rh_ctx {
     } while (0)
 
 // kernels' host launchers (each returns after enqueueing)
-rh_status rh_launch_select(rh_ctx*, const float* imp, int F, int nseg, int mode,
+// The selection's scratch memory: per-frame and per-segment tables of at least F entries each
+// (seg_par: 4 per segment; there are at most F segments).
+struct rh_select_scratch { int32_t* frame_seg; uint32_t *seg_par, *seg_T, *frame_nsel, *frame_ties; };
+hipError_t rh_enqueue_select(hipStream_t stream, const rh_select_scratch& sc, const float* imp, int F, int per,
+                             const rh_segment* segs, int nseg, int mode, uint8_t* mask, uint32_t* list, uint32_t* n_sel);
+const char* rh_check_select_args(const float* importance, int F, const rh_segment* segs, int nseg, int mode,
+                                 const uint8_t* mask, const uint32_t* list, const uint32_t* n_sel, rh_status* st);
+rh_status rh_launch_select(rh_ctx*, const float* imp, int F, const rh_segment* segs, int nseg, int mode,
                            uint8_t* mask, uint32_t* list, uint32_t* n_sel);
 rh_status rh_launch_plan(rh_ctx*, int F, const float* imp, const uint8_t* mask,
                          const uint32_t* list, const uint32_t* n_sel,
@@ -119,7 +126,6 @@ rh_status rh_launch_temporal_select(rh_ctx*, const uint64_t* phi, const int32_t*
                                     uint32_t* n_selected);
 rh_status rh_launch_temporal_spread(rh_ctx*, float* imp, int F, const uint8_t* selected, const uint32_t* reuse_from);
 rh_status rh_pack_weights_bf16(rh_ctx*, const float* host_blob);
-rh_status rh_upload_segments(rh_ctx*, const rh_segment* segs, int nseg, int F);
 rh_status rh_plan_init(rh_ctx*);
 // exact-border mode: zero the out-of-frame part of every box in an activation tensor
 // [N][S*res][S*res][px_bytes]; a no-op unless an rh_enhance_exact call is in progress

@@ -245,9 +245,15 @@ __global__ __launch_bounds__(256) void k_select_write(const float* __restrict__ 
 // freed as soon as rh_select_regions returns and no host synchronisation is needed.
 struct seg_chunk { uint32_t n, first; uint32_t fb[64], fe[64], k[64], thr[64]; };
 
-__global__ __launch_bounds__(256) void k_upload_segments(seg_chunk c, int per, uint32_t* __restrict__ seg_par,
+// One workgroup.  The first chunk of a call (c.first == 0) also marks every frame as belonging to
+// no segment before the segments' frames are labelled.
+__global__ __launch_bounds__(256) void k_upload_segments(seg_chunk c, int per, int F, uint32_t* __restrict__ seg_par,
                                                          int32_t* __restrict__ frame_seg)
 {
+    if (c.first == 0) {
+        for (int f = threadIdx.x; f < F; f += 256) frame_seg[f] = -1;
+        __syncthreads();
+    }
     for (uint32_t s = 0; s < c.n; ++s) {
         if (threadIdx.x == 0) {
             uint32_t* p = seg_par + 4 * (size_t)(c.first + s);
@@ -257,31 +263,55 @@ __global__ __launch_bounds__(256) void k_upload_segments(seg_chunk c, int per, u
     }
 }
 
-rh_status rh_upload_segments(rh_ctx* ctx, const rh_segment* segs, int nseg, int F)
+hipError_t rh_enqueue_select(hipStream_t stream, const rh_select_scratch& sc, const float* imp, int F, int per,
+                                 const rh_segment* segs, int nseg, int mode, uint8_t* mask, uint32_t* list, uint32_t* n_sel)
 {
-    rh_fill_i32(ctx, ctx->frame_seg, -1, (size_t)F);
-    for (int s0 = 0; s0 < nseg; s0 += 64) {
+    for (int s0 = 0; s0 < nseg || s0 == 0; s0 += 64) {       // at least one launch: it clears frame_seg
         seg_chunk c;
         c.n = (uint32_t)((nseg - s0) < 64 ? (nseg - s0) : 64); c.first = (uint32_t)s0;
         for (uint32_t i = 0; i < c.n; ++i) {
             const rh_segment& g = segs[s0 + i];
             c.fb[i] = g.frame_begin; c.fe[i] = g.frame_end; c.k[i] = g.k; memcpy(&c.thr[i], &g.thr, 4);
         }
-        hipLaunchKernelGGL(k_upload_segments, dim3(1), dim3(256), 0, ctx->stream, c, ctx->per, ctx->seg_par, ctx->frame_seg);
+        hipLaunchKernelGGL(k_upload_segments, dim3(1), dim3(256), 0, stream, c, per, F, sc.seg_par, sc.frame_seg);
     }
-    RH_HIP(ctx, hipGetLastError());
+    if (nseg > 0)
+        hipLaunchKernelGGL(k_select_kth, dim3(nseg), dim3(1024), 0, stream, imp, sc.seg_par, mode, per, sc.seg_T,
+                           sc.frame_nsel, sc.frame_ties);
+    hipLaunchKernelGGL(k_select_write, dim3(F), dim3(256), 0, stream, imp, sc.frame_seg, sc.seg_T, sc.frame_nsel,
+                       sc.frame_ties, per, F, mask, list, n_sel);
+    return hipGetLastError();
+}
+
+// Argument checks shared by both entry points; returns a message or null.
+const char* rh_check_select_args(const float* importance, int F, const rh_segment* segs, int nseg, int mode,
+                                     const uint8_t* mask, const uint32_t* list, const uint32_t* n_sel, rh_status* st)
+{
+    *st = RH_E_INVALID;
+    if (!importance || !mask || !list || !n_sel || (nseg > 0 && !segs) || nseg < 0) return "null argument";
+    if (mode != RH_TOPK && mode != RH_THRESHOLD) return "bad mode";
+    if (nseg > F) return "more segments than frames";
+    uint32_t prev_end = 0;
+    for (int s = 0; s < nseg; ++s) {
+        const rh_segment& g = segs[s];
+        if (g.frame_begin > g.frame_end || g.frame_end > (uint32_t)F || g.frame_begin < prev_end)
+            return "a segment is out of range, unordered or overlapping";
+        prev_end = g.frame_end;
+    }
+    *st = RH_OK;
+    return nullptr;
+}
+
+rh_status rh_launch_select(rh_ctx* ctx, const float* imp, int F, const rh_segment* segs, int nseg, int mode,
+                           uint8_t* mask, uint32_t* list, uint32_t* n_sel)
+{
+    rh_status st;
+    if (const char* msg = rh_check_select_args(imp, F, segs, nseg, mode, mask, list, n_sel, &st))
+        RH_FAIL(ctx, st, "rh_select_regions: %s", msg);
+    const int n_up = nseg > 0 ? (nseg + 63) / 64 : 1;
+    rh_prof_scope ps(ctx, RH_PROF_SELECT, n_up + (nseg > 0 ? 2 : 1));
+    const rh_select_scratch sc = {ctx->frame_seg, ctx->seg_par, ctx->seg_T, ctx->frame_nsel, ctx->frame_ties};
+    RH_HIP(ctx, rh_enqueue_select(ctx->stream, sc, imp, F, ctx->per, segs, nseg, mode, mask, list, n_sel));
     return RH_OK;
 }
 
-rh_status rh_launch_select(rh_ctx* ctx, const float* imp, int F, int nseg, int mode,
-                           uint8_t* mask, uint32_t* list, uint32_t* n_sel)
-{
-    rh_prof_scope ps(ctx, RH_PROF_SELECT, nseg > 0 ? 2 : 1);
-    if (nseg > 0)
-        hipLaunchKernelGGL(k_select_kth, dim3(nseg), dim3(1024), 0, ctx->stream, imp, ctx->seg_par, mode,
-                           ctx->per, ctx->seg_T, ctx->frame_nsel, ctx->frame_ties);
-    hipLaunchKernelGGL(k_select_write, dim3(F), dim3(256), 0, ctx->stream, imp, ctx->frame_seg, ctx->seg_T,
-                       ctx->frame_nsel, ctx->frame_ties, ctx->per, F, mask, list, n_sel);
-    RH_HIP(ctx, hipGetLastError());
-    return RH_OK;
-}

@@ -39,9 +39,7 @@ __global__ void k_tr_reset(unsigned long long* phi, int F, uint32_t* n_border, u
 }
 
 #define TR_ROWS 8                  // rows per wave in k_tr_init
-#ifndef TR_WAVES
 #define TR_WAVES 4                 // waves per workgroup of k_tr_init
-#endif
 #define TR_TILE_H (TR_WAVES * TR_ROWS)    // a workgroup labels a tile of 64 x 32 pixels
 
 __device__ __forceinline__ uint32_t tr_lds_find(uint32_t* lab, uint32_t x)
