@@ -98,8 +98,12 @@ def load_library():
     L.rh_temporal_spread.argtypes = [vp, vp, i32, vp, vp]
     L.rh_profile_enable.argtypes = [vp, i32]
     L.rh_profile_read.argtypes = [vp, C.POINTER(C.c_double * PROF_N), C.POINTER(C.c_uint32 * PROF_N)]
+    L.rh_select_regions_noalloc.argtypes = [vp, i32, i32, i32, C.POINTER(Segment), i32, i32, vp, vp, vp, vp]
     _lib = L
     return L
+
+
+NOALLOC_MAX_FRAMES = 4096      # RH_NOALLOC_MAX_FRAMES of include/rh_noalloc.h
 
 
 def _segments(segments):
@@ -107,6 +111,21 @@ def _segments(segments):
     for i, s in enumerate(segments):
         segs[i] = Segment(int(s[0]), int(s[1]), int(s[2]), float(s[3]) if len(s) > 3 else 0.0)
     return segs
+
+
+def select_regions_noalloc(importance: torch.Tensor, segments, mask: torch.Tensor, lst: torch.Tensor,
+                           n_sel: torch.Tensor, mode="topk", stream=None) -> None:
+    """rh_select_regions_noalloc: the selection without a context and without any allocation; the
+    caller passes every output (mask u8 [F,MBH,MBW], lst int32 [F*MBH*MBW], n_sel int32 [1])."""
+    L = load_library()
+    F, mbh, mbw = importance.shape
+    assert importance.is_cuda and importance.dtype == torch.float32 and importance.is_contiguous()
+    assert mask.is_cuda and mask.numel() >= importance.numel() and lst.numel() >= importance.numel() and n_sel.numel() >= 1
+    stream = stream if stream is not None else torch.cuda.current_stream(importance.device)
+    st = L.rh_select_regions_noalloc(_ptr(importance), F, mbh, mbw, _segments(segments), len(segments), MODE[mode],
+                                     _ptr(mask), _ptr(lst), _ptr(n_sel), C.c_void_p(stream.cuda_stream))
+    if st != 0:
+        raise RhError(st, "rh_select_regions_noalloc failed (see include/rh_noalloc.h)")
 
 
 def _ptr(t):

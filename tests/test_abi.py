@@ -10,7 +10,8 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def declared_functions():
-    text = open(os.path.join(ROOT, "include", "rh.h")).read()
+    inc = os.path.join(ROOT, "include")
+    text = "".join(open(os.path.join(inc, n)).read() for n in sorted(os.listdir(inc)) if n.endswith(".h"))
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(rh_[a-z_]+)\s*\(", text)))
 
@@ -21,7 +22,7 @@ def test_library_exports_every_declared_symbol():
     names = declared_functions()
     assert {"rh_create", "rh_destroy", "rh_select_regions", "rh_pack", "rh_enhance", "rh_unpack",
             "rh_read_counts", "rh_last_error", "rh_budget", "rh_identity_places", "rh_set_stream",
-            "rh_temporal_phi", "rh_temporal_select", "rh_temporal_spread"} <= set(names)
+            "rh_temporal_phi", "rh_temporal_select", "rh_temporal_spread", "rh_select_regions_noalloc"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
@@ -68,3 +69,5 @@ def test_new_entry_points_reject_null_arguments():
     assert lib.rh_temporal_phi(None, None, 1, 0, 1, None) == 1
     assert lib.rh_temporal_select(None, None, None, 1, 1, None, None, None, None) == 1
     assert lib.rh_temporal_spread(None, None, 1, None, None) == 1
+    assert lib.rh_select_regions_noalloc(None, 1, 1, 1, None, 0, 0, None, None, None, None) == 1
+    assert lib.rh_select_regions_noalloc(None, 5000, 1, 1, None, 0, 0, None, None, None, None) == 3   # beyond the fixed tables
