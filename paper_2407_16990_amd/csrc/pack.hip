@@ -2,104 +2,120 @@
 // Bins are zero outside the boxes and where a halo leaves the frame.
 #include "rh_internal.h"
 
-// Zero bins [0, n_bins).  bin_vec = 16-byte vectors per bin.
-__global__ __launch_bounds__(256) void k_bins_zero(uint4* __restrict__ bins, const uint32_t* __restrict__ counts,
-                                                   size_t bin_vec)
+// One launch writes every byte of bins [0, n_bins) exactly once.  A work unit is a band of RB rows
+// of one bin, put together in LDS and written out as whole 16-byte vectors (the band is one
+// contiguous piece of the bin tensor):
+//   1. the band's LDS image is cleared and the box list is scanned for boxes of this bin that
+//      reach into the band (a 2-byte field per box; the few that match are listed in LDS);
+//   2. every listed box adds its pixels: the frame's bytes are fetched as aligned 4-byte words and
+//      shifted into place (frame and bin positions are misaligned against each other by an
+//      arbitrary amount), bytes outside the frame or outside the box are masked to zero, and the
+//      word is OR-ed into the cleared image, so boxes that meet inside one word compose;
+//   3. the image goes to the bin.
+// Box rectangles of one bin are disjoint, so the result does not depend on the order of the boxes.
+#define GATHER_LIST 64
+
+__device__ __forceinline__ uint32_t byte_mask(int lo_cut, int hi_cut)      // bytes [lo_cut, hi_cut) of a word, cuts in 0..4
 {
-    const size_t n = (size_t)counts[1] * bin_vec;
-    const uint4 z = make_uint4(0, 0, 0, 0);
-    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) bins[i] = z;
+    const uint32_t below_hi = hi_cut >= 4 ? 0xFFFFFFFFu : ((1u << (8 * hi_cut)) - 1u);
+    const uint32_t below_lo = lo_cut >= 4 ? 0xFFFFFFFFu : ((1u << (8 * lo_cut)) - 1u);
+    return below_hi & ~below_lo;
 }
 
-// A work unit is a band of 4 * GATHER_RPW rows of one box (as stored in the bin); workgroups stride over the
-// units, each wave copies GATHER_RPW rows, lanes run along the row's bytes (contiguous in both the frame
-// and the bin).  Box rectangles of one bin are disjoint, so no two units write the same byte.
-#ifndef GATHER_RPW
-#define GATHER_RPW 2
-#endif
+// Adds the part of box b that lies in rows [y0, y0 + rows) of its bin to the band image.
+__device__ __forceinline__ void gather_box(const rh_box& b, const uint8_t* __restrict__ frames, int H, int W, int halo,
+                                           int S, int y0, int rows, uint32_t* img)
+{
+    const int bw = RH_MB * b.wmb + 2 * halo, bh = RH_MB * b.hmb + 2 * halo;
+    const int sx0 = RH_MB * b.mbx0 - halo, sy0 = RH_MB * b.mby0 - halo;
+    const int n_rows = b.rot ? bw : bh, n_cols = b.rot ? bh : bw;          // as stored in the bin
+    const int j0 = max(0, y0 - (int)b.by), j1 = min(n_rows, y0 + rows - (int)b.by);
+    if (j1 <= j0) return;
+    const uint8_t* src = frames + (size_t)b.frame * H * W * 3;
+    const int L = n_cols * 3, pitch_w = S * 3 / 4;                         // row length in bytes; band row pitch in words
+    const int dofs = (((int)b.by + j0 - y0) * S + (int)b.bx) * 3;          // byte offset of the first stored row in the image
+    const int head = dofs & 3, ndw = (head + L + 3) >> 2, items = (j1 - j0) * ndw;
+    for (int t = threadIdx.x; t < items; t += 256) {
+        const int r = t / ndw, kk = t - r * ndw, j = j0 + r;
+        const int c = 4 * kk - head;                                       // row byte held by the word's first byte (may be < 0)
+        uint32_t v = 0;
+        if (b.rot) {
+            // turned box: stored row j holds box column j, so its bytes come from one source column
+            const int sx = sx0 + j;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int cc = c + q;
+                if (cc < 0 || cc >= L) continue;
+                const int jj = cc / 3, ch = cc - 3 * jj, sy = sy0 + jj;
+                if (sx >= 0 && sx < W && sy >= 0 && sy < H) v |= (uint32_t)src[((size_t)sy * W + sx) * 3 + ch] << (8 * q);
+            }
+        } else {
+            const int sy = sy0 + j;
+            if (sy < 0 || sy >= H) continue;
+            const int vb = max(0, -sx0) * 3, ve = min(bw, W - sx0) * 3;    // in-frame bytes of a row
+            const int lo_cut = min(max(vb - c, 0), 4), hi_cut = min(max(ve - c, 0), 4);
+            if (hi_cut <= lo_cut) continue;
+            const uintptr_t sa = (uintptr_t)(src + ((long)sy * W + sx0) * 3) + (long)c;
+            const uint32_t* al = (const uint32_t*)(sa & ~(uintptr_t)3);
+            const int sh = (int)(sa & 3);
+            // an aligned word is fetched only if it holds one of the wanted bytes (hence lies in mapped memory)
+            uint32_t lo = 0, hi = 0;
+            if (4 - sh > lo_cut) lo = al[0];
+            if (sh && 4 - sh < hi_cut) hi = al[1];
+            v = (sh ? __builtin_amdgcn_alignbyte(hi, lo, sh) : lo) & byte_mask(lo_cut, hi_cut);
+        }
+        if (v) atomicOr(&img[(dofs >> 2) + r * pitch_w + kk], v);
+    }
+}
+
 __global__ __launch_bounds__(256) void k_gather(const uint8_t* __restrict__ frames, const rh_box* __restrict__ boxes,
                                                 const uint32_t* __restrict__ counts, int H, int W, int halo, int S,
-                                                int bands, uint8_t* __restrict__ bins)
+                                                int RB, uint8_t* __restrict__ bins)
 {
-    const uint32_t n_units = counts[0] * (uint32_t)bands;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    for (uint32_t u = blockIdx.x; u < n_units; u += gridDim.x) {
-        const rh_box b = boxes[u / bands];
-        if (b.bin == RH_NO_BIN) continue;
-        const int bw = RH_MB * b.wmb + 2 * halo, bh = RH_MB * b.hmb + 2 * halo, row_bytes = bw * 3;
-        const int sx0 = RH_MB * b.mbx0 - halo, sy0 = RH_MB * b.mby0 - halo;
-        const int x_lo = max(0, -sx0) * 3, x_hi = min(bw, W - sx0) * 3;   // in-frame byte range of a row
-        const uint8_t* src = frames + (size_t)b.frame * H * W * 3;
-        uint8_t* dst = bins + ((size_t)b.bin * S + b.by) * S * 3 + (size_t)b.bx * 3;
-        if (b.rot) {
-            // turned box: bin row i holds box column i, so a row's bytes come from one source
-            // column (strided reads; turned boxes are the exception)
-#pragma unroll
-            for (int rr = 0; rr < GATHER_RPW; ++rr) {
-                const int i = (u % bands) * (4 * GATHER_RPW) + wave * GATHER_RPW + rr;     // bin row = box column
-                if (i >= bw) continue;
-                const int sx = sx0 + i;
-                uint8_t* drow = dst + (size_t)i * S * 3;
-                for (int c = lane; c < bh * 3; c += 64) {
-                    const int j = c / 3, ch = c - 3 * j, sy = sy0 + j;
-                    drow[c] = (sx >= 0 && sx < W && sy >= 0 && sy < H) ? src[((size_t)sy * W + sx) * 3 + ch] : (uint8_t)0;
+    extern __shared__ __attribute__((aligned(16))) uint32_t img[];         // RB * S * 3 bytes
+    __shared__ uint32_t s_list[GATHER_LIST];
+    __shared__ uint32_t s_cnt;
+    const uint32_t n_boxes = counts[0], n_bins = counts[1];
+    const int nb = (S + RB - 1) / RB;                                      // bands per bin
+    // A unit is a run of bpu bands of one bin; the box list is scanned once per unit.  Small batches
+    // take one band per unit (enough units to occupy the chip), large ones a whole bin.
+    const int bpu = (uint64_t)n_bins * (uint64_t)nb <= 2048u ? 1 : nb;
+    const int upb = (nb + bpu - 1) / bpu;                                  // units per bin
+    const int tid = threadIdx.x;
+    for (uint32_t u = blockIdx.x; u < n_bins * (uint32_t)upb; u += gridDim.x) {
+        const uint32_t bin = u / upb;
+        const int ya = (int)(u - bin * upb) * bpu * RB, yb = min(S, ya + bpu * RB);   // rows [ya, yb) of the bin
+        if (tid == 0) s_cnt = 0;
+        __syncthreads();
+        for (uint32_t i = tid; i < n_boxes; i += 256) {
+            if (boxes[i].bin != bin) continue;
+            const rh_box b = boxes[i];
+            const int n_rows = b.rot ? RH_MB * b.wmb + 2 * halo : RH_MB * b.hmb + 2 * halo;
+            if ((int)b.by < yb && (int)b.by + n_rows > ya) {
+                const uint32_t k = atomicAdd(&s_cnt, 1u);
+                if (k < GATHER_LIST) s_list[k] = i;
+            }
+        }
+        for (int y0 = ya; y0 < yb; y0 += RB) {
+            const int rows = min(RB, yb - y0);
+            const int n_vec = rows * S * 3 / 16;                           // S is a multiple of 4 and so is rows
+            for (int i = tid; i < n_vec; i += 256) ((uint4*)img)[i] = make_uint4(0, 0, 0, 0);
+            __syncthreads();                                               // image cleared, list complete
+            const uint32_t cnt = s_cnt;                                    // uniform over the workgroup
+            if (cnt <= GATHER_LIST) {
+                for (uint32_t k = 0; k < cnt; ++k) gather_box(boxes[s_list[k]], frames, H, W, halo, S, y0, rows, img);
+            } else {
+                // more boxes reach into these rows than the list holds (tiny boxes in very wide bins):
+                // go through all boxes one after the other
+                for (uint32_t i = 0; i < n_boxes; ++i) {
+                    const rh_box b = boxes[i];
+                    if (b.bin == bin) gather_box(b, frames, H, W, halo, S, y0, rows, img);
                 }
             }
-            continue;
-        }
-        // Upright box: the band's rows go out as aligned 4-byte stores (plus up to 3 single bytes at
-        // either end of a row).  Source and destination are misaligned against each other by an
-        // arbitrary amount, so a destination word is funnelled out of the two aligned source words
-        // that hold its bytes; each of those contains at least one byte of the row, hence lies in
-        // mapped memory.  Words that straddle the frame's left or right edge are put together byte
-        // by byte (bytes outside the frame are zero).  The words of the whole band are dealt to the
-        // 256 threads, and a thread requests all of its words before it stores the first: the
-        // kernel lives on the number of loads in flight.
-        const int j0 = (u % bands) * (4 * GATHER_RPW), nrow = min(4 * GATHER_RPW, bh - j0);
-        if (nrow <= 0) continue;
-        const int head = (int)((4u - (unsigned)((uintptr_t)dst & 3u)) & 3u);     // the same for every row: the row pitch is a multiple of 4
-        const int nd = (row_bytes - head) >> 2, tail0 = head + 4 * nd, nends = head + (row_bytes - tail0);
-        const int tid = threadIdx.x;
-        if (tid < nrow * nends) {                                                 // the few bytes at the rows' ends
-            const int r = tid / nends, e = tid - r * nends, c = e < head ? e : tail0 + (e - head);
-            const int sy = sy0 + j0 + r;
-            const bool ok = sy >= 0 && sy < H && c >= x_lo && c < x_hi;
-            dst[(size_t)(j0 + r) * S * 3 + c] = ok ? src[((long)sy * W + sx0) * 3 + c] : (uint8_t)0;
-        }
-        constexpr int WPT = 3;                                                    // words per thread and pass
-        const int total = nrow * nd;
-        for (int t0 = 0; t0 < total; t0 += WPT * 256) {
-            uint32_t lo[WPT], hi[WPT]; int off[WPT]; unsigned sh[WPT]; bool funnel[WPT];
-#pragma unroll
-            for (int k = 0; k < WPT; ++k) {
-                const int t = t0 + k * 256 + tid;
-                funnel[k] = false; lo[k] = 0; hi[k] = 0; sh[k] = 0; off[k] = 0;
-                if (t < total) {
-                    const int r = t / nd, i = t - r * nd, c = head + 4 * i, sy = sy0 + j0 + r;
-                    off[k] = (j0 + r) * S * 3 + c;
-                    const bool row_in = sy >= 0 && sy < H;
-                    const uint8_t* sp = src + ((long)sy * W + sx0) * 3 + c;
-                    if (row_in && c >= x_lo && c + 4 <= x_hi) {
-                        const uintptr_t sa = (uintptr_t)sp;
-                        const uint32_t* p = (const uint32_t*)(sa & ~(uintptr_t)3);
-                        sh[k] = (unsigned)(sa & 3);
-                        lo[k] = p[0];
-                        if (sh[k]) hi[k] = p[1];
-                        funnel[k] = true;
-                    } else {                                  // outside the frame, or across its edge: rare, stored at once
-                        uint32_t w = 0;
-                        if (row_in) {
-#pragma unroll
-                            for (int q = 0; q < 4; ++q)
-                                if (c + q >= x_lo && c + q < x_hi) w |= (uint32_t)sp[q] << (8 * q);
-                        }
-                        *(uint32_t*)(dst + off[k]) = w;
-                    }
-                }
-            }
-#pragma unroll
-            for (int k = 0; k < WPT; ++k)
-                if (funnel[k]) *(uint32_t*)(dst + off[k]) = sh[k] ? __builtin_amdgcn_alignbyte(hi[k], lo[k], sh[k]) : lo[k];
+            __syncthreads();
+            uint4* dst = (uint4*)(bins + ((size_t)bin * S + y0) * S * 3);
+            for (int i = tid; i < n_vec; i += 256) dst[i] = ((const uint4*)img)[i];
+            __syncthreads();
         }
     }
 }
@@ -163,12 +179,21 @@ rh_status rh_launch_gather(rh_ctx* ctx, const uint8_t* frames, int F, const rh_b
 {
     (void)F;
     const int S = ctx->cfg.bin_size;
-    const size_t bin_vec = (size_t)S * S * 3 / 16;
-    rh_prof_scope ps(ctx, RH_PROF_GATHER, 2);
-    hipLaunchKernelGGL(k_bins_zero, dim3(1024), dim3(256), 0, ctx->stream, (uint4*)bins, counts, bin_vec);
-    const int bands = (RH_MB * ctx->T + 2 * ctx->cfg.halo + 4 * GATHER_RPW - 1) / (4 * GATHER_RPW);
-    hipLaunchKernelGGL(k_gather, dim3(4096), dim3(256), 0, ctx->stream, frames, boxes, counts, ctx->cfg.frame_h,
-                       ctx->cfg.frame_w, ctx->cfg.halo, S, bands, bins);
+    if ((uintptr_t)bins & 15) RH_FAIL(ctx, RH_E_INVALID, "rh_pack: bins must be 16-byte aligned");
+    // rows per band: a multiple of 4 (whole 16-byte vectors), about 6 KB of LDS image, at most 48 KB
+    int RB = (6 * 1024 / (S * 3)) & ~3;
+    RB = RB < 4 ? 4 : (RB > 32 ? 32 : RB);
+    const size_t lds = (size_t)RB * S * 3;
+    static bool attr_done[RH_MAX_DEVICES] = {};
+    if (!attr_done[ctx->device]) {
+        RH_HIP(ctx, hipFuncSetAttribute((const void*)k_gather, hipFuncAttributeMaxDynamicSharedMemorySize, 48 * 1024));
+        attr_done[ctx->device] = true;
+    }
+    const long units = (long)ctx->cfg.max_bins * ((S + RB - 1) / RB);
+    const int grid = (int)(units < 4096 ? (units > 0 ? units : 1) : 4096);
+    rh_prof_scope ps(ctx, RH_PROF_GATHER, 1);
+    hipLaunchKernelGGL(k_gather, dim3(grid), dim3(256), lds, ctx->stream, frames, boxes, counts, ctx->cfg.frame_h,
+                       ctx->cfg.frame_w, ctx->cfg.halo, S, RB, bins);
     RH_HIP(ctx, hipGetLastError());
     return RH_OK;
 }

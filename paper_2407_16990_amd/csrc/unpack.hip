@@ -3,22 +3,6 @@
 // macroblock the pixel is clamp(base/255 + net) quantised, otherwise the base itself.
 #include "rh_internal.h"
 
-__global__ __launch_bounds__(256) void k_fill_i32(int32_t* __restrict__ p, int32_t v, size_t n)
-{
-    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) p[i] = v;
-}
-
-__global__ __launch_bounds__(256) void k_slot_scatter(const rh_mbplace* __restrict__ places,
-                                                      const uint32_t* __restrict__ n_places, uint32_t cap,
-                                                      int32_t* __restrict__ slot_of_mb)
-{
-    const uint32_t n = min(*n_places, cap);
-    for (uint32_t i = blockIdx.x * 256u + threadIdx.x; i < n; i += gridDim.x * 256u) {
-        const uint32_t g = places[i].mb_id;
-        if (g < cap) slot_of_mb[g] = (int32_t)i;
-    }
-}
-
 __global__ __launch_bounds__(256) void k_identity_places(rh_mbplace* __restrict__ places, uint32_t* __restrict__ n_places,
                                                          int mbw, int per, uint32_t total)
 {
@@ -31,76 +15,133 @@ __global__ __launch_bounds__(256) void k_identity_places(rh_mbplace* __restrict_
     places[g] = p;
 }
 
-// Bilinear base + paste for integer scale S.  A workgroup writes a strip of NMBX macroblocks
-// (one macroblock row tall): the 64 lanes of a wave lie side by side along x, 4 output pixels
-// (12 bytes) each, so a wave instruction writes up to 768 contiguous bytes; the 4 waves split
-// the 16 input rows.  The input tile (18 rows, clamped at the frame edge) sits in LDS.
+// Bilinear base + paste for integer scale S, one launch.  A workgroup writes a strip of NMBX
+// macroblocks (one macroblock row tall): the 64 lanes of a wave lie side by side along x, 4 output
+// pixels (12 bytes) each, so a wave instruction writes up to 768 contiguous bytes; the 4 waves
+// split the 16 input rows.
+// Input tile (18 rows, clamped at the frame edge): fetched as aligned 4-byte words, every thread
+// issuing all of its loads before it waits for one; a row's words land in LDS as they are and the
+// row's byte shift (frame rows start at arbitrary byte addresses) is applied when pixels are read.
+// Placement lookup: `places` is ascending in mb_id, so the rows of the strip's macroblocks are
+// found by a 64-ary search in which the lanes of a wave probe 64 rows at a time (two or three
+// dependent loads for any batch size); no per-call index table is built.
 // Exact integer interpolation: weights are multiples of 1/(2S) in each direction,
-// out = (sum + D*D/2) / (D*D) with D = 2S.  For a placed macroblock the pixel becomes
-// floor(255 * clamp(base/255 + net, 0, 1) + 0.5) in fp32 (base/255 from a 256-entry table of
-// correctly rounded quotients).
+// out = (sum + D*D/2) / (D*D) with D = 2S; all intermediate values fit 16 bits (255 * D * D +
+// D*D/2 <= 16352), so the arithmetic runs on packed pairs.  For a placed macroblock the pixel
+// becomes floor(255 * clamp(base/255 + net, 0, 1) + 0.5) in fp32 (base/255 from a 256-entry table
+// of correctly rounded quotients).
 // EDGE: frames with cut macroblocks at the right / bottom edge (sides not multiples of 16) or a row
 // pitch that is not a multiple of 4 bytes; those blocks go pixel by pixel.  A place is honoured
 // when the in-frame part of its block lies inside the enhanced image (for whole macroblocks:
 // px + 16 <= iw and py + 16 <= ih), otherwise the macroblock stays bilinear.
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+
 template <int S, bool EDGE>
 __global__ __launch_bounds__(256) void k_unpack(const uint8_t* __restrict__ lr, int H, int W, int mbw,
                                                 const float* __restrict__ enh, int n_img, int ih, int iw,
                                                 const rh_mbplace* __restrict__ places,
-                                                const int32_t* __restrict__ slot_of_mb,
+                                                const uint32_t* __restrict__ n_places, uint32_t cap,
                                                 uint8_t* __restrict__ hr, float* __restrict__ sel)
 {
     constexpr int B = RH_MB * S, D = 2 * S, GPM = B / 4, NMBX = 64 / GPM, LANES = NMBX * GPM;
-    constexpr int TWID = RH_MB * NMBX + 2;
-    __shared__ uint8_t tile[18][TWID][3];
+    constexpr int TWID = RH_MB * NMBX + 2;                   // tile width in pixels
+    constexpr int TPD = (TWID * 3 + 3 + 3) / 4 + 1;          // 4-byte words per tile row, any byte shift
+    constexpr int NLD = (18 * TPD + 255) / 256;              // words per thread
+    __shared__ uint32_t tile[18][TPD];
     __shared__ float q255[256];
     const int strip = blockIdx.x, my = blockIdx.y, f = blockIdx.z, tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6, mbh = gridDim.y;
-    const uint8_t* src = lr + (size_t)f * H * W * 3;
-    const int lx0 = RH_MB * NMBX * strip - 1;
-    for (int i = tid; i < 18 * TWID * 3; i += 256) {
-        const int c = i % 3, px = (i / 3) % TWID, py = i / (3 * TWID);
-        const int y = min(max(RH_MB * my - 1 + py, 0), H - 1), x = min(max(lx0 + px, 0), W - 1);
-        tile[py][px][c] = src[((size_t)y * W + x) * 3 + c];
+    const int lx0 = RH_MB * NMBX * strip - 1;                // frame column of tile pixel 0 (may be -1)
+    const int xs = max(lx0, 0), xe = min(lx0 + TWID, W);     // columns [xs, xe) are fetched
+    // ---- issue the tile's loads ----
+    uint32_t tw[NLD];
+#pragma unroll
+    for (int j = 0; j < NLD; ++j) {
+        const int idx = j * 256 + tid, row = idx / TPD, d = idx - row * TPD;
+        tw[j] = 0;
+        if (row < 18) {
+            const int y = min(max(RH_MB * my - 1 + row, 0), H - 1);
+            const uintptr_t beg = (uintptr_t)lr + (((size_t)f * H + y) * W + xs) * 3, end = beg + (size_t)(xe - xs) * 3;
+            const uintptr_t wa = (beg & ~(uintptr_t)3) + 4u * (uintptr_t)d;      // holds at least one byte of the row
+            if (wa < end) tw[j] = *(const uint32_t*)wa;
+        }
+    }
+    // ---- placement rows of the strip's macroblocks: 64-ary lower bound of the first one ----
+    const uint32_t g0 = ((uint32_t)f * mbh + my) * mbw + strip * NMBX;
+    const uint32_t n = min(*n_places, cap);
+    uint32_t lo = 0, hi = n;                                 // rows < lo have mb_id < g0, rows >= hi have mb_id >= g0
+    while (hi - lo > 64u - NMBX) {                           // uniform over the wave
+        const uint32_t step = (hi - lo + 63u) / 64u, p = lo + (uint32_t)lane * step;
+        const bool below = p < hi && places[p].mb_id < g0;
+        const uint32_t cnt = (uint32_t)__popcll(__ballot(below));           // lanes 0 .. cnt-1 (the rows are ascending)
+        const uint32_t nhi = lo + cnt * step;
+        if (cnt < 64u && nhi < hi) hi = nhi;
+        if (cnt) lo = lo + (cnt - 1u) * step + 1u;
+    }
+    // the lower bound lies in [lo, hi], hi - lo <= 64 - NMBX: rows lo .. lo+63 hold every macroblock of the strip
+    uint4 row4 = make_uint4(0xFFFFFFFFu, 0, 0, 0);
+    if (lo + (uint32_t)lane < n) row4 = *(const uint4*)(places + lo + lane);
+    const int mbi = lane / GPM, mx = strip * NMBX + mbi;
+    int slot = -1;
+    uint32_t pl_bin_px = 0, pl_py_rot = 0;
+#pragma unroll
+    for (int j = 0; j < NMBX; ++j) {
+        const unsigned long long m = __ballot(row4.x == g0 + (uint32_t)j);
+        const int src = m ? __ffsll((long long)m) - 1 : 0;
+        const uint32_t a2 = (uint32_t)__shfl((int)row4.z, src), a3 = (uint32_t)__shfl((int)row4.w, src);
+        if (m && j == mbi) { slot = (int)lo + src; pl_bin_px = a2; pl_py_rot = a3; }
+    }
+    // ---- tile -> LDS ----
+#pragma unroll
+    for (int j = 0; j < NLD; ++j) {
+        const int idx = j * 256 + tid;
+        if (idx < 18 * TPD) (&tile[0][0])[idx] = tw[j];
     }
     q255[tid] = __fdiv_rn((float)tid, 255.0f);
     __syncthreads();
-    const int mbi = lane / GPM, mx = strip * NMBX + mbi;
     if (lane >= LANES || mx >= mbw) return;
     const int gx = (lane - mbi * GPM) * 4;                // first of this lane's 4 pixels inside the macroblock
-    const uint32_t g = ((uint32_t)f * mbh + my) * mbw + mx;
-    const int slot = slot_of_mb[g];
     const float* net = nullptr;
     bool turned = false;
     const int HW = W * S;
     const int fh = EDGE ? min(B, H * S - my * B) : B, fw = EDGE ? min(B, HW - mx * B) : B;   // in-frame part of the block
     if (slot >= 0) {
-        const rh_mbplace p = places[slot];
-        turned = p.rot != 0;
+        const int p_bin = (int)(pl_bin_px & 0xFFFFu), p_px = (int)(pl_bin_px >> 16), p_py = (int)(pl_py_rot & 0xFFFFu);
+        turned = (pl_py_rot >> 16) != 0;
         const int need_w = turned ? fh : fw, need_h = turned ? fw : fh;     // extent of that part inside the bin image
-        if (p.bin != RH_NO_BIN && p.bin < n_img && p.px * S + need_w <= iw * S && p.py * S + need_h <= ih * S) {
+        if (p_bin != (int)RH_NO_BIN && p_bin < n_img && p_px * S + need_w <= iw * S && p_py * S + need_h <= ih * S) {
             // upright: this lane's first pixel of row 0; turned: the block's first pixel (rows and
             // columns are exchanged when reading)
-            net = enh + (((size_t)p.bin * (ih * S) + (size_t)p.py * S) * (iw * S) + (size_t)p.px * S + (turned ? 0 : gx)) * 3;
+            net = enh + (((size_t)p_bin * (ih * S) + (size_t)p_py * S) * (iw * S) + (size_t)p_px * S + (turned ? 0 : gx)) * 3;
         }
     }
-    // horizontal taps of the 4 pixels: tile column and weight of the right neighbour
-    int tx[4], wx1[4];
+    // horizontal taps of the 4 pixels: byte offset of the left neighbour inside a tile row (before
+    // the row's shift), of the right one, and the right one's weight; columns clamp at the frame edge
+    int o0[4], o1[4], wx1[4];
+    const int row_sh0 = (int)(((uintptr_t)lr + ((size_t)f * H * W + xs) * 3) & 3u);     // shift of a row with y*W*3 = 0 (mod 4)
+    const int pitch_sh = (W * 3) & 3;
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
         const int nx = 2 * (gx + p) + 1 - S + D;          // shifted by one input pixel, always >= 0
-        tx[p] = nx / D + RH_MB * mbi; wx1[p] = nx % D;
+        const int c0 = lx0 + nx / D + RH_MB * mbi;        // frame column of the left neighbour (-1 .. W-1)
+        o0[p] = (min(max(c0, 0), W - 1) - xs) * 3; o1[p] = (min(c0 + 1, W - 1) - xs) * 3; wx1[p] = nx % D;
     }
-    // horizontal sums of one tile row for the 4 pixels x 3 channels
-    auto hsum = [&](int row, int (&h)[12]) __attribute__((always_inline)) {
+    // horizontal sums of one tile row for the 4 pixels x 3 channels, as 6 packed pairs (k, k+6)
+    auto hsum = [&](int row, u16x2 (&h)[6]) __attribute__((always_inline)) {
+        const int y = min(max(RH_MB * my - 1 + row, 0), H - 1);
+        const uint8_t* t = (const uint8_t*)&tile[row][0] + ((row_sh0 + y * pitch_sh) & 3);
+        unsigned short v[12];
 #pragma unroll
         for (int p = 0; p < 4; ++p)
 #pragma unroll
-            for (int c = 0; c < 3; ++c) h[p * 3 + c] = (D - wx1[p]) * tile[row][tx[p]][c] + wx1[p] * tile[row][tx[p] + 1][c];
+            for (int c = 0; c < 3; ++c)
+                v[p * 3 + c] = (unsigned short)((D - wx1[p]) * t[o0[p] + c] + wx1[p] * t[o1[p] + c]);
+#pragma unroll
+        for (int k = 0; k < 6; ++k) { h[k].x = v[k]; h[k].y = v[k + 6]; }
     };
     const bool edge = EDGE && (fh < B || fw < B || ((HW * 3) & 3));
     uint8_t* dst = hr + (((size_t)f * H * S + (size_t)my * B) * HW + (size_t)mx * B + gx) * 3;
-    int h0[12], h1[12], h2[12];                            // input rows r-1, r, r+1 (tile rows r, r+1, r+2)
+    u16x2 h0[6], h1[6], h2[6];                             // input rows r-1, r, r+1 (tile rows r, r+1, r+2)
     const int r0 = wave * 4;
     hsum(r0, h0); hsum(r0 + 1, h1);
 #pragma unroll
@@ -113,10 +154,17 @@ __global__ __launch_bounds__(256) void k_unpack(const uint8_t* __restrict__ lr, 
             const int wy1 = ny < 0 ? ny + D : ny;
             const int yy = r * S + j;
             uint32_t bytes[12];
+            const u16x2 wa = {(unsigned short)(D - wy1), (unsigned short)(D - wy1)}, wb = {(unsigned short)wy1, (unsigned short)wy1};
+            const u16x2 rnd = {(unsigned short)(D * D / 2), (unsigned short)(D * D / 2)};
 #pragma unroll
-            for (int k = 0; k < 12; ++k) {
-                const int acc = ny < 0 ? (D - wy1) * h0[k] + wy1 * h1[k] : (D - wy1) * h1[k] + wy1 * h2[k];
-                bytes[k] = (uint32_t)(acc + D * D / 2) / (uint32_t)(D * D);
+            for (int k = 0; k < 6; ++k) {
+                const u16x2 acc = (ny < 0 ? h0[k] * wa + h1[k] * wb : h1[k] * wa + h2[k] * wb) + rnd;
+                if constexpr ((D * D & (D * D - 1)) == 0) {
+                    const u16x2 q = acc >> (unsigned short)__builtin_ctz(D * D);
+                    bytes[k] = q.x; bytes[k + 6] = q.y;
+                } else {
+                    bytes[k] = (uint32_t)acc.x / (uint32_t)(D * D); bytes[k + 6] = (uint32_t)acc.y / (uint32_t)(D * D);
+                }
             }
             if (EDGE && edge) {
                 // Macroblock cut by the frame edge, or a row pitch that is not a multiple of 4 bytes:
@@ -176,13 +224,19 @@ __global__ __launch_bounds__(256) void k_unpack(const uint8_t* __restrict__ lr, 
                 }
             }
             uint32_t* o = (uint32_t*)(dst + (size_t)yy * HW * 3);
-            o[0] = bytes[0] | (bytes[1] << 8) | (bytes[2] << 16) | (bytes[3] << 24);
-            o[1] = bytes[4] | (bytes[5] << 8) | (bytes[6] << 16) | (bytes[7] << 24);
-            o[2] = bytes[8] | (bytes[9] << 8) | (bytes[10] << 16) | (bytes[11] << 24);
+            const uint32_t w0 = bytes[0] | (bytes[1] << 8) | (bytes[2] << 16) | (bytes[3] << 24);
+            const uint32_t w1 = bytes[4] | (bytes[5] << 8) | (bytes[6] << 16) | (bytes[7] << 24);
+            const uint32_t w2 = bytes[8] | (bytes[9] << 8) | (bytes[10] << 16) | (bytes[11] << 24);
+            o[0] = w0; o[1] = w1; o[2] = w2;
         }
 #pragma unroll
-        for (int k = 0; k < 12; ++k) { h0[k] = h1[k]; h1[k] = h2[k]; }
+        for (int k = 0; k < 6; ++k) { h0[k] = h1[k]; h1[k] = h2[k]; }
     }
+}
+
+__global__ __launch_bounds__(256) void k_fill_i32(int32_t* __restrict__ p, int32_t v, size_t n)
+{
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) p[i] = v;
 }
 
 void rh_fill_i32(rh_ctx* ctx, int32_t* p, int32_t v, size_t n)
@@ -196,10 +250,7 @@ rh_status rh_launch_unpack(rh_ctx* ctx, const float* enh, int n_img, int ih, int
                            const uint8_t* lr, int F, uint8_t* hr, float* sel)
 {
     const uint32_t total = (uint32_t)ctx->per * F;
-    const int nb = (int)min((total + 255u) / 256u, 1024u);
-    rh_prof_scope ps(ctx, RH_PROF_UNPACK, 3);
-    rh_fill_i32(ctx, ctx->slot_of_mb, -1, (size_t)total);
-    hipLaunchKernelGGL(k_slot_scatter, dim3(nb), dim3(256), 0, ctx->stream, places, n_places, total, ctx->slot_of_mb);
+    rh_prof_scope ps(ctx, RH_PROF_UNPACK, 1);
     const int S = ctx->cfg.net.scale;
     const bool cut = ctx->cfg.frame_w % RH_MB || ctx->cfg.frame_h % RH_MB || ((ctx->cfg.frame_w * S * 3) & 3);
 #define LAUNCH_UNPACK(SC)                                                                                       \
@@ -207,7 +258,7 @@ rh_status rh_launch_unpack(rh_ctx* ctx, const float* enh, int n_img, int ih, int
 #define LAUNCH_UNPACK_E(SC, E)                                                                                  \
     hipLaunchKernelGGL((k_unpack<SC, E>), dim3((ctx->mbw + (64 / (4 * SC)) - 1) / (64 / (4 * SC)), ctx->mbh, F), dim3(256), 0, \
                        ctx->stream, lr, ctx->cfg.frame_h, ctx->cfg.frame_w, ctx->mbw, enh, n_img, ih, iw, places,  \
-                       ctx->slot_of_mb, hr, sel)
+                       n_places, total, hr, sel)
     if (S == 1) LAUNCH_UNPACK(1); else if (S == 2) LAUNCH_UNPACK(2); else if (S == 3) LAUNCH_UNPACK(3); else LAUNCH_UNPACK(4);
 #undef LAUNCH_UNPACK
 #undef LAUNCH_UNPACK_E
