@@ -86,6 +86,13 @@ typedef struct {
                                    not equivariant under that, so the enhanced pixels of a
                                    turned box differ from the upright ones (the paper accepts
                                    this); 0 keeps every box upright                         */
+    int32_t per_layer_tail;     /* RH_BF16, RH_NET_EDSR only.  After the body these nets are linear
+                                   (upsampling convs, pixel shuffles, last conv, no activation), so
+                                   rh_enhance runs that part as ONE composed convolution (5 x 5 taps
+                                   on the body's output, 3*s*s outputs, weights composed at rh_create):
+                                   the same function without the high-resolution intermediate
+                                   tensors and their bf16 rounding.  1: run these layers one by one
+                                   instead (what rh_enhance_exact always does)                */
 } rh_config;
 
 /* One selection segment: frames [frame_begin, frame_end).  RH_TOPK uses k, RH_THRESHOLD thr. */
@@ -147,7 +154,7 @@ rh_status rh_select_regions(rh_ctx* ctx, const float* importance, int32_t F,
  * strip plus the rest, rectangles with a side < 16+2*halo are dropped, survivors replace the
  * free rectangle in the list, smaller area first.  Boxes stay upright (rot = 0) unless
  * rh_config.rotate is set.
- * Stitch: bins u8 [max_bins][S][S][3]; inside a placed box the frame's pixels (zero where the
+ * Stitch: bins u8 [max_bins][S][S][3], 16-byte aligned; inside a placed box the frame's pixels (zero where the
  * halo leaves the frame), zero elsewhere; only bins [0, n_bins) are written.
  * Inputs (dev): frames u8 [F][H][W][3], importance, and mask/list/n_sel from rh_select_regions.
  * Outputs (dev): bins; boxes (capacity F*MBH*MBW) in placement order; places (same capacity)
@@ -163,7 +170,7 @@ rh_status rh_pack(rh_ctx* ctx, const uint8_t* frames, int32_t F, const float* im
  * SR forward (Sec. 3.3.3) on N images u8 [N][H][W][3] -> raw network output f32
  * [N][s*H][s*W][3].  Used for the packed bins and, with whole frames, for the frame-based
  * comparison run.  n_valid (dev u32[1], may be NULL): when given, only images [0, *n_valid)
- * are computed (pass &counts[1] to avoid a host round trip).  H, W >= 3.
+ * are computed (pass &counts[1] to avoid a host round trip).  H, W >= 3; out 16-byte aligned.
  * The context's activation workspace only grows: a call that needs more than every earlier call
  * synchronises the stream and reallocates it (sized by N, not by *n_valid); later calls of the
  * same or a smaller size allocate nothing.  RH_BF16: one image's activations at the network's

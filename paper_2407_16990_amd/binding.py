@@ -37,7 +37,7 @@ class Config(C.Structure):
     _fields_ = [("frame_w", C.c_int32), ("frame_h", C.c_int32), ("max_frames", C.c_int32), ("halo", C.c_int32),
                 ("bin_size", C.c_int32), ("max_bins", C.c_int32), ("connectivity", C.c_int32),
                 ("max_box_mbs", C.c_int32), ("precision", C.c_int32), ("net", NetDesc),
-                ("sort_policy", C.c_int32), ("rotate", C.c_int32)]
+                ("sort_policy", C.c_int32), ("rotate", C.c_int32), ("per_layer_tail", C.c_int32)]
 
 
 class Segment(C.Structure):
@@ -145,7 +145,7 @@ class RH:
 
     def __init__(self, *, frame_w, frame_h, max_frames, halo, bin_size, max_bins, net, weights: np.ndarray,
                  precision="bf16", connectivity=8, max_box_mbs=0, sort_policy="density", rotate=False,
-                 device="cuda:0", stream=None):
+                 per_layer_tail=False, device="cuda:0", stream=None):
         self.lib = load_library()
         if not torch.cuda.is_available():
             raise RuntimeError("paper_2407_16990_amd needs a GPU: there is no CPU fallback")
@@ -154,7 +154,7 @@ class RH:
         self.cfg = Config(frame_w, frame_h, max_frames, halo, bin_size, max_bins, connectivity, max_box_mbs,
                           {"fp32": RH_FP32, "bf16": RH_BF16}[precision],
                           NetDesc(TOPOLOGY[net.topology], net.channels, net.n_blocks, net.scale),
-                          {"density": 0, "area": 1}[sort_policy], int(bool(rotate)))
+                          {"density": 0, "area": 1}[sort_policy], int(bool(rotate)), int(bool(per_layer_tail)))
         self.scale = net.scale
         self.mbw, self.mbh = (frame_w + 15) // 16, (frame_h + 15) // 16
         w = np.ascontiguousarray(weights, dtype=np.float32)

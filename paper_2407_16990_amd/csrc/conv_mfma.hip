@@ -476,13 +476,16 @@ rh_status rh_launch_enhance_bf16(rh_ctx* ctx, const uint8_t* in, int N, int H, i
     const int C = d.channels, s = d.scale;
     const size_t lr = (size_t)N * H * W * C;
     size_t need = 3 * lr, up1 = 0, up2 = 0;
-    if (d.topology == RH_NET_EDSR) {
+    // the composed upsampler + last conv replaces the per-layer run, except in exact-border mode
+    // (which clears the out-of-frame activations of every layer it would skip)
+    const bool fold = d.topology == RH_NET_EDSR && ctx->fold_chunks > 0 && !ctx->bz_boxes;
+    if (d.topology == RH_NET_EDSR && !fold) {
         const int r = (s == 4) ? 2 : s;
         up1 = lr * r * r; need += up1;
         if (s == 4) { up2 = up1 * 4; need += up2; }
     }
     {   // the conv kernels address one image with 32-bit byte offsets (buffer instructions)
-        const int rmax = d.topology == RH_NET_EDSR ? s : 1;
+        const int rmax = (d.topology == RH_NET_EDSR && !fold) ? s : 1;
         const unsigned long long img_bytes = (unsigned long long)H * rmax * W * rmax * C * 2ull;
         if (img_bytes >= (1ull << 31))
             RH_FAIL(ctx, RH_E_SHAPE, "rh_enhance: %dx%d images need %llu bytes of bf16 activations each at x%d; the limit is 2 GiB",
@@ -525,11 +528,18 @@ rh_status rh_launch_enhance_bf16(rh_ctx* ctx, const uint8_t* in, int N, int H, i
             LAST_CONV(L[li++], x, out, nullptr, N, H, W, 0, true, s, n_valid);
         } else {
             CONV(L[li++], x, t, h, N, H, W, 0, false, 1, n_valid); ZERO(t, 1);       // body end + long skip
-            const int r = (s == 4) ? 2 : s;
-            CONV(L[li++], t, u1, nullptr, N, H, W, 0, false, 1, n_valid); ZERO(u1, r);
-            const __bf16* lastin = u1; int hh = H * r, ww = W * r;
-            if (s == 4) { CONV(L[li++], u1, u2, nullptr, N, hh, ww, 0, false, 1, n_valid); ZERO(u2, 2 * r); lastin = u2; hh *= 2; ww *= 2; }
-            LAST_CONV(L[li++], lastin, out, nullptr, N, hh, ww, 0, true, 1, n_valid);
+            if (fold) {
+                rh_prof_end(ctx, n_conv);
+                rh_prof_scope ps_(ctx, RH_PROF_CONV_LAST, 2);
+                st = rh_launch_fold(ctx, t, out, N, H, W, n_valid, ctx->conv_parity ^= 1);
+                if (st != RH_OK) return st;
+            } else {
+                const int r = (s == 4) ? 2 : s;
+                CONV(L[li++], t, u1, nullptr, N, H, W, 0, false, 1, n_valid); ZERO(u1, r);
+                const __bf16* lastin = u1; int hh = H * r, ww = W * r;
+                if (s == 4) { CONV(L[li++], u1, u2, nullptr, N, hh, ww, 0, false, 1, n_valid); ZERO(u2, 2 * r); lastin = u2; hh *= 2; ww *= 2; }
+                LAST_CONV(L[li++], lastin, out, nullptr, N, hh, ww, 0, true, 1, n_valid);
+            }
         }
     }
 #undef CONV

@@ -60,3 +60,5 @@ hipError_t rh_launch_conv_tail3(hipStream_t stream, int device, const conv_args&
 // first conv 3 -> C on the matrix cores (conv_head.hip)
 hipError_t rh_launch_head_mfma(hipStream_t stream, int C, const uint8_t* in, const uint4* wp, const float* bias, __bf16* out,
                                int N, int H, int W, int relu, const uint32_t* n_valid);
+// upsampler + last conv of an EDSR-shaped net as one composed 5 x 5 conv (conv_fold.hip): t -> raw network output
+rh_status rh_launch_fold(rh_ctx* ctx, const __bf16* t, float* out, int N, int H, int W, const uint32_t* n_valid, int rev);

@@ -55,7 +55,7 @@ extern "C" void rh_destroy(rh_ctx* ctx)
     (void)hipStreamSynchronize(ctx->stream);
     for (rh_prof_rec& r : ctx->prof_pending) { if (r.t0) (void)hipEventDestroy(r.t0); if (r.t1) (void)hipEventDestroy(r.t1); }
     for (hipEvent_t e : ctx->prof_pool) (void)hipEventDestroy(e);
-    void* ptrs[] = {ctx->w_f32, ctx->wpack, ctx->bpack, ctx->frame_seg, ctx->seg_par, ctx->seg_T, ctx->seg_budget,
+    void* ptrs[] = {ctx->w_f32, ctx->wpack, ctx->bpack, ctx->fold_w, ctx->fold_b, ctx->frame_seg, ctx->seg_par, ctx->seg_T, ctx->seg_budget,
                     ctx->frame_nsel, ctx->frame_ties, ctx->owner_id, ctx->rank_of_id, ctx->raw, ctx->sorted,
                     ctx->pcount, ctx->slot_of_mb, ctx->tr_off, ctx->tr_A, ctx->tr_T, ctx->act};
     for (void* p : ptrs) if (p) (void)hipFree(p);
@@ -75,6 +75,7 @@ extern "C" rh_status rh_create(const rh_config* cfg, const float* weights, size_
     if (cfg->connectivity != 4 && cfg->connectivity != 8) return RH_E_INVALID;
     if (cfg->sort_policy != RH_SORT_DENSITY && cfg->sort_policy != RH_SORT_AREA) return RH_E_INVALID;
     if (cfg->rotate != 0 && cfg->rotate != 1) return RH_E_INVALID;
+    if (cfg->per_layer_tail != 0 && cfg->per_layer_tail != 1) return RH_E_INVALID;
     if (cfg->precision != RH_FP32 && cfg->precision != RH_BF16) return RH_E_INVALID;
     const int Tmax = (cfg->bin_size - 2 * cfg->halo) / RH_MB;
     if (cfg->max_box_mbs < 0 || cfg->max_box_mbs > Tmax || Tmax > 255) return RH_E_SHAPE;
@@ -115,6 +116,7 @@ extern "C" rh_status rh_create(const rh_config* cfg, const float* weights, size_
     }
     if (st == RH_OK) st = rh_plan_init(ctx);
     if (st == RH_OK && cfg->precision == RH_BF16) st = rh_pack_weights_bf16(ctx, weights);
+    if (st == RH_OK && cfg->precision == RH_BF16 && !cfg->per_layer_tail) st = rh_fold_weights(ctx, weights);
     if (st != RH_OK) { rh_destroy(ctx); return st; }
     *out = ctx;
     return RH_OK;
@@ -257,6 +259,7 @@ extern "C" rh_status rh_enhance(rh_ctx* ctx, const uint8_t* in, int32_t N, int32
     if (!ctx) return RH_E_INVALID;
     if (!in || !out) RH_FAIL(ctx, RH_E_INVALID, "rh_enhance: null argument");
     if (N < 1 || H < 3 || W < 3 || H > 16384 || W > 16384 || N > 65535) RH_FAIL(ctx, RH_E_SHAPE, "rh_enhance: bad shape N=%d H=%d W=%d", N, H, W);
+    if ((uintptr_t)out & 15) RH_FAIL(ctx, RH_E_INVALID, "rh_enhance: out must be 16-byte aligned");
     return ctx->cfg.precision == RH_BF16 ? rh_launch_enhance_bf16(ctx, in, N, H, W, out, n_valid)
                                          : rh_launch_enhance_fp32(ctx, in, N, H, W, out, n_valid);
 }
@@ -267,6 +270,7 @@ extern "C" rh_status rh_enhance_exact(rh_ctx* ctx, const uint8_t* in, int32_t N,
     if (!ctx) return RH_E_INVALID;
     if (!in || !out || !boxes || !counts) RH_FAIL(ctx, RH_E_INVALID, "rh_enhance_exact: null argument");
     if (N < 1 || N > 65535) RH_FAIL(ctx, RH_E_SHAPE, "rh_enhance_exact: bad N=%d", N);
+    if ((uintptr_t)out & 15) RH_FAIL(ctx, RH_E_INVALID, "rh_enhance_exact: out must be 16-byte aligned");
     const int S = ctx->cfg.bin_size;
     ctx->bz_boxes = boxes; ctx->bz_counts = counts;
     const rh_status st = ctx->cfg.precision == RH_BF16 ? rh_launch_enhance_bf16(ctx, in, N, S, S, out, n_valid)

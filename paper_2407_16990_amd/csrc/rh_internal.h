@@ -54,6 +54,11 @@ struct rh_ctx {
     float* w_f32;           // dev: the fp32 blob as given
     void* wpack;            // dev: bf16 weights in fragment order (RH_BF16 only)
     float* bpack;           // dev: biases matching wpack's channel order
+    // EDSR-shaped nets, bf16: the upsampler and the last conv composed into one 5 x 5 conv (conv_fold.hip)
+    void* fold_w;           // dev: bf16 weights [class 9][chunk][tap 25][k-step][lane][8]
+    float* fold_b;          // dev: [class][chunk][32]
+    int fold_chunks;        // 32-row chunks of the composed conv's 3*s*s outputs (0: no composed conv)
+    int fold_rows, fold_ipc;   // valid rows per chunk, output rows i per chunk
 
     // select scratch (dev)
     int32_t* frame_seg;     // [max_frames] segment of each frame or -1
@@ -126,6 +131,7 @@ rh_status rh_launch_temporal_select(rh_ctx*, const uint64_t* phi, const int32_t*
                                     uint32_t* n_selected);
 rh_status rh_launch_temporal_spread(rh_ctx*, float* imp, int F, const uint8_t* selected, const uint32_t* reuse_from);
 rh_status rh_pack_weights_bf16(rh_ctx*, const float* host_blob);
+rh_status rh_fold_weights(rh_ctx*, const float* host_blob);
 rh_status rh_plan_init(rh_ctx*);
 // exact-border mode: zero the out-of-frame part of every box in an activation tensor
 // [N][S*res][S*res][px_bytes]; a no-op unless an rh_enhance_exact call is in progress

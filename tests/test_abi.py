@@ -30,7 +30,7 @@ def test_library_exports_every_declared_symbol():
 def test_struct_layouts_match_header_comments():
     import paper_2407_16990_amd as pkg
     assert pkg.BOX_DTYPE.itemsize == 24 and pkg.PLACE_DTYPE.itemsize == 16
-    assert C.sizeof(pkg.Config) == 15 * 4 and C.sizeof(pkg.Segment) == 16
+    assert C.sizeof(pkg.Config) == 16 * 4 and C.sizeof(pkg.Segment) == 16
 
 
 def test_budget_host_helper():

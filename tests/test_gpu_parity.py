@@ -14,13 +14,14 @@ pytestmark = pytest.mark.gpu
 
 
 def full_path_check(cfg, n_frames=None, precision=None, segs=None, max_bins=None, sort_policy="density", rotate=False,
-                    expect_turned=False):
+                    expect_turned=False, per_layer_tail=False):
     F = cfg.n_frames if n_frames is None else n_frames
     precision = precision or cfg.precision
     frames, imp = wl.make_frames(cfg, F), wl.make_importance(cfg, F)
     segs = wl.make_segments(cfg, F) if segs is None else segs
     blob = wl.make_weights(cfg.net, cfg.weight_seed, precision)
-    rh = make_rh(cfg, blob, F, precision=precision, max_bins=max_bins, sort_policy=sort_policy, rotate=rotate)
+    rh = make_rh(cfg, blob, F, precision=precision, max_bins=max_bins, sort_policy=sort_policy, rotate=rotate,
+                 per_layer_tail=per_layer_tail)
     o_plan, po, (d_frames, d_imp, o_bins) = check_select_and_plan(rh, cfg, frames, imp, segs, sort_policy=sort_policy,
                                                                   rotate=rotate)
     if expect_turned:
@@ -178,9 +179,10 @@ def test_empty_selection_and_overflow_and_errors():
         RH(frame_w=64, frame_h=64, max_frames=1, halo=4, bin_size=64, max_bins=4, net=net, weights=blob[:-1], precision="fp32")
     rh.close()
     # bf16 path: an image whose activations would pass 2 GiB is refused before anything is launched or allocated
+    # (layer by layer the x4 net holds 64 channels at the output resolution)
     net64 = wl.Net("edsr", 64, 1, 4, 0.02)
     rh2 = RH(frame_w=64, frame_h=64, max_frames=1, halo=4, bin_size=64, max_bins=4, net=net64,
-             weights=wl.make_weights(net64, 0, "bf16"), precision="bf16")
+             weights=wl.make_weights(net64, 0, "bf16"), precision="bf16", per_layer_tail=True)
     with pytest.raises(RhError) as ei:
         rh2.enhance(torch.zeros((1, 1100, 1100, 3), dtype=torch.uint8, device="cuda"))   # 4400 x 4400 x 128 B > 2 GiB
     assert "2 GiB" in str(ei.value)
@@ -217,6 +219,15 @@ def test_small_topologies_bf16(net):
     give several 32-wide tiles with a ragged tail in both directions."""
     cfg = wl.replace(wl.config(1), net=net, n_frames=2, halo=5, frac=0.3, bin_size=80, precision="bf16")
     full_path_check(cfg)
+
+
+@pytest.mark.parametrize("net", [wl.Net("edsr", 64, 1, 2, 0.03), wl.Net("edsr", 64, 1, 3, 0.03), wl.Net("edsr", 64, 2, 4, 0.03),
+                                 wl.Net("edsr", 32, 1, 4, 0.03)])
+def test_small_topologies_bf16_layer_by_layer_tail(net):
+    """The same nets with the upsampler and the last conv run layer by layer (rh_config.per_layer_tail)
+    instead of as one composed convolution."""
+    cfg = wl.replace(wl.config(1), net=net, n_frames=2, halo=5, frac=0.3, bin_size=80, precision="bf16")
+    full_path_check(cfg, per_layer_tail=True)
 
 
 def test_cfg2_two_frames_bf16():
