@@ -407,3 +407,45 @@ def test_partial_macroblock_frames(orc):
         base = orc.bilinear(frames[f], s)
         keep = ~np.kron(r.mask[f], np.ones((B, B), dtype=np.uint8)).astype(bool)[:200, :336]
         assert np.array_equal(r.frames_hr[f][keep], base[keep])
+
+
+def test_place_that_leaves_the_enhanced_image_stays_bilinear(orc):
+    """A place is honoured only when the in-frame part of its macroblock lies inside the enhanced
+    image; otherwise the macroblock keeps the bilinear base and sel reports zeros.  Hand case: one
+    4 x 3 macroblock frame, an enhanced image of 40 x 24 low-resolution pixels, four places."""
+    rng = np.random.default_rng(5)
+    s, B = 2, 32
+    frame = rng.integers(0, 256, size=(1, 48, 64, 3), dtype=np.uint8)
+    net = rng.normal(0.0, 0.1, size=(1, 24 * s, 40 * s, 3))
+    base = orc.bilinear(frame[0], s)
+    #          mb_id box bin  px  py
+    places = [[0, 0, 0, 0, 0],        # inside: pasted
+              [1, 0, 0, 24, 8],       # px + 16 = 40 <= 40, py + 16 = 24 <= 24: just inside, pasted
+              [5, 0, 0, 25, 0],       # px + 16 = 41 > 40: leaves the image on the right
+              [6, 0, 0, 0, 9],        # py + 16 = 25 > 24: leaves it at the bottom
+              [7, 0, 0xFFFF, 0, 0]]   # not placed at all
+    hr, sel = orc.unpack(frame, s, net, np.array(places, dtype=np.int32))
+    for i, (g, _, b, px, py) in enumerate(places):
+        y, x = divmod(g, 4)
+        got = hr[0, y * B:(y + 1) * B, x * B:(x + 1) * B]
+        bb = base[y * B:(y + 1) * B, x * B:(x + 1) * B]
+        if i < 2:
+            e = np.clip(bb.astype(np.float64) / 255.0 + net[0, py * s:py * s + B, px * s:px * s + B], 0, 1)
+            assert np.abs(sel[i] - e).max() < 1e-6 and (got != bb).any()
+            assert np.abs(got.astype(np.float64) - np.floor(e * 255.0 + 0.5)).max() <= 1
+        else:
+            assert np.array_equal(got, bb) and not sel[i].any()
+    # every macroblock without a place is the base as well
+    untouched = np.ones((3, 4), dtype=bool); untouched[0, 0] = untouched[0, 1] = False
+    keep = np.kron(untouched, np.ones((B, B), dtype=bool))
+    assert np.array_equal(hr[0][keep], base[keep])
+    # a turned place swaps the roles of the two extents: 16 x 16 blocks are symmetric, a cut block is not
+    frame2 = rng.integers(0, 256, size=(1, 40, 64, 3), dtype=np.uint8)         # bottom macroblock row is 8 pixels tall
+    net2 = rng.normal(0.0, 0.1, size=(1, 24 * s, 40 * s, 3))
+    pl = np.array([[8, 0, 0, 30, 0], [9, 0, 0, 30, 0]], dtype=np.int32)        # both in the cut row (y = 2)
+    # upright needs 16 columns x 8 rows: 30 + 16 > 40 -> leaves; turned needs 8 columns x 16 rows: 30 + 8 <= 40 -> pasted
+    hr2, sel2 = orc.unpack(frame2, s, net2, pl, place_rot=np.array([0, 1], dtype=np.int32))
+    base2 = orc.bilinear(frame2[0], s)
+    assert np.array_equal(hr2[0, 64:80, 0:32], base2[64:80, 0:32]) and not sel2[0].any()
+    e = np.clip(base2[64:80, 32:64].astype(np.float64) / 255.0 + net2[0, 0:32, 60:76].transpose(1, 0, 2), 0, 1)
+    assert np.abs(sel2[1][:16] - e).max() < 1e-6 and not sel2[1][16:].any()
