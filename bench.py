@@ -6,9 +6,12 @@ over one batch of synthetic input already resident in HBM.  Workload: configurat
 benchmark list (16 frames 480x272, EDSR-baseline x4, top 20 % macroblocks, halo 10, 128x128
 bins, bf16), the one the headline metric "enhanced macroblocks/s" is quoted on.
 
-Prints ONE JSON line with the metric, the roofline of the dominant kernel (the bf16 MFMA conv,
-timed with HIP events inside the timed region), the CPU oracle timed on a bounded sample
-(cpu_baseline), and the 100 %-macroblock frame-based run on the GPU for comparison.
+Prints ONE JSON line with the metric, the roofline of the dominant kernel (the bf16 MFMA conv of
+the network body, timed with HIP events on the library's stream inside the timed region), the
+CPU oracle timed on a bounded sample (cpu_baseline), the 100 %-macroblock frame-based run, the
+memory-bound steps at batch size and on 16 batches, the other benchmark configurations
+(other_configs: 1, 2, 5 and the selected-fraction sweep of configuration 4), planner-lite's choice
+of the bin size (planner_lite) and the temporal importance reuse leg.
 """
 from __future__ import annotations
 
@@ -23,39 +26,161 @@ import numpy as np
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-MFMA_BF16_PEAK = 2.5e15   # dense bf16 MFMA, FLOP/s (MI355X published)
+MFMA_BF16_PEAK = 2.5e15    # dense bf16 MFMA, FLOP/s (MI355X published)
 FP32_VALU_PEAK = 157.3e12  # fp32 vector ALUs, FLOP/s (MI355X published)
-# HBM bytes per launch of the dominant kernel class on the default workload, from the rocprofv3
-# FETCH_SIZE / WRITE_SIZE runs summarised in profiles/conv_mfma_cfg3_hbm_counters.md (scaled by
-# the plain-copy calibration); not measured live, so only reported for that workload.
-MEASURED_TRAFFIC = {"cfg3_16x480x272_edsr64_x4_bf16": 499.0e6}
-CONV_KERNEL = {64: "k_conv_mfma_duo<SKIP,RELU,10> (bf16-output 64-channel convs: ReLU, skip-add and plain instantiations)",
+HBM_PEAK = 8.0e12          # B/s
+# HBM bytes per launch of the dominant kernel class on the default workload: NOT measured live but
+# taken from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in the named profile (scaled by
+# the plain-copy calibration stated there); only reported for that workload and kernel set.
+PROFILED_TRAFFIC = {"cfg3_16x480x272_edsr64_x4_bf16": (406.2e6, "profiles/conv_mfma_cfg3_hbm_counters.md")}
+CONV_KERNEL = {64: "k_conv_mfma_duo<SKIP,RELU,10> (64-channel bf16-output convs of the network body: ReLU and skip-add instantiations)",
                32: "k_conv_mfma<32,1,16,false,SKIP,RELU> (bf16-output 32-channel convs)"}
 
 
-def conv_flops_per_lr_pixel(net):
-    """Algorithmic FLOPs of the C-input/bf16-output convs (the profiled kernel class) per
-    packed low-resolution pixel: 18*cin*cout per output pixel at the layer's resolution."""
+def net_flops(net, composed_tail):
+    """Per packed low-resolution pixel: flop and launches of the profiled conv class (bf16 path: the
+    C-input / bf16-output convs; 18*cin*cout per output pixel at the layer's resolution), the
+    network's flop as defined layer by layer, and the flop the kernels execute (they differ when
+    the linear tail of an EDSR-shaped net runs as one composed 5x5 conv on padded MFMA rows)."""
     C, s = net.channels, net.scale
-    body = 2 * net.n_blocks + (1 if net.topology == "edsr" else 0)
-    fl = body * 18 * C * C
-    launches = body
+    body = net.n_blocks - 2 if net.topology == "plain" else 2 * net.n_blocks + (1 if net.topology == "edsr" else 0)
+    cls_fl, cls_n = body * 18 * C * C, body
+    head = 18 * 3 * C
     if net.topology == "edsr":
-        if s == 4:
-            fl += 18 * C * 4 * C + 4 * 18 * C * 4 * C
-            launches += 2
+        ups = 18 * C * 4 * C + 4 * 18 * C * 4 * C if s == 4 else 18 * C * C * s * s
+        network = head + cls_fl + ups + s * s * 18 * C * 3
+        if composed_tail:
+            executed = head + cls_fl + 2 * 25 * C * 32 * (2 if s == 4 else 1)
         else:
-            fl += 18 * C * C * s * s
-            launches += 1
-    return fl, launches
+            executed = network
+            cls_fl += ups
+            cls_n += 2 if s == 4 else 1
+    else:
+        network = executed = head + cls_fl + 18 * C * 3 * s * s
+    return cls_fl, cls_n, network, executed
 
 
-def total_flops_per_lr_pixel(net):
-    C, s = net.channels, net.scale
-    fl, _ = conv_flops_per_lr_pixel(net)
-    fl += 18 * 3 * C
-    fl += (s * s * 18 * C * 3) if net.topology == "edsr" else 18 * C * 3 * s * s
-    return fl
+class Runner:
+    """One configuration resident on the GPU: inputs, context, preallocated outputs, and a step()."""
+
+    def __init__(self, cfg, args, max_box_mbs=0, per_layer_tail=False):
+        import torch
+        import workloads as wl
+        from paper_2407_16990_amd import RH
+        self.torch, self.cfg = torch, cfg
+        F, S = cfg.n_frames, cfg.bin_size
+        self.frames, self.imp, self.segs = wl.make_frames(cfg), wl.make_importance(cfg), wl.make_segments(cfg)
+        self.blob = wl.make_weights(cfg.net, cfg.weight_seed, cfg.precision)
+        # room for the packer's worst case (isolated macroblocks: one box each)
+        worst = cfg.index == 5 or cfg.importance == "uniform" or max_box_mbs == 1 or cfg.frac > 0.3
+        self.max_bins = (512 if worst else 256) * max(1, (128 // S) ** 2)
+        self.composed = (cfg.precision == "bf16" and cfg.net.topology == "edsr" and not per_layer_tail
+                         and not args.exact_border)
+        self.rh = RH(frame_w=cfg.width, frame_h=cfg.height, max_frames=F, halo=cfg.halo, bin_size=S, max_bins=self.max_bins,
+                     net=cfg.net, weights=self.blob, precision=cfg.precision, max_box_mbs=max_box_mbs,
+                     per_layer_tail=per_layer_tail)
+        self.d_frames = torch.from_numpy(self.frames).cuda()
+        self.d_imp = torch.from_numpy(self.imp).cuda()
+        self.seg_rows = [tuple(r) for r in self.segs.tolist()]
+        self.po = None
+        self.exact = args.exact_border
+        self.sync_counts = args.sync_counts
+        self.net_out = self.hr = None
+        self.cap = 0
+
+    def alloc(self, n_bins_cap):
+        torch, cfg = self.torch, self.cfg
+        s, S = cfg.net.scale, cfg.bin_size
+        self.cap = n_bins_cap
+        self.net_out = torch.empty((n_bins_cap, S * s, S * s, 3), dtype=torch.float32, device="cuda")
+        self.hr = torch.empty((cfg.n_frames, cfg.height * s, cfg.width * s, 3), dtype=torch.uint8, device="cuda")
+
+    def plan_only(self):
+        rh = self.rh
+        mask, lst, n_sel = rh.select_regions(self.d_imp, self.seg_rows)
+        self.po = rh.pack(self.d_frames, self.d_imp, mask, lst, n_sel, out=self.po)
+        return rh.read_counts(self.po.counts)
+
+    def step(self):
+        rh = self.rh
+        mask, lst, n_sel = rh.select_regions(self.d_imp, self.seg_rows)
+        self.po = po = rh.pack(self.d_frames, self.d_imp, mask, lst, n_sel, out=self.po)
+        if self.exact:
+            rh.enhance_exact(po.bins, po.boxes, po.counts, n=self.cap, n_valid=po.counts[1:2], out=self.net_out)
+        elif self.sync_counts:
+            rh.enhance(po.bins, n=rh.read_counts(po.counts)[1], out=self.net_out)
+        else:
+            rh.enhance(po.bins, n=self.cap, n_valid=po.counts[1:2], out=self.net_out)   # device-side bin count
+        rh.unpack(self.net_out, po.places, po.counts[3:4], self.d_frames, out=self.hr)
+
+    def timed(self, steps, warmup):
+        """-> (ms per step, per-class kernel (ms, launches) per step, counts)."""
+        torch, rh = self.torch, self.rh
+        counts = self.plan_only()
+        if self.net_out is None:
+            # all outputs are allocated once, outside the timed region; the enhance call is sized by
+            # the output capacity (the bins this batch needs plus slack) and told the device-side count
+            self.alloc(min(self.max_bins, counts[1] + 8))
+        for _ in range(warmup):
+            self.step()
+        torch.cuda.synchronize()
+        rh.profile_enable(True)
+        rh.profile_read()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            self.step()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        prof = rh.profile_read()
+        rh.profile_enable(False)
+        return dt / steps * 1e3, {k: (v[0] / steps, v[1] / steps) for k, v in prof.items()}, counts
+
+    def frame_based(self, steps):
+        """100 % of the macroblocks: rh_enhance on whole frames + identity placement -> ms per step."""
+        torch, rh, cfg = self.torch, self.rh, self.cfg
+        s, F = cfg.net.scale, cfg.n_frames
+        places, n_pl = rh.identity_places(F)
+        fb_net = torch.empty((F, cfg.height * s, cfg.width * s, 3), dtype=torch.float32, device="cuda")
+        if self.hr is None:
+            self.alloc(1)
+
+        def fb_step():
+            rh.enhance(self.d_frames, out=fb_net)
+            rh.unpack(fb_net, places, n_pl, self.d_frames, out=self.hr)
+        fb_step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fb_step()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps * 1e3
+
+    def summary(self, ms, prof, counts):
+        cfg = self.cfg
+        S = cfg.bin_size
+        n_boxes, n_bins, _, k_sel = counts
+        px_lr = n_bins * S * S
+        cls_fl, cls_n, network_fl, executed_fl = net_flops(cfg.net, self.composed)
+        if cfg.precision != "bf16":
+            import workloads as wl
+            cls_fl, cls_n = network_fl, len(wl.net_layers(cfg.net))      # fp32 path: all layers are one class
+        conv_ms, conv_n = prof["conv"]
+        launch_s = conv_ms / max(conv_n, 1) * 1e-3
+        flop_per_launch = cls_fl * px_lr / max(cls_n, 1)
+        achieved = flop_per_launch / launch_s if launch_s > 0 else 0.0
+        peak = MFMA_BF16_PEAK if cfg.precision == "bf16" else FP32_VALU_PEAK
+        enh_s = sum(prof[k][0] for k in ("head", "conv", "conv_last")) * 1e-3
+        return {"ms_per_step": ms, "macroblocks_per_s": k_sel / (ms * 1e-3), "n_selected": k_sel, "n_boxes": n_boxes,
+                "n_bins": n_bins, "occupy_ratio": 256.0 * k_sel / px_lr if px_lr else 0.0,
+                "kernel_ms_per_step": {k: v[0] for k, v in prof.items()},
+                "conv_class": {"achieved_tflops": achieved / 1e12, "frac_of_peak": achieved / peak, "avg_launch_us": launch_s * 1e6,
+                               "launches_per_step": conv_n, "flop_per_launch": flop_per_launch},
+                "enhance_tflops_executed": executed_fl * px_lr / max(enh_s, 1e-12) / 1e12,
+                "enhance_tflops_network": network_fl * px_lr / max(enh_s, 1e-12) / 1e12}
+
+    def close(self):
+        self.rh.close()
 
 
 def main():
@@ -66,33 +191,30 @@ def main():
     ap.add_argument("--config", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-frame-based", action="store_true")
-    ap.add_argument("--fraction", type=float, default=None,
-                    help="override the selected fraction of the configuration (the fraction sweep of configuration 4)")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="skip configurations 1, 2, 5 and the selected-fraction sweep of configuration 4")
+    ap.add_argument("--fraction", type=float, default=None, help="override the selected fraction of the configuration")
     ap.add_argument("--importance", choices=["clustered", "uniform"], default=None,
                     help="override the importance recipe (uniform = iid, isolated macroblocks: the packer's worst case)")
     ap.add_argument("--exact-border", action="store_true",
                     help="enhance with rh_enhance_exact (per-layer zeroing of the out-of-frame part of the boxes)")
+    ap.add_argument("--per-layer-tail", action="store_true",
+                    help="run the upsampler and the last conv layer by layer instead of as one composed convolution")
     ap.add_argument("--bin-size", type=int, default=None, help="override the bin side S (pixels)")
     ap.add_argument("--max-box-mbs", type=int, default=0,
                     help="Partition's preset size in macroblocks (0 = the largest that fits a bin; 1 = every "
                          "macroblock its own box, the paper's MB-packing / Block policy)")
-    ap.add_argument("--policy-study", type=int, default=0, metavar="N",
-                    help="occupy ratio (selected-MB pixels / packed pixels) of the packing policies over N random "
-                         "importance maps of the configuration: importance-density order (the paper's), the same "
-                         "with RotatePacking, large-item-first order, and one box per macroblock (MB packing)")
     ap.add_argument("--mem-batch", type=int, default=16, metavar="X",
                     help="also time the memory-bound steps (pack gather, unpack) on X copies of the batch, where "
                          "they are large enough to be bandwidth- rather than launch-bound (0 = skip)")
     ap.add_argument("--no-temporal", action="store_true",
                     help="skip the temporal importance reuse leg (Sec. 3.2.2; reported beside the path, not in `value`)")
+    ap.add_argument("--no-planner", action="store_true", help="skip planner-lite's choice of the bin size")
     ap.add_argument("--temporal-streams", type=int, default=10, help="streams of the temporal leg's chunk")
     ap.add_argument("--temporal-frames", type=int, default=30, help="frames per stream of the temporal leg's chunk")
     ap.add_argument("--sync-counts", action="store_true",
                     help="read the bin count back to the host after rh_pack (one synchronisation per step) and "
                          "enhance exactly that many bins, instead of passing the device-side count")
-    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
-                    help="also run one plain device copy of this many MiB (reference for scaling rocprofv3's "
-                         "FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (--gpus 1); no multi-GPU figure exists", file=sys.stderr)
@@ -113,89 +235,48 @@ def main():
         cfg = wl.replace(cfg, name=f"{cfg.name}_T{args.max_box_mbs}")
     if args.exact_border:
         cfg = wl.replace(cfg, name=f"{cfg.name}_exact_border")
-    F, s = cfg.n_frames, cfg.net.scale
-    frames, imp, segs = wl.make_frames(cfg), wl.make_importance(cfg), wl.make_segments(cfg)
-    blob = wl.make_weights(cfg.net, cfg.weight_seed, cfg.precision)
-    # room for the packer's worst case (isolated macroblocks: one box each)
-    max_bins = 512 if (cfg.index == 5 or cfg.importance == "uniform" or args.max_box_mbs == 1) else 256
-    max_bins = max_bins * max(1, (128 // cfg.bin_size) ** 2)
-    rh = RH(frame_w=cfg.width, frame_h=cfg.height, max_frames=F, halo=cfg.halo, bin_size=cfg.bin_size,
-            max_bins=max_bins, net=cfg.net, weights=blob, precision=cfg.precision, max_box_mbs=args.max_box_mbs)
-    d_frames = torch.from_numpy(frames).cuda()
-    d_imp = torch.from_numpy(imp).cuda()
-    seg_rows = [tuple(r) for r in segs.tolist()]
-    S = cfg.bin_size
-    # all outputs are allocated once, outside the timed region
-    po = None
-    net_out = torch.empty((max_bins, S * s, S * s, 3), dtype=torch.float32, device="cuda")
-    hr = torch.empty((F, cfg.height * s, cfg.width * s, 3), dtype=torch.uint8, device="cuda")
+    if args.per_layer_tail:
+        cfg = wl.replace(cfg, name=f"{cfg.name}_per_layer_tail")
+    F, s, S = cfg.n_frames, cfg.net.scale, cfg.bin_size
 
-    def step():
-        nonlocal po
-        mask, lst, n_sel = rh.select_regions(d_imp, seg_rows)
-        po = rh.pack(d_frames, d_imp, mask, lst, n_sel, out=po)
-        if args.exact_border:
-            rh.enhance_exact(po.bins, po.boxes, po.counts, n=max_bins, n_valid=po.counts[1:2], out=net_out)
-        elif args.sync_counts:
-            rh.enhance(po.bins, n=rh.read_counts(po.counts)[1], out=net_out)
-        else:
-            rh.enhance(po.bins, n=max_bins, n_valid=po.counts[1:2], out=net_out)   # device-side bin count
-        rh.unpack(net_out, po.places, po.counts[3:4], d_frames, out=hr)
-
-    if args.calibrate_copy:
-        src = torch.full((args.calibrate_copy << 20,), 7, dtype=torch.uint8, device="cuda")
-        dst = torch.empty_like(src)
-        dst.copy_(src)
-        torch.cuda.synchronize()
-    for _ in range(args.warmup):
-        step()
+    # A plain device copy of known size, outside every timed region: what rocprofv3's FETCH_SIZE /
+    # WRITE_SIZE read for it calibrates those counters in a counter run of this same command.
+    cal_src = torch.full((256 << 20,), 7, dtype=torch.uint8, device="cuda")
+    cal_dst = torch.empty_like(cal_src)
+    cal_dst.copy_(cal_src)
     torch.cuda.synchronize()
-    counts = rh.read_counts(po.counts)
+    del cal_src, cal_dst
+
+    run = Runner(cfg, args, max_box_mbs=args.max_box_mbs, per_layer_tail=args.per_layer_tail)
+    ms_step, prof, counts = run.timed(args.steps, args.warmup)
+    sm = run.summary(ms_step, prof, counts)
     n_boxes, n_bins, _, k_sel = counts
-    rh.profile_enable(True)
-    rh.profile_read()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    prof = rh.profile_read()
-    rh.profile_enable(False)
-
-    ms_step = dt / args.steps * 1e3
-    mbs_per_s = k_sel * args.steps / dt
-    out_mpix = F * cfg.height * s * cfg.width * s * args.steps / dt / 1e6
+    rh, po, d_frames, d_imp, seg_rows, blob = run.rh, run.po, run.d_frames, run.d_imp, run.seg_rows, run.blob
+    frames, imp, segs = run.frames, run.imp, run.segs
     px_lr = n_bins * S * S
-    conv_fl, conv_launches = conv_flops_per_lr_pixel(cfg.net)
-    if cfg.precision != "bf16":
-        # the fp32 path times all its layers as one class: direct convs on the vector ALUs
-        conv_fl, conv_launches = total_flops_per_lr_pixel(cfg.net), len(wl.net_layers(cfg.net))
-    conv_ms, conv_n = prof["conv"]
-    avg_launch_s = conv_ms / max(conv_n, 1) * 1e-3
-    flop_per_launch = conv_fl * px_lr / conv_launches
-    achieved = flop_per_launch / avg_launch_s if avg_launch_s > 0 else 0.0
-    PEAK = MFMA_BF16_PEAK if cfg.precision == "bf16" else FP32_VALU_PEAK
+    cc = sm["conv_class"]
+    traffic = PROFILED_TRAFFIC.get(cfg.name) if run.composed else None
 
     result = {
         "metric": "enhanced macroblocks/s",
-        "value": mbs_per_s, "unit": "MB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "value": sm["macroblocks_per_s"], "unit": "MB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if cfg.precision == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": cfg.name, "frames": F, "frame": [cfg.width, cfg.height], "scale": s,
                    "selected_fraction": cfg.frac, "halo": cfg.halo, "bin_size": S,
-                   "n_selected": k_sel, "n_boxes": n_boxes, "n_bins": n_bins,
-                   "occupy_ratio": 256.0 * k_sel / (n_bins * S * S) if n_bins else 0.0},
-        "output_mpixel_per_s": out_mpix,
-        "kernel_ms_per_step": {k: v[0] / args.steps for k, v in prof.items()},
+                   "n_selected": k_sel, "n_boxes": n_boxes, "n_bins": n_bins, "occupy_ratio": sm["occupy_ratio"],
+                   "tail": "composed 5x5 conv" if run.composed else "layer by layer"},
+        "output_mpixel_per_s": F * cfg.height * s * cfg.width * s / (ms_step * 1e-3) / 1e6,
+        "kernel_ms_per_step": sm["kernel_ms_per_step"],
         "roofline": {"bound": "mfma" if cfg.precision == "bf16" else "alu",
                      "kernel": CONV_KERNEL.get(cfg.net.channels, "k_conv_mfma") if cfg.precision == "bf16" else "k_conv3x3_f32 (all layers)",
-                     "achieved": achieved / 1e12,
-                     "peak": PEAK / 1e12, "unit": "TFLOP/s", "frac": achieved / PEAK,
-                     "traffic": MEASURED_TRAFFIC.get(cfg.name), "avg_launch_us": avg_launch_s * 1e6, "launches_per_step": conv_n / args.steps,
-                     "flop_per_launch": flop_per_launch},
-        "enhance_tflops_all_layers": total_flops_per_lr_pixel(cfg.net) * px_lr /
-                                     max(sum(prof[k][0] for k in ("head", "conv", "conv_last")) / args.steps * 1e-3, 1e-12) / 1e12,
+                     "achieved": cc["achieved_tflops"], "peak": (MFMA_BF16_PEAK if cfg.precision == "bf16" else FP32_VALU_PEAK) / 1e12,
+                     "unit": "TFLOP/s", "frac": cc["frac_of_peak"],
+                     "traffic": traffic[0] if traffic else None, "traffic_source": traffic[1] if traffic else None,
+                     "avg_launch_us": cc["avg_launch_us"], "launches_per_step": cc["launches_per_step"],
+                     "flop_per_launch": cc["flop_per_launch"]},
+        "enhance_tflops_executed": sm["enhance_tflops_executed"],
+        "enhance_tflops_network": sm["enhance_tflops_network"],
     }
 
     # ---- the memory-bound steps: algorithmic bytes / event time, at batch size and at X batches ----
@@ -205,20 +286,25 @@ def main():
         unpack_b = nf * cfg.height * s * cfg.width * s * 3 + nf * cfg.height * cfg.width * 3 + nsel * (16 * s) ** 2 * 3 * 4
         return pack_b, unpack_b
 
+    def mem_row(nbytes, ms):
+        us = ms * 1e3
+        gbs = nbytes / (us * 1e-6) / 1e9 if us > 0 else 0.0
+        return {"bytes": nbytes, "us": us, "GB/s": gbs, "frac_of_hbm_peak": gbs * 1e9 / HBM_PEAK}
+
     boxes_host = RH.boxes_np(po.boxes, n_boxes)
     pb, ub = mem_bytes(n_bins, boxes_host, k_sel, F)
     sel_bytes = lambda nf, nsel: nf * rh.mbh * rh.mbw * 5 + nsel * 4          # 4 B read + 1 B mask per MB, 4 B per selected MB
-    sb = sel_bytes(F, k_sel)
     result["memory_steps"] = {
-        "select": {"bytes": sb, "us": prof["select"][0] / args.steps * 1e3, "GB/s": sb / (prof["select"][0] / args.steps * 1e-3) / 1e9,
-                   "note": "latency-bound: tens of kilobytes"},
-        "pack_gather": {"bytes": pb, "us": prof["gather"][0] / args.steps * 1e3, "GB/s": pb / (prof["gather"][0] / args.steps * 1e-3) / 1e9},
-        "unpack": {"bytes": ub, "us": prof["unpack"][0] / args.steps * 1e3, "GB/s": ub / (prof["unpack"][0] / args.steps * 1e-3) / 1e9},
-        "hbm_peak_GB/s": 8000.0}
+        "select": dict(mem_row(sel_bytes(F, k_sel), prof["select"][0]), note="latency-bound: tens of kilobytes"),
+        "plan": {"us": prof["plan"][0] * 1e3,
+                 "share_of_enhance_time": prof["plan"][0] / max(prof["head"][0] + prof["conv"][0] + prof["conv_last"][0], 1e-12)},
+        "pack_gather": mem_row(pb, prof["gather"][0]),
+        "unpack": mem_row(ub, prof["unpack"][0]),
+        "hbm_peak_GB/s": HBM_PEAK / 1e9}
     if args.mem_batch > 0:
         X = args.mem_batch
         rhx = RH(frame_w=cfg.width, frame_h=cfg.height, max_frames=F * X, halo=cfg.halo, bin_size=cfg.bin_size,
-                 max_bins=max_bins * X, net=cfg.net, weights=blob, precision=cfg.precision,
+                 max_bins=run.max_bins * X, net=cfg.net, weights=blob, precision=cfg.precision,
                  max_box_mbs=args.max_box_mbs)
         xf = d_frames.repeat(X, 1, 1, 1)
         xi = d_imp.repeat(X, 1, 1)
@@ -245,10 +331,11 @@ def main():
         xpb, xub = mem_bytes(xc[1], xboxes, xc[3], F * X)
         result["memory_steps"][f"x{X}"] = {
             "frames": F * X, "n_bins": xc[1],
-            "select": {"bytes": sel_bytes(F * X, xc[3]), "us": xprof["select"][0] / reps * 1e3,
-                       "GB/s": sel_bytes(F * X, xc[3]) / (xprof["select"][0] / reps * 1e-3) / 1e9},
-            "pack_gather": {"bytes": xpb, "us": xprof["gather"][0] / reps * 1e3, "GB/s": xpb / (xprof["gather"][0] / reps * 1e-3) / 1e9},
-            "unpack": {"bytes": xub, "us": xprof["unpack"][0] / reps * 1e3, "GB/s": xub / (xprof["unpack"][0] / reps * 1e-3) / 1e9}}
+            "select": mem_row(sel_bytes(F * X, xc[3]), xprof["select"][0] / reps),
+            "plan_us": xprof["plan"][0] / reps * 1e3,
+            "pack_gather": mem_row(xpb, xprof["gather"][0] / reps),
+            "unpack": mem_row(xub, xprof["unpack"][0] / reps)}
+        rhx.close()
         del rhx, xf, xi, xhr, xnet, xpo
 
     if not args.no_temporal:
@@ -294,55 +381,73 @@ def main():
             assert np.array_equal(d_phi.cpu().numpy().view(np.uint64)[: len(sub)], o_phi), "temporal leg: Phi differs from the oracle"
             result["temporal_reuse"]["cpu_oracle"] = {"phi_us_per_frame": (t1 - t0) / len(sub) * 1e6, "cores": 1,
                                                       "sample": f"{len(sub)} frames"}
+        rht.close()
         del rht, d_res
 
-    if args.policy_study > 0:
-        pols = {"density": dict(), "density+rotate": dict(rotate=True), "area": dict(sort_policy="area"),
-                "area+rotate": dict(sort_policy="area", rotate=True), "mb_packing": dict(max_box_mbs=1)}
-        ctxs = {k: RH(frame_w=cfg.width, frame_h=cfg.height, max_frames=F, halo=cfg.halo, bin_size=cfg.bin_size,
-                      max_bins=4 * max_bins, net=cfg.net, weights=blob, precision=cfg.precision, **kw)
-                for k, kw in pols.items()}
-        occ = {k: [] for k in pols}
-        plan_ms = {k: 0.0 for k in pols}
-        for it in range(args.policy_study):
-            ci = wl.replace(cfg, index=1000 + it)                     # another seed of the same recipe
-            x_imp = torch.from_numpy(wl.make_importance(ci)).cuda()
-            x_segs = [tuple(r) for r in wl.make_segments(ci).tolist()]
-            for k, c in ctxs.items():
-                c.profile_enable(True)
-                m_, l_, n_ = c.select_regions(x_imp, x_segs)
-                o_ = c.pack(d_frames, x_imp, m_, l_, n_)
-                cnt = c.read_counts(o_.counts)
-                plan_ms[k] += c.profile_read()["plan"][0]
-                occ[k].append(256.0 * cnt[3] / (cnt[1] * S * S) if cnt[1] else 0.0)
-        result["policy_study"] = {"n": args.policy_study, "bin_size": S, "halo": cfg.halo}
-        for k, v in occ.items():
-            a = np.asarray(v)
-            result["policy_study"][k] = {"occupy_mean": float(a.mean()), "occupy_p05": float(np.percentile(a, 5)),
-                                         "occupy_p10": float(np.percentile(a, 10)), "occupy_p50": float(np.percentile(a, 50)),
-                                         "plan_ms_mean": plan_ms[k] / args.policy_study}
-        for c in ctxs.values():
-            c.close()
-
+    fb_ms = None
     if not args.no_frame_based:
-        # 100 % of the macroblocks: rh_enhance on whole frames + identity placement
-        places, n_pl = rh.identity_places(F)
-        fb_net = torch.empty((F, cfg.height * s, cfg.width * s, 3), dtype=torch.float32, device="cuda")
-
-        def fb_step():
-            rh.enhance(d_frames, out=fb_net)
-            rh.unpack(fb_net, places, n_pl, d_frames, out=hr)
-        fb_step()
-        torch.cuda.synchronize()
-        n_fb = max(2, args.steps // 4)
-        t0 = time.perf_counter()
-        for _ in range(n_fb):
-            fb_step()
-        torch.cuda.synchronize()
-        fdt = (time.perf_counter() - t0) / n_fb
-        result["frame_based"] = {"ms_per_step": fdt * 1e3, "macroblocks_per_s": F * cfg.mbw * cfg.mbh / fdt,
-                                 "region_speedup": fdt * 1e3 / ms_step,
+        fb_ms = run.frame_based(max(2, args.steps // 4))
+        result["frame_based"] = {"ms_per_step": fb_ms, "macroblocks_per_s": F * cfg.mbw * cfg.mbh / (fb_ms * 1e-3),
+                                 "region_speedup": fb_ms / ms_step,
                                  "pixel_ratio": F * cfg.width * cfg.height / max(px_lr, 1)}
+    other_ms = sum(prof[k][0] for k in ("select", "plan", "gather", "unpack"))
+    run.close()
+    del run, rh, po
+
+    if not args.no_other_configs:
+        # The other benchmark configurations, GPU legs only (fewer steps): 1, 2 and 5 as listed, and
+        # configuration 4 = configuration 3's batch with 5 ... 100 % of the macroblocks selected, for
+        # clustered and for iid-uniform importance; region-based time against the frame-based run.
+        oc = {}
+        o_steps = max(3, args.steps // 4)
+
+        def leg(c, fb=None):
+            r = Runner(c, args)
+            ms, pr, cn = r.timed(o_steps, 2)
+            d = r.summary(ms, pr, cn)
+            d["conv_class_frac"] = d.pop("conv_class")["frac_of_peak"]
+            d["plan_ms"] = d["kernel_ms_per_step"]["plan"]
+            del d["kernel_ms_per_step"]
+            if fb is None:
+                fb = r.frame_based(2)
+            d["frame_based_ms"] = fb
+            d["region_speedup"] = fb / ms
+            r.close()
+            return d, fb
+        for ci in (1, 2, 5):
+            c = wl.config(ci)
+            oc[c.name], _ = leg(c)
+        plain3 = (args.config in (3, 4) and not args.exact_border and not args.per_layer_tail and args.bin_size is None
+                  and not args.max_box_mbs)
+        sweep, fb4 = {}, (fb_ms if plain3 else None)
+        for kind in ("clustered", "uniform"):
+            for frac in (0.05, 0.10, 0.20, 0.50, 1.00):
+                d, fb4 = leg(wl.replace(wl.config(4), frac=frac, importance=kind), fb4)
+                sweep[f"{kind}_{int(frac * 100)}pct"] = d
+        oc["cfg4_fraction_sweep"] = sweep
+        result["other_configs"] = oc
+
+    if not args.no_planner and cfg.precision == "bf16":
+        # Planner-lite (Sec. 3.4): bin size and bins per launch from the cost curve kept in the tree and
+        # the packer's bin counts for this batch; the chosen geometry is then timed end to end.
+        from paper_2407_16990_amd import planner as PL
+        if os.path.exists(PL.CURVE_FILE):
+            curve = PL.load_curve()
+            cands = PL.measure_candidates(d_frames, d_imp, seg_rows, cfg.net, blob, cfg.precision, cfg.halo,
+                                          [(Sx, 0) for Sx in sorted(curve)])
+            ch = PL.choose(curve, cands, other_ms=other_ms)
+            pl = {"candidates": [{"bin_size": c.bin_size, "n_bins": c.n_bins} for c in cands],
+                  "chosen": {"bin_size": ch.bin_size, "bins_per_launch": ch.bins_per_launch, "launches": ch.launches,
+                             "predicted_ms_per_step": ch.ms_per_batch, "predicted_macroblocks_per_s": ch.macroblocks_per_s}}
+            if ch.bin_size != S:
+                r2 = Runner(wl.replace(cfg, bin_size=ch.bin_size), args)
+                ms2, _, cn2 = r2.timed(max(3, args.steps // 2), 2)
+                pl["chosen"].update({"measured_ms_per_step": ms2, "measured_macroblocks_per_s": cn2[3] / (ms2 * 1e-3),
+                                     "speedup_over_configured_bin_size": ms_step / ms2})
+                r2.close()
+            else:
+                pl["chosen"].update({"measured_ms_per_step": ms_step, "speedup_over_configured_bin_size": 1.0})
+            result["planner_lite"] = pl
 
     if not args.no_cpu_baseline:
         import oracle

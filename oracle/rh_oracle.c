@@ -9,7 +9,8 @@
  * Everything is written as the plain definition (selection, gather, 3x3
  * convolution, pixel shuffle, bilinear interpolation, paste) or, for the
  * bin-packing heuristic, as the steps of Alg. 1 in the paper's order.  Loops
- * are naive; the only parallelism is OpenMP over independent images.
+ * are naive; the only parallelism is OpenMP over independent images or, when a batch has fewer
+ * images than there are threads, over the independent output rows of a convolution.
  * Floating point is fp64 except where a value decides an integer that the
  * GPU decides in fp32 (the box sort key's numerator and the final 8-bit
  * quantisation), which is done in fp32 here too.
@@ -27,6 +28,7 @@
  * "parity unpinned" with respect to the paper.
  */
 #include <math.h>
+#include <omp.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -363,6 +365,9 @@ void orc_bilinear(const uint8_t* in, int H, int W, int s, uint8_t* out)
 void orc_conv3x3(const double* in, int H, int W, int Cin, const float* w, const float* b,
                  int Cout, int relu, double* out)
 {
+    /* every output value is computed on its own: rows may go to different threads (this pragma is
+     * inert inside orc_sr_forward's parallel loop over images, nested parallelism being off) */
+#pragma omp parallel for schedule(dynamic, 1)
     for (int y = 0; y < H; ++y) for (int x = 0; x < W; ++x) for (int co = 0; co < Cout; ++co) {
         double acc = (double)b[co];
         for (int ky = 0; ky < 3; ++ky) {
@@ -477,7 +482,7 @@ void orc_sr_forward(int topology, int C, int nblk, int s, const float* blob,
                     const uint8_t* in, int N, int H, int W, const uint8_t* keep, double* out)
 {
     size_t ipx = (size_t)H * W * 3, opx = ipx * s * s;
-#pragma omp parallel for schedule(dynamic, 1)
+#pragma omp parallel for schedule(dynamic, 1) if (N >= omp_get_max_threads())
     for (int n = 0; n < N; ++n)
         sr_one(topology, C, nblk, s, blob, in + n * ipx, H, W, keep ? keep + (size_t)n * H * W : NULL, out + n * opx);
 }
