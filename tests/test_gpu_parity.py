@@ -8,7 +8,7 @@ import torch
 import oracle
 import workloads as wl
 from paper_2407_16990_amd import RH, RhError
-from gpu_common import check_select_and_plan, dev, gpu_select, make_rh, rel_l2
+from gpu_common import bf16_max_abs_bar, check_net, check_select_and_plan, dev, gpu_select, make_rh, rel_l2
 
 pytestmark = pytest.mark.gpu
 
@@ -31,9 +31,7 @@ def full_path_check(cfg, n_frames=None, precision=None, segs=None, max_bins=None
     g_net = rh.enhance(po.bins, n=o_plan.n_bins)
     o_net = oracle.sr_forward(cfg.net, blob, o_bins)
     tol = 1e-5 if precision == "fp32" else 1e-2
-    e = rel_l2(g_net.cpu().numpy(), o_net)
-    print(f"[{cfg.name}/{precision}] n_bins={o_plan.n_bins} net rel-L2={e:.3e}", flush=True)
-    assert e <= tol
+    check_net(g_net.cpu().numpy(), o_net, precision, f"{cfg.name} n_bins={o_plan.n_bins}")
     g_net2 = torch.zeros_like(g_net)
     rh.enhance(po.bins, n=o_plan.n_bins, n_valid=po.counts[1:2], out=g_net2)
     assert torch.equal(g_net, g_net2)
@@ -53,7 +51,8 @@ def full_path_check(cfg, n_frames=None, precision=None, segs=None, max_bins=None
     if precision == "fp32":
         assert d.max() <= 1 and (d > 0).mean() < 1e-3
     else:
-        assert np.abs(g_sel - o_sel).max() <= 2.0 / 255.0 and d.max() <= 2
+        bar = bf16_max_abs_bar(o_net)
+        assert np.abs(g_sel - o_sel).max() <= bar and d.max() <= round(bar * 255)
     rh.close()
 
 
@@ -201,7 +200,7 @@ def test_frame_based_run_fp32_matches_oracle():
     hr, sel = rh.unpack(net, places, n, d_frames, want_sel=True)
     o_net = oracle.sr_forward(cfg.net, blob, frames)
     o_hr, o_sel = oracle.unpack(frames, 2, o_net, oracle.identity_places(2, cfg.mbh, cfg.mbw))
-    assert rel_l2(net.cpu().numpy(), o_net) <= 1e-5
+    check_net(net.cpu().numpy(), o_net, "fp32", "frame-based cfg1")
     assert rel_l2(sel.cpu().numpy(), o_sel) <= 1e-5
     assert np.abs(hr.cpu().numpy().astype(int) - o_hr.astype(int)).max() <= 1
     rh.close()
@@ -230,12 +229,19 @@ def test_small_topologies_bf16_layer_by_layer_tail(net):
     full_path_check(cfg, per_layer_tail=True)
 
 
-def test_cfg2_two_frames_bf16():
-    full_path_check(wl.config(2), n_frames=2)
+def test_cfg2_all_frames_bf16():
+    full_path_check(wl.config(2))
 
 
 def test_cfg3_two_frames_bf16():
     full_path_check(wl.config(3), n_frames=2)
+
+
+def test_cfg3_two_frames_bf16_larger_output_amplitude():
+    """The same net with a last conv 1.6 times larger (output rms 0.08, beyond the range the 2/255
+    bar is claimed for): the error grows in proportion and the bar with it."""
+    cfg = wl.config(3)
+    full_path_check(wl.replace(cfg, net=wl.replace(cfg.net, tail_scale=0.02)), n_frames=2)
 
 
 def test_frame_based_run_bf16_matches_oracle():
@@ -249,7 +255,7 @@ def test_frame_based_run_bf16_matches_oracle():
     hr, sel = rh.unpack(net, places, n, d_frames, want_sel=True)
     o_net = oracle.sr_forward(cfg.net, blob, frames)
     o_hr, o_sel = oracle.unpack(frames, 4, o_net, oracle.identity_places(1, cfg.mbh, cfg.mbw))
-    assert rel_l2(net.cpu().numpy(), o_net) <= 1e-2
+    check_net(net.cpu().numpy(), o_net, "bf16", "frame-based 112x80")
     assert rel_l2(sel.cpu().numpy(), o_sel) <= 1e-2 and np.abs(sel.cpu().numpy() - o_sel).max() <= 2 / 255
     assert np.abs(hr.cpu().numpy().astype(int) - o_hr.astype(int)).max() <= 2
     rh.close()
@@ -291,19 +297,21 @@ def test_rotate_whole_path_fp32():
 @pytest.mark.parametrize("scale", [3, 4])
 def test_rotate_whole_path_bf16_edsr(scale):
     cfg = wl.replace(wl.config(3), n_frames=2, width=160, height=112, halo=6, bin_size=96, importance="uniform", frac=0.4,
-                     net=wl.Net("edsr", 64, 2, scale, 0.02))
+                     net=wl.Net("edsr", 64, 2, scale, 0.05))
     full_path_check(cfg, rotate=True, expect_turned=True)
 
 
 # ---- full benchmark sizes, in the launch configuration bench.py times --------------------------
 
-@pytest.mark.parametrize("ci,sample", [(3, 3), (5, 2)])
-def test_full_size_bf16_sampled_bins(ci, sample):
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("ci,sample", [(3, None), (5, 8)])
+def test_full_size_bf16(ci, sample):
     """The whole batch of configurations 3 and 5 through the path exactly as bench.py drives it
     (capacity-sized enhance call with the device-side bin count).  Metadata and packed bytes are
-    compared in full; the network output and the pasted pixels on a sample of bins the oracle can
-    afford (first, last, and one in the middle), every unselected macroblock against the bilinear
-    base, and bins past the count must stay untouched."""
+    compared in full.  Configuration 3: the network output of ALL bins and the pasted pixels of ALL
+    selected macroblocks, element by element.  Configuration 5: the same on 8 bins spread over the
+    batch.  Every unselected macroblock of every frame against the bilinear base, and bins past the
+    count must stay untouched."""
     cfg = wl.config(ci)
     F, s, S = cfg.n_frames, cfg.net.scale, cfg.bin_size
     frames, imp, segs = wl.make_frames(cfg), wl.make_importance(cfg), wl.make_segments(cfg)
@@ -317,30 +325,33 @@ def test_full_size_bf16_sampled_bins(ci, sample):
     rh.enhance(po.bins[: nb + 1], n=nb + 1, n_valid=po.counts[1:2], out=net_out)
     assert bool((net_out[nb] == 7.0).all()), "an image past the device-side count was written"
     hr, sel = rh.unpack(net_out, po.places, po.counts[3:4], d_frames, want_sel=True)
-    pick = sorted({0, nb // 2, nb - 1})[:sample]
+    pick = list(range(nb)) if sample is None else sorted({int(round(i * (nb - 1) / (sample - 1))) for i in range(sample)})
+    print(f"[{cfg.name}] {nb} bins, oracle on {len(pick)} of them", flush=True)
     o_net = oracle.sr_forward(cfg.net, blob, o_bins[pick])
-    g_net = net_out[pick].cpu().numpy()
-    e = rel_l2(g_net, o_net)
-    print(f"[{cfg.name}] {nb} bins, sampled {pick}: net rel-L2={e:.3e}", flush=True)
-    assert e <= 1e-2
-    # pasted pixels of the macroblocks that live in the sampled bins
+    check_net(net_out[pick].cpu().numpy(), o_net, "bf16", f"{cfg.name} {len(pick)} of {nb} bins")
+    bar = bf16_max_abs_bar(o_net)
+    assert bar == 2.0 / 255.0, "the benchmark nets stay inside the output range the 2/255 bar is claimed for"
+    # pasted pixels of the macroblocks that live in the checked bins
     B = 16 * s
     g_sel = sel.cpu().numpy()
     per = cfg.mbw * cfg.mbh
     worst, n_chk = 0.0, 0
     base_cache = {}
+    where = {b: i for i, b in enumerate(pick)}
     for i, (g, box, b, px, py) in enumerate(o_plan.places.tolist()):
-        if b not in pick:
+        if b not in where:
             continue
         f, rem = divmod(g, per); y, x = divmod(rem, cfg.mbw)
         if f not in base_cache:
             base_cache[f] = oracle.bilinear(frames[f], s)
         base = base_cache[f][y * B:(y + 1) * B, x * B:(x + 1) * B].astype(np.float32) / np.float32(255.0)
-        blk = o_net[pick.index(b), py * s:py * s + B, px * s:px * s + B].astype(np.float32)
+        blk = o_net[where[b], py * s:py * s + B, px * s:px * s + B].astype(np.float32)
         want = np.clip(base + blk, 0.0, 1.0)
         worst = max(worst, float(np.abs(g_sel[i] - want).max())); n_chk += 1
-    print(f"[{cfg.name}] {n_chk} pasted macroblocks checked, max abs={worst:.3e}", flush=True)
-    assert n_chk > 0 and worst <= 2.0 / 255.0
+    print(f"[{cfg.name}] {n_chk} of {len(o_plan.places)} pasted macroblocks checked, max abs={worst:.3e} (bar {bar:.3e})", flush=True)
+    assert n_chk > 0 and worst <= bar
+    if sample is None:
+        assert n_chk == len(o_plan.places)
     # every unselected macroblock of every frame is the bilinear base, byte for byte
     g_hr = hr.cpu().numpy()
     o_mask = oracle.select(imp, segs)[0]
@@ -350,6 +361,29 @@ def test_full_size_bf16_sampled_bins(ci, sample):
             base = oracle.bilinear(frames[f], s)
         keep = ~np.kron(o_mask[f], np.ones((B, B), dtype=np.uint8)).astype(bool)
         assert np.array_equal(g_hr[f][keep], base[keep])
+    rh.close()
+
+
+@pytest.mark.timeout(300)
+def test_frame_based_run_bf16_full_size_frames():
+    """The 100 % run of the fraction sweep at its real shape: whole 480 x 272 frames through rh_enhance
+    and the identity placement, two frames of the batch against the oracle element by element."""
+    cfg = wl.config(4)
+    F, s = 2, cfg.net.scale
+    frames = wl.make_frames(cfg, F)
+    blob = wl.make_weights(cfg.net, cfg.weight_seed, "bf16")
+    rh = make_rh(cfg, blob, n_frames=F, max_bins=4)
+    d_frames = dev(frames)
+    net = rh.enhance(d_frames)
+    places, n = rh.identity_places(F)
+    hr, sel = rh.unpack(net, places, n, d_frames, want_sel=True)
+    o_net = oracle.sr_forward(cfg.net, blob, frames)
+    o_hr, o_sel = oracle.unpack(frames, s, o_net, oracle.identity_places(F, cfg.mbh, cfg.mbw))
+    check_net(net.cpu().numpy(), o_net, "bf16", "frame-based 2 x 480x272")
+    d = np.abs(sel.cpu().numpy() - o_sel)
+    print(f"[frame-based 2 x 480x272] pasted pixels max abs={d.max():.3e}", flush=True)
+    assert d.max() <= bf16_max_abs_bar(o_net) == 2.0 / 255.0
+    assert np.abs(hr.cpu().numpy().astype(int) - o_hr.astype(int)).max() <= 2
     rh.close()
 
 
@@ -369,12 +403,13 @@ def exact_border_check(cfg, precision, rotate=False, border_bias=True):
     o_plain = oracle.sr_forward(cfg.net, blob, o_bins)
     g_net = rh.enhance_exact(po.bins, po.boxes, po.counts, n=o_plan.n_bins, n_valid=po.counts[1:2]).cpu().numpy()
     tol = 1e-5 if precision == "fp32" else 1e-2
-    e, e_plain = rel_l2(g_net, o_net), rel_l2(g_net, o_plain)
-    print(f"[{cfg.name}/{precision}] exact-border net rel-L2={e:.3e} (against the plain mode: {e_plain:.3e})", flush=True)
+    e, _ = check_net(g_net, o_net, precision, f"{cfg.name} exact-border")
+    e_plain = rel_l2(g_net, o_plain)
+    print(f"[{cfg.name}/{precision}] exact-border against the plain mode: {e_plain:.3e}", flush=True)
     assert e <= tol and e_plain > 3 * e
     # the plain call is unchanged by the exact one having run
     g_plain = rh.enhance(po.bins, n=o_plan.n_bins).cpu().numpy()
-    assert rel_l2(g_plain, o_plain) <= tol
+    check_net(g_plain, o_plain, precision, f"{cfg.name} plain after exact")
     rh.close()
     return g_net, o_plan, frames, blob
 
@@ -426,7 +461,7 @@ def test_partial_macroblock_frames_whole_path(w, h, net, precision):
     g_net = rh.enhance(po.bins, n=o_plan.n_bins)
     o_net = oracle.sr_forward(cfg.net, blob, o_bins)
     tol = 1e-5 if precision == "fp32" else 1e-2
-    assert rel_l2(g_net.cpu().numpy(), o_net) <= tol
+    check_net(g_net.cpu().numpy(), o_net, precision, f"partial {w}x{h}")
     sel0 = torch.full((po.places.shape[0], 16 * s, 16 * s, 3), 9.0, dtype=torch.float32, device="cuda")   # stale values must be overwritten
     hr, sel = rh.unpack(g_net, po.places, po.counts[3:4], d_frames, want_sel=True, sel=sel0)
     o_hr, o_sel = oracle.unpack(frames, s, o_net, o_plan.places)
@@ -449,7 +484,7 @@ def test_partial_macroblock_frames_whole_path(w, h, net, precision):
     hr2, sel2 = rh.unpack(f_net, places, n, d_frames, want_sel=True)
     of_net = oracle.sr_forward(cfg.net, blob, frames)
     o_hr2, o_sel2 = oracle.unpack(frames, s, of_net, oracle.identity_places(F, cfg.mbh, cfg.mbw))
-    assert rel_l2(f_net.cpu().numpy(), of_net) <= tol
+    check_net(f_net.cpu().numpy(), of_net, precision, f"partial {w}x{h} frame-based")
     assert rel_l2(sel2.cpu().numpy(), o_sel2) <= tol
     assert np.abs(hr2.cpu().numpy().astype(np.int16) - o_hr2.astype(np.int16)).max() <= (1 if precision == "fp32" else 2)
     rh.close()
@@ -470,7 +505,6 @@ def test_enhance_small_and_ragged_images(precision, net):
         imgs = rng.integers(0, 256, size=(n, h, w, 3), dtype=np.uint8)
         got = rh.enhance(dev(imgs)).cpu().numpy()
         want = oracle.sr_forward(net, blob, imgs)
-        e = rel_l2(got, want)
-        print(f"[{net.topology}{net.channels}x{net.scale}/{precision}] {n}x{h}x{w}: rel-L2 {e:.3e}", flush=True)
-        assert got.shape == want.shape and e <= tol
+        assert got.shape == want.shape
+        check_net(got, want, precision, f"{net.topology}{net.channels}x{net.scale} {n}x{h}x{w}")
     rh.close()
