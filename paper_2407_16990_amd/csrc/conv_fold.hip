@@ -241,23 +241,32 @@ __global__ __launch_bounds__(64) void k_fold_ring(fold_args a)
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[e] = bias[(e >> 2) * 8 + hi * 4 + (e & 3)];
     const __bf16* img = a.in + (size_t)n * a.H * a.W * CIN;
-    for (int ky = 0; ky < 5; ++ky) {
+    // one tap row (5 taps x KS k-steps) of operands is requested while the previous one is multiplied:
+    // a wave that waited for every tap's loads in turn spent 100 load latencies per pixel group
+    uint4 A[2][5][KS], B[2][5][KS];
+    auto load_row = [&](int ky, uint4 (&Ar)[5][KS], uint4 (&Br)[5][KS]) __attribute__((always_inline)) {
         const int yy = y + ky - 2;
         const bool row_ok = valid && yy >= 0 && yy < a.H;
 #pragma unroll
         for (int kx = 0; kx < 5; ++kx) {
             const int xx = x + kx - 2;
             const bool ok = row_ok && xx >= 0 && xx < a.W;
-            uint4 A[KS], B[KS];
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
-                A[ks] = wp[((ky * 5 + kx) * KS + ks) * 64 + lane];
-                B[ks] = ok ? *(const uint4*)(img + ((size_t)yy * a.W + xx) * CIN + ks * 16 + hi * 8) : make_uint4(0, 0, 0, 0);
+                Ar[kx][ks] = wp[((ky * 5 + kx) * KS + ks) * 64 + lane];
+                Br[kx][ks] = ok ? *(const uint4*)(img + ((size_t)yy * a.W + xx) * CIN + ks * 16 + hi * 8) : make_uint4(0, 0, 0, 0);
             }
+        }
+    };
+    load_row(0, A[0], B[0]);
+#pragma unroll
+    for (int ky = 0; ky < 5; ++ky) {
+        if (ky + 1 < 5) load_row(ky + 1, A[(ky + 1) & 1], B[(ky + 1) & 1]);
+#pragma unroll
+        for (int kx = 0; kx < 5; ++kx)
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks)
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8*)&A[ks], *(const bf16x8*)&B[ks], acc, 0, 0, 0);
-        }
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8*)&A[ky & 1][kx][ks], *(const bf16x8*)&B[ky & 1][kx][ks], acc, 0, 0, 0);
     }
     if (valid) fold_store(a, acc, n, y, x, chunk, hi);
 }

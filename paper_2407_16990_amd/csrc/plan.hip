@@ -107,6 +107,25 @@ __global__ __launch_bounds__(256) void k_plan_label(const uint8_t* __restrict__ 
     }
 }
 
+// Orders the LDS accesses of one wave: what lanes wrote before it is what any lane reads after it.
+__device__ __forceinline__ void wave_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// The packing order on integers: a larger ord_key comes first, equal keys go by ascending id.  Same
+// order as box_before: doubles map to their order-preserving 64-bit image (-0 = +0), NaN to 0 (last;
+// no finite key or -inf maps that low: -inf gives 0x000FFFFFFFFFFFFF).
+__device__ __forceinline__ unsigned long long ord_key(double k)
+{
+    if (k != k) return 0ull;
+    unsigned long long b = (unsigned long long)__double_as_longlong(k);
+    if (b == 0x8000000000000000ull) b = 0ull;
+    return (b & 0x8000000000000000ull) ? ~b : (b | 0x8000000000000000ull);
+}
+
 // a before b in the packing order: higher key (density, or area) first, NaN last, ties by ascending id.
 __device__ __forceinline__ bool box_before(double ka, uint32_t ia, double kb, uint32_t ib)
 {
@@ -147,52 +166,63 @@ __global__ __launch_bounds__(256) void k_plan_rank(const rh_rawbox* __restrict__
 // rotate: a rectangle that cannot take the box upright may take it turned (RotatePacking).
 // The loop over the boxes is serial by definition, so its cost is the latency of one step.  It
 // runs in ONE wave: the 64 lanes test 64 free rectangles at a time and a ballot gives the first
-// fit; LDS traffic of a single wave is executed in program order, so the list needs no barrier,
-// no atomics, and every lane tracks the list length and bin count in registers.
-__global__ __launch_bounds__(64) void k_plan_place(const rh_rawbox* __restrict__ sorted, uint32_t* pcount,
-                                                   int halo, int S, int max_bins, int free_cap, int rotate,
-                                                   uint32_t* __restrict__ box_pos)
+// fit.  The hardware executes the LDS traffic of a single wave in program order; wave_sync() after
+// every step in which lanes write what other lanes read next keeps the compiler from moving LDS
+// accesses across it.  Every lane tracks the list length and bin count in registers.
+// One wave.  sizes: box i's (wmb | hmb << 16) comes from size_of(i).  Returns through n_bins / overflow.
+template <typename SizeOf>
+__device__ __forceinline__ void place_boxes(uint32_t n, SizeOf size_of, uint32_t* fxy, uint32_t* fwh, uint32_t* fbin,
+                                            int halo, int S, int max_bins, int free_cap, int rotate,
+                                            uint32_t* __restrict__ box_pos, int& n_bins_out, bool& overflow_out)
 {
-    extern __shared__ uint32_t sm[];
-    uint32_t* fxy = sm; uint32_t* fwh = sm + free_cap; uint32_t* fbin = sm + 2 * free_cap;
-    __shared__ uint32_t s_size[256];
-    const int lane = threadIdx.x;
-    const uint32_t n = pcount[0];
+    const int lane = threadIdx.x & 63;
     const int minside = RH_MB + 2 * halo;
     int nfree = 0, nbins = 0;
-    uint32_t i = 0;
+    uint32_t i = 0, szv = 0, pos0 = 0, pos1 = 0;             // lane l keeps the position of box (i & ~63) + l
     bool overflow = false;
+    // Results leave in groups of 64: a global store per box would be waited for by the next box's
+    // loads (stores and loads share the wave's memory counter), half a microsecond each.
+    auto flush = [&](uint32_t upto) {                        // boxes [upto & ~63 ... upto) when upto is not a multiple of 64, else the last 64
+        const uint32_t g0 = (upto - 1u) & ~63u;
+        if (upto && g0 + lane < upto) { box_pos[2 * (g0 + lane)] = pos0; box_pos[2 * (g0 + lane) + 1] = pos1; }
+    };
     for (; i < n && !overflow; ++i) {
-        if ((i & 255u) == 0) {                                   // stage the next 256 box sizes
-            for (int t = lane; t < 256; t += 64)
-                if (i + t < n) s_size[t] = sorted[i + t].wmb | ((uint32_t)sorted[i + t].hmb << 16);
+        if ((i & 63u) == 0) {
+            flush(i);
+            szv = (i + lane < n) ? size_of(i + lane) : 0u;   // the next 64 box sizes, one per lane
         }
-        const uint32_t sz = s_size[i & 255u];
+        const uint32_t sz = (uint32_t)__builtin_amdgcn_readlane((int)szv, (int)(i & 63u));
         int bw = RH_MB * (int)(sz & 0xFFFF) + 2 * halo, bh = RH_MB * (int)(sz >> 16) + 2 * halo;
-        uint32_t at = NONE;
-        for (int base = 0; base < nfree; base += 64) {           // first rectangle, in list order, that fits
+        // first rectangle, in list order, that fits: every lane reads one entry whole, the winner's
+        // fields are then taken from its lane
+        uint32_t at = NONE, exy = 0, ewh = 0, ebin = 0;
+        for (int base = 0; base < nfree; base += 64) {
             const int j = base + lane;
-            bool fit = false;
-            if (j < nfree) {
-                const uint32_t wh = fwh[j];
-                const int w = (int)(wh & 0xFFFF), h = (int)(wh >> 16);
-                fit = (w >= bw && h >= bh) || (rotate && w >= bh && h >= bw);
-            }
+            uint32_t wh = 0, xy = 0, bn = 0;
+            if (j < nfree) { wh = fwh[j]; xy = fxy[j]; bn = fbin[j]; }
+            const int w = (int)(wh & 0xFFFF), h = (int)(wh >> 16);
+            const bool fit = j < nfree && ((w >= bw && h >= bh) || (rotate && w >= bh && h >= bw));
             const unsigned long long m = __ballot(fit);
-            if (m) { at = (uint32_t)(base + __ffsll((long long)m) - 1); break; }
+            if (m) {
+                const int l = __ffsll((long long)m) - 1;
+                at = (uint32_t)(base + l);
+                exy = (uint32_t)__builtin_amdgcn_readlane((int)xy, l); ewh = (uint32_t)__builtin_amdgcn_readlane((int)wh, l);
+                ebin = (uint32_t)__builtin_amdgcn_readlane((int)bn, l);
+                break;
+            }
         }
         int fx, fy, fw, fh, fb, cur_n;
         if (at == NONE) {
             if (nbins >= max_bins || nfree + 2 > free_cap) { overflow = true; break; }
             at = nfree; fx = 0; fy = 0; fw = S; fh = S; fb = nbins++; cur_n = nfree + 1;
         } else {
-            fx = fxy[at] & 0xFFFF; fy = fxy[at] >> 16; fw = fwh[at] & 0xFFFF; fh = fwh[at] >> 16; fb = fbin[at];
+            fx = exy & 0xFFFF; fy = exy >> 16; fw = ewh & 0xFFFF; fh = ewh >> 16; fb = ebin;
             cur_n = nfree;
             if (nfree + 1 > free_cap) { overflow = true; break; }
         }
         const bool turned = !(fw >= bw && fh >= bh);         // upright whenever that fits
         if (turned) { const int t = bw; bw = bh; bh = t; }   // occupied size
-        if (lane == 0) { box_pos[2 * i] = (uint32_t)fb | (turned ? 0x10000u : 0u); box_pos[2 * i + 1] = (uint32_t)fx | ((uint32_t)fy << 16); }
+        if (lane == (int)(i & 63u)) { pos0 = (uint32_t)fb | (turned ? 0x10000u : 0u); pos1 = (uint32_t)fx | ((uint32_t)fy << 16); }
         // remainder: the larger of (right strip, full height) and (bottom strip, full width),
         // plus what is left of the other
         const int ar = (fw - bw) * fh, ab = fw * (fh - bh);
@@ -212,35 +242,49 @@ __global__ __launch_bounds__(64) void k_plan_place(const rh_rawbox* __restrict__
         if (delta > 0) {
             for (int hi = cur_n; hi > first; hi -= 64) {         // from the top down: a chunk is read whole before it is written
                 const int j = hi - 1 - lane;
-                if (j >= first) { const uint32_t a = fxy[j], b = fwh[j], c = fbin[j]; fxy[j + 1] = a; fwh[j + 1] = b; fbin[j + 1] = c; }
+                uint32_t a = 0, b = 0, c = 0;
+                if (j >= first) { a = fxy[j]; b = fwh[j]; c = fbin[j]; }
+                wave_sync();
+                if (j >= first) { fxy[j + 1] = a; fwh[j + 1] = b; fbin[j + 1] = c; }
+                wave_sync();
             }
         } else if (delta < 0) {
             for (int lo = first; lo < cur_n; lo += 64) {
                 const int j = lo + lane;
-                if (j < cur_n) { const uint32_t a = fxy[j], b = fwh[j], c = fbin[j]; fxy[j - 1] = a; fwh[j - 1] = b; fbin[j - 1] = c; }
+                uint32_t a = 0, b = 0, c = 0;
+                if (j < cur_n) { a = fxy[j]; b = fwh[j]; c = fbin[j]; }
+                wave_sync();
+                if (j < cur_n) { fxy[j - 1] = a; fwh[j - 1] = b; fbin[j - 1] = c; }
+                wave_sync();
             }
         }
         if (lane < ni) { fxy[at + lane] = ixy[lane]; fwh[at + lane] = iwh[lane]; fbin[at + lane] = fb; }
+        wave_sync();
         nfree = cur_n + delta;
     }
+    flush(i);                                                // i = boxes placed
     // boxes that did not fit (only after an overflow)
     for (uint32_t j = i + lane; j < n; j += 64) { box_pos[2 * j] = RH_NO_BIN; box_pos[2 * j + 1] = 0; }
-    if (lane == 0) { pcount[1] = nbins; pcount[2] = overflow ? 1u : 0u; }
+    n_bins_out = nbins; overflow_out = overflow;
 }
 
-__global__ __launch_bounds__(256) void k_plan_emit(const rh_rawbox* __restrict__ sorted,
-                                                   const uint32_t* __restrict__ box_pos,
-                                                   const uint32_t* __restrict__ pcount,
-                                                   const uint32_t* __restrict__ list,
-                                                   const uint32_t* __restrict__ n_sel_p,
-                                                   const uint32_t* __restrict__ owner_id,
-                                                   const uint32_t* __restrict__ rank_of_id, int mbw, int per,
-                                                   int halo, rh_box* __restrict__ boxes,
-                                                   rh_mbplace* __restrict__ places, uint32_t* __restrict__ counts)
+__global__ __launch_bounds__(64) void k_plan_place(const rh_rawbox* __restrict__ sorted, uint32_t* pcount,
+                                                   int halo, int S, int max_bins, int free_cap, int rotate,
+                                                   uint32_t* __restrict__ box_pos)
 {
-    const uint32_t i = blockIdx.x * 256u + threadIdx.x;
-    const uint32_t n = pcount[0], n_sel = *n_sel_p;
-    if (i == 0) { counts[0] = n; counts[1] = pcount[1]; counts[2] = pcount[2]; counts[3] = n_sel; }
+    extern __shared__ uint32_t sm[];
+    int nbins; bool overflow;
+    place_boxes(pcount[0], [&](uint32_t i) { return (uint32_t)sorted[i].wmb | ((uint32_t)sorted[i].hmb << 16); },
+                sm, sm + free_cap, sm + 2 * free_cap, halo, S, max_bins, free_cap, rotate, box_pos, nbins, overflow);
+    if (threadIdx.x == 0) { pcount[1] = nbins; pcount[2] = overflow ? 1u : 0u; }
+}
+
+// Placement rows of box i and of selected macroblock i (Alg. 1's output).
+__device__ __forceinline__ void emit_rows(uint32_t i, uint32_t n, uint32_t n_sel, const rh_rawbox* __restrict__ sorted,
+                                          const uint32_t* __restrict__ box_pos, const uint32_t* __restrict__ list,
+                                          const uint32_t* __restrict__ owner_id, const uint32_t* __restrict__ rank_of_id,
+                                          int mbw, int per, int halo, rh_box* __restrict__ boxes, rh_mbplace* __restrict__ places)
+{
     if (i < n) {
         const rh_rawbox b = sorted[i];
         rh_box o;
@@ -267,13 +311,216 @@ __global__ __launch_bounds__(256) void k_plan_emit(const rh_rawbox* __restrict__
     }
 }
 
+__global__ __launch_bounds__(256) void k_plan_emit(const rh_rawbox* __restrict__ sorted,
+                                                   const uint32_t* __restrict__ box_pos,
+                                                   const uint32_t* __restrict__ pcount,
+                                                   const uint32_t* __restrict__ list,
+                                                   const uint32_t* __restrict__ n_sel_p,
+                                                   const uint32_t* __restrict__ owner_id,
+                                                   const uint32_t* __restrict__ rank_of_id, int mbw, int per,
+                                                   int halo, rh_box* __restrict__ boxes,
+                                                   rh_mbplace* __restrict__ places, uint32_t* __restrict__ counts)
+{
+    const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+    const uint32_t n = pcount[0], n_sel = *n_sel_p;
+    if (i == 0) { counts[0] = n; counts[1] = pcount[1]; counts[2] = pcount[2]; counts[3] = n_sel; }
+    emit_rows(i, n, n_sel, sorted, box_pos, list, owner_id, rank_of_id, mbw, per, halo, boxes, places);
+}
+
+// ------------------------------------------------------------------------------------------------
+// The whole plan in ONE launch of one 1024-thread workgroup, for frames of at most 64 x 64
+// macroblocks (1024 x 1024 pixels; the paper's streams are 640 x 360).  A plan is a few hundred
+// boxes: five dependent launches cost more than the work itself.
+//   A  label + bound + partition: one wave per frame (16 frames at a time), no barriers.  Lane y
+//      holds row y of the frame's selection as a 64-bit mask.  A region grows from its first
+//      macroblock in raster order (= its smallest index, its label): rows exchange masks with the
+//      rows above and below, spread by one column (8-connectivity: the union of the three, 4: only
+//      the row's own), and fill whole horizontal runs with two carry-propagating additions, until
+//      nothing changes.  The region's bounding box is cut on the T x T grid; one lane per cell
+//      walks the cell's rows (masks fetched from the row lanes), tightens the bounds, adds the
+//      importance values in ascending index (fp32, from an LDS copy of the frame's map) and
+//      writes the box and its macroblocks' owner.
+//   B  rank by counting over all threads (keys in LDS for up to PF_KEYS boxes)
+//   C  first fit by wave 0 (place_boxes), the free list in LDS
+//   D  placement rows by all threads
+#define PF_THREADS 1024
+#define PF_WAVES (PF_THREADS / 64)
+#define PF_KEYS 2048
+#define PF_MAX_PER 2304                   // 16 waves x per x 4 B of importance <= 144 KB
+
+typedef unsigned long long u64;
+
+__device__ __forceinline__ u64 fill_runs(u64 n, u64 m)     // extend the bits of n (a subset of m) along the runs of ones of m
+{
+    const u64 up = ((m + n) ^ m) & m;                        // a carry runs from every seed to the end of its run
+    const u64 rm = __brevll(m), rn = __brevll(n);
+    const u64 dn = __brevll(((rm + rn) ^ rm) & rm);
+    return n | up | dn;
+}
+
+struct plan_args {
+    const uint8_t* mask; const float* imp; const uint32_t* list; const uint32_t* n_sel;
+    int F, mbw, mbh, conn, T, sort_policy, halo, S, max_bins, free_cap, rotate;
+    uint32_t* owner_id; uint32_t* rank_of_id; rh_rawbox* raw; rh_rawbox* sorted; uint32_t* box_pos;
+    rh_box* boxes; rh_mbplace* places; uint32_t* counts;
+};
+
+__global__ __launch_bounds__(PF_THREADS) void k_plan_fused(plan_args a)
+{
+    extern __shared__ __attribute__((aligned(16))) uint32_t dyn[];
+    __shared__ uint32_t s_nraw, s_nbins, s_overflow;
+    __shared__ uint32_t s_sz[PF_KEYS];                       // sizes of the sorted boxes, for the first fit
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int mbw = a.mbw, mbh = a.mbh, per = mbw * mbh, T = a.T;
+    if (tid == 0) s_nraw = 0;
+    __syncthreads();
+
+    // ---------------- A: regions and boxes, one wave per frame ----------------
+    float* simp = (float*)dyn + (size_t)wave * per;
+    for (int f = wave; f < a.F; f += PF_WAVES) {
+        const size_t base = (size_t)f * per;
+        for (int i = lane; i < per; i += 64) simp[i] = a.imp[base + i];
+        u64 m = 0;
+        for (int y = 0; y < mbh; y += 8) {                   // eight rows' loads in flight at a time
+            uint8_t v8[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v8[u] = (lane < mbw && y + u < mbh) ? a.mask[base + (size_t)(y + u) * mbw + lane] : (uint8_t)0;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const u64 row = __ballot(v8[u] != 0);
+                if (lane == y + u) m = row;
+            }
+        }
+        wave_sync();                                         // simp is read by other lanes below
+        u64 rem = m;
+        for (;;) {
+            const u64 rows_left = __ballot(rem != 0);
+            if (!rows_left) break;
+            const int ys = __ffsll((long long)rows_left) - 1;
+            const u64 seed_row = __shfl(rem, ys);
+            u64 comp = lane == ys ? (seed_row & (~seed_row + 1)) : 0;           // lowest set bit: the region's label
+            for (;;) {                                       // RegionProps: grow until stable
+                u64 up = __shfl_up(comp, 1), dn = __shfl_down(comp, 1);
+                if (lane == 0) up = 0;
+                if (lane == 63) dn = 0;
+                u64 n;
+                if (a.conn == 8) { n = comp | up | dn; n |= (n << 1) | (n >> 1); }
+                else n = comp | up | dn | (comp << 1) | (comp >> 1);
+                n = fill_runs((n & m) | comp, m);
+                const bool changed = n != comp;
+                comp = n;
+                if (!__any(changed)) break;
+            }
+            rem &= ~comp;
+            // Bound
+            const u64 rows_in = __ballot(comp != 0);
+            const int y0 = __ffsll((long long)rows_in) - 1, y1 = 63 - __clzll((long long)rows_in);
+            u64 cols = comp;
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) cols |= __shfl_xor(cols, o);
+            const int x0 = __ffsll((long long)cols) - 1, x1 = 63 - __clzll((long long)cols);
+            // Partition: cells of the T x T grid anchored at (x0, y0), one lane per cell
+            const int ncx = (x1 - x0) / T + 1, ncy = (y1 - y0) / T + 1, cells = ncx * ncy;
+            for (int c0 = 0; c0 < cells; c0 += 64) {         // uniform over the wave
+                const int c = c0 + lane;
+                const bool active = c < cells;
+                const int cy = active ? c / ncx : 0, cx = active ? c - cy * ncx : 0;
+                const int ra = y0 + cy * T, rb = min(ra + T - 1, y1), ca = x0 + cx * T, cb = min(ca + T - 1, x1);
+                const u64 cmask = ((cb - ca + 1) >= 64 ? ~0ull : ((1ull << (cb - ca + 1)) - 1ull)) << ca;
+                int leader = -1, bx0 = 64, bx1 = -1, by0 = 64, by1 = -1;
+                float sum = 0.0f;
+                const int span = min(T, y1 - y0 + 1);       // rows a cell can have: uniform
+                for (int rr = 0; rr < span; ++rr) {
+                    const int r = ra + rr;
+                    const u64 rowbits = __shfl(comp, (active && r <= rb) ? r : 0);     // every lane takes part
+                    u64 bits = (active && r <= rb) ? (rowbits & cmask) : 0;
+                    if (bits) {
+                        if (leader < 0) { leader = r * mbw + (__ffsll((long long)bits) - 1); by0 = r; }
+                        by1 = r;
+                        bx0 = min(bx0, __ffsll((long long)bits) - 1); bx1 = max(bx1, 63 - __clzll((long long)bits));
+                        while (bits) {                       // ascending column = ascending flat index
+                            const int x = __ffsll((long long)bits) - 1;
+                            bits &= bits - 1;
+                            sum = __fadd_rn(sum, simp[r * mbw + x]);
+                            a.owner_id[base + r * mbw + x] = (uint32_t)(base + leader);
+                        }
+                    }
+                }
+                const bool has = leader >= 0;
+                const u64 hm = __ballot(has);
+                uint32_t slot0 = 0;
+                if (lane == 0 && hm) slot0 = atomicAdd(&s_nraw, (uint32_t)__popcll(hm));
+                slot0 = __shfl(slot0, 0);
+                if (has) {
+                    rh_rawbox b;
+                    b.frame = f; b.mbx0 = bx0; b.mby0 = by0; b.wmb = bx1 - bx0 + 1; b.hmb = by1 - by0 + 1;
+                    b.id = (uint32_t)(base + leader); b.sum = sum;
+                    const int area = (bx1 - bx0 + 1) * (by1 - by0 + 1);
+                    b.key = a.sort_policy == RH_SORT_AREA ? (double)area : (double)sum / (double)area;
+                    a.raw[slot0 + (uint32_t)__popcll(hm & ((1ull << lane) - 1ull))] = b;
+                }
+            }
+        }
+        wave_sync();                                         // before the next frame overwrites simp
+    }
+    __threadfence_block();
+    __syncthreads();
+    const uint32_t n = s_nraw, n_sel = *a.n_sel;
+
+    // ---------------- B: rank by counting ----------------
+    u64* s_key = (u64*)dyn;
+    uint32_t* s_id = (uint32_t*)(s_key + PF_KEYS);
+    const bool keys_in_lds = n <= PF_KEYS;
+    if (keys_in_lds)
+        for (uint32_t j = tid; j < n; j += PF_THREADS) { s_key[j] = ord_key(a.raw[j].key); s_id[j] = a.raw[j].id; }
+    __syncthreads();
+    for (uint32_t i = tid; i < n; i += PF_THREADS) {
+        const rh_rawbox me = a.raw[i];
+        uint32_t rank = 0;
+        if (keys_in_lds) {
+            const u64 mk = ord_key(me.key);
+            uint32_t j = 0;
+            for (; j + 8 <= n; j += 8) {                     // eight independent LDS reads in flight
+                u64 k8[8]; uint32_t d8[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) { k8[u] = s_key[j + u]; d8[u] = s_id[j + u]; }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) rank += (k8[u] > mk || (k8[u] == mk && d8[u] < me.id)) ? 1u : 0u;
+            }
+            for (; j < n; ++j) rank += (s_key[j] > mk || (s_key[j] == mk && s_id[j] < me.id)) ? 1u : 0u;
+        } else for (uint32_t j = 0; j < n; ++j) rank += box_before(a.raw[j].key, a.raw[j].id, me.key, me.id) ? 1u : 0u;
+        a.sorted[rank] = me; a.rank_of_id[me.id] = rank;
+        if (rank < PF_KEYS) s_sz[rank] = (uint32_t)me.wmb | ((uint32_t)me.hmb << 16);
+    }
+    __threadfence_block();
+    __syncthreads();                                         // keys are dead: the free list takes their place
+
+    // ---------------- C: first fit, wave 0 ----------------
+    if (wave == 0) {
+        int nbins; bool overflow;
+        place_boxes(n, [&](uint32_t i) { return i < PF_KEYS ? s_sz[i] : ((uint32_t)a.sorted[i].wmb | ((uint32_t)a.sorted[i].hmb << 16)); },
+                    dyn, dyn + a.free_cap, dyn + 2 * a.free_cap, a.halo, a.S, a.max_bins, a.free_cap, a.rotate, a.box_pos,
+                    nbins, overflow);
+        if (lane == 0) { s_nbins = (uint32_t)nbins; s_overflow = overflow ? 1u : 0u; }
+    }
+    __threadfence_block();
+    __syncthreads();
+
+    // ---------------- D: placement rows ----------------
+    if (tid == 0) { a.counts[0] = n; a.counts[1] = s_nbins; a.counts[2] = s_overflow; a.counts[3] = n_sel; }
+    const uint32_t top = n > n_sel ? n : n_sel;
+    for (uint32_t i = tid; i < top; i += PF_THREADS)
+        emit_rows(i, n, n_sel, a.sorted, a.box_pos, a.list, a.owner_id, a.rank_of_id, mbw, per, a.halo, a.boxes, a.places);
+}
+
 rh_status rh_plan_init(rh_ctx* ctx)
 {
-    // Both planning kernels may need more dynamic LDS than the default limit.  The attribute belongs
+    // The planning kernels may need more dynamic LDS than the default limit.  The attribute belongs
     // to the kernel, not to the context: it is raised to what the largest admissible context needs
-    // (rh_create bounds both sizes below 150 KB), so contexts of different sizes can coexist.
+    // (rh_create bounds the sizes below 150 KB), so contexts of different sizes can coexist.
     RH_HIP(ctx, hipFuncSetAttribute((const void*)k_plan_label, hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024));
     RH_HIP(ctx, hipFuncSetAttribute((const void*)k_plan_place, hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024));
+    RH_HIP(ctx, hipFuncSetAttribute((const void*)k_plan_fused, hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024));
     return RH_OK;
 }
 
@@ -283,6 +530,23 @@ rh_status rh_launch_plan(rh_ctx* ctx, int F, const float* imp, const uint8_t* ma
 {
     const int per = ctx->per, total = per * F;
     uint32_t* box_pos = ctx->pcount + 8;
+    if (ctx->mbw <= 64 && ctx->mbh <= 64 && per <= PF_MAX_PER) {
+        // the usual case: everything in one launch
+        size_t lds = (size_t)PF_WAVES * per * 4;
+        if (lds < (size_t)PF_KEYS * 12) lds = (size_t)PF_KEYS * 12;
+        if (lds < (size_t)ctx->free_cap * 12) lds = (size_t)ctx->free_cap * 12;
+        plan_args a;
+        a.mask = mask; a.imp = imp; a.list = list; a.n_sel = n_sel;
+        a.F = F; a.mbw = ctx->mbw; a.mbh = ctx->mbh; a.conn = ctx->cfg.connectivity; a.T = ctx->T;
+        a.sort_policy = ctx->cfg.sort_policy; a.halo = ctx->cfg.halo; a.S = ctx->cfg.bin_size; a.max_bins = ctx->cfg.max_bins;
+        a.free_cap = ctx->free_cap; a.rotate = ctx->cfg.rotate;
+        a.owner_id = ctx->owner_id; a.rank_of_id = ctx->rank_of_id; a.raw = ctx->raw; a.sorted = ctx->sorted; a.box_pos = box_pos;
+        a.boxes = boxes; a.places = places; a.counts = counts;
+        rh_prof_scope ps(ctx, RH_PROF_PLAN, 1);
+        hipLaunchKernelGGL(k_plan_fused, dim3(1), dim3(PF_THREADS), lds, ctx->stream, a);
+        RH_HIP(ctx, hipGetLastError());
+        return RH_OK;
+    }
     rh_prof_scope ps(ctx, RH_PROF_PLAN, 5);
     hipLaunchKernelGGL(k_plan_zero, dim3(1), dim3(64), 0, ctx->stream, ctx->pcount);
     const int imp_in_lds = (size_t)per * 20 <= 150 * 1024;

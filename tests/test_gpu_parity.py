@@ -117,6 +117,20 @@ def test_tie_stress_and_connectivity(levels):
         rh.close()
 
 
+@pytest.mark.parametrize("w,h,kind,conn,T,rotate", [(1056, 48, "uniform", 8, 0, False), (1072, 80, "clustered", 4, 2, True),
+                                                    (64, 1056, "uniform", 8, 1, False), (1040, 1040, "clustered", 8, 0, False)])
+def test_plan_of_frames_wider_than_64_macroblocks(w, h, kind, conn, T, rotate):
+    """Frames of more than 64 macroblocks a side are planned by the general multi-launch kernels
+    (the one-launch kernel keeps a frame's rows in 64-bit masks, one row per lane)."""
+    cfg = wl.replace(wl.config(1), n_frames=2, width=w, height=h, importance=kind, frac=0.3, halo=4, bin_size=96)
+    frames, imp = wl.make_frames(cfg), wl.make_importance(cfg)
+    net = wl.Net("plain", 4, 2, 2)
+    rh = make_rh(wl.replace(cfg, net=net), wl.make_weights(net, 0, "fp32"), precision="fp32", connectivity=conn,
+                 max_box_mbs=T, rotate=rotate)
+    check_select_and_plan(rh, cfg, frames, imp, wl.make_segments(cfg), conn=conn, T=T or None, rotate=rotate)
+    rh.close()
+
+
 def test_select_specials_threshold_and_edges():
     cfg = wl.replace(wl.config(1), n_frames=3)
     imp = wl.make_importance(cfg)
