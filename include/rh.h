@@ -204,7 +204,8 @@ rh_status rh_enhance_exact(rh_ctx* ctx, const uint8_t* in, int32_t N, const rh_b
  * (frame sides that are not multiples of 16) only the part inside the frame is pasted and sel
  * reports 0 for the rest.  A place is honoured when the in-frame part of its block lies inside
  * the enhanced image (whole MBs: px + 16 <= iw, py + 16 <= ih); otherwise the MB stays bilinear.
- * places/n_places: dev, from rh_pack (n_places = &counts[3]) or rh_identity_places.
+ * places/n_places: dev, from rh_pack (n_places = &counts[3]) or rh_identity_places; rows in ascending
+ * mb_id (as both write them): the kernel finds a macroblock's row by searching.
  * sel (dev, may be NULL): f32 [n_places][16s][16s][3], the unquantised e of every placed MB.
  */
 rh_status rh_unpack(rh_ctx* ctx, const float* enhanced, int32_t n_img, int32_t ih, int32_t iw,
