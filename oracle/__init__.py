@@ -141,9 +141,20 @@ def border_keep(frame_h: int, frame_w: int, boxes: np.ndarray, halo: int, bin_si
     return keep
 
 
-def sr_forward(net, blob: np.ndarray, imgs: np.ndarray, keep: np.ndarray | None = None) -> np.ndarray:
+def cell_keep(boxes: np.ndarray, halo: int, bin_size: int, n_bins: int, cell_h: int = 16, cell_w: int = 32) -> np.ndarray:
+    """Box-masked mode: u8 [n_bins,S,S], 1 in every cell_h x cell_w cell that a placed box touches."""
+    boxes = np.ascontiguousarray(boxes, dtype=np.int32).reshape(-1, 10)
+    keep = np.zeros((n_bins, bin_size, bin_size), dtype=np.uint8)
+    lib().orc_cell_keep(_p(boxes), len(boxes), halo, bin_size, n_bins, cell_h, cell_w, _p(keep))
+    return keep
+
+
+def sr_forward(net, blob: np.ndarray, imgs: np.ndarray, keep: np.ndarray | None = None,
+               body_only: bool = False) -> np.ndarray:
     """imgs u8 [N,H,W,3] -> raw network output fp64 [N,sH,sW,3].  keep (u8 [N,H,W], optional):
-    exact-border mode, every layer's output is zeroed where keep == 0."""
+    exact-border mode, every layer's output is zeroed where keep == 0; with body_only (box-masked
+    mode) only the first conv's and the body convs' outputs are, the layers after the body run
+    unmasked."""
     imgs = np.ascontiguousarray(imgs, dtype=np.uint8)
     blob = np.ascontiguousarray(blob, dtype=np.float32)
     N, H, W, _ = imgs.shape
@@ -152,6 +163,11 @@ def sr_forward(net, blob: np.ndarray, imgs: np.ndarray, keep: np.ndarray | None 
     if keep is not None:
         keep = np.ascontiguousarray(keep, dtype=np.uint8)
         assert keep.shape == (N, H, W)
+    if body_only:
+        assert keep is not None
+        lib().orc_sr_forward_masked(TOPOLOGY[net.topology], net.channels, net.n_blocks, s, _p(blob),
+                                    _p(imgs), N, H, W, _p(keep), _p(out))
+        return out
     lib().orc_sr_forward(TOPOLOGY[net.topology], net.channels, net.n_blocks, s, _p(blob),
                          _p(imgs), N, H, W, _p(keep) if keep is not None else None, _p(out))
     return out
@@ -198,12 +214,16 @@ class PathResult:
 
 def run_path(frames, imp, segs, net, blob, halo, bin_size, conn=8, T=None,
              mode="topk", thr=None, max_bins=1 << 15, sort_policy="density", rotate=False,
-             exact_border=False) -> PathResult:
+             exact_border=False, box_masked=False) -> PathResult:
     """The whole hot path: select -> plan -> gather -> SR -> paste."""
     mask, lst = select(imp, segs, mode, thr)
     pl = plan(mask, imp, halo, bin_size, conn, T, max_bins, sort_policy, rotate)
     bins = gather(frames, pl.boxes, halo, bin_size, pl.n_bins)
     keep = border_keep(frames.shape[1], frames.shape[2], pl.boxes, halo, bin_size, pl.n_bins) if exact_border else None
-    net_out = sr_forward(net, blob, bins, keep)
+    if box_masked:
+        assert not exact_border
+        net_out = sr_forward(net, blob, bins, cell_keep(pl.boxes, halo, bin_size, pl.n_bins), body_only=True)
+    else:
+        net_out = sr_forward(net, blob, bins, keep)
     hr, sel = unpack(frames, net.scale, net_out, pl.places, place_rot=pl.place_rot)
     return PathResult(mask, lst, pl, bins, net_out, hr, sel)

@@ -419,7 +419,7 @@ static void apply_keep(double* buf, int h, int w, int C, const uint8_t* keep, in
 /* One image through the network.  topology: 0 plain, 1 res, 2 edsr.
  * in: u8 [H][W][3]; out: fp64 [sH][sW][3] (the network's raw output). */
 static void sr_one(int topology, int C, int nblk, int s, const float* blob,
-                   const uint8_t* in, int H, int W, const uint8_t* keep, double* out)
+                   const uint8_t* in, int H, int W, const uint8_t* keep, int keep_tail, double* out)
 {
     size_t px = (size_t)H * W;
     const float* p = blob; olayer L;
@@ -466,7 +466,7 @@ static void sr_one(int topology, int C, int nblk, int s, const float* blob,
                 double* z = dalloc((size_t)h * w * Co);
                 orc_pixel_shuffle(y, h, w, Co, r, z); free(y); free(cur);
                 cur = z; h *= r; w *= r;
-                apply_keep(cur, h, w, C, keep, h / H);
+                if (keep_tail) apply_keep(cur, h, w, C, keep, h / H);
             }
             take_layer(&p, C, 3, &L); orc_conv3x3(cur, h, w, C, L.w, L.b, 3, 0, out);
             free(cur);
@@ -484,7 +484,44 @@ void orc_sr_forward(int topology, int C, int nblk, int s, const float* blob,
     size_t ipx = (size_t)H * W * 3, opx = ipx * s * s;
 #pragma omp parallel for schedule(dynamic, 1) if (N >= omp_get_max_threads())
     for (int n = 0; n < N; ++n)
-        sr_one(topology, C, nblk, s, blob, in + n * ipx, H, W, keep ? keep + (size_t)n * H * W : NULL, out + n * opx);
+        sr_one(topology, C, nblk, s, blob, in + n * ipx, H, W, keep ? keep + (size_t)n * H * W : NULL, 1, out + n * opx);
+}
+
+/* Box-masked mode (Sec. 3.3.2: packed bins are only partly occupied; the area no box covers need
+ * not be enhanced).  keep u8 [N][H][W] as written by orc_cell_keep.  The output of the first conv
+ * and of every conv of the body (after its residual / long-skip addition) is set to zero where
+ * keep == 0; the layers after the body - upsampling convs, pixel shuffles, last conv - run on
+ * that tensor unmasked. */
+void orc_sr_forward_masked(int topology, int C, int nblk, int s, const float* blob,
+                           const uint8_t* in, int N, int H, int W, const uint8_t* keep, double* out)
+{
+    size_t ipx = (size_t)H * W * 3, opx = ipx * s * s;
+#pragma omp parallel for schedule(dynamic, 1) if (N >= omp_get_max_threads())
+    for (int n = 0; n < N; ++n)
+        sr_one(topology, C, nblk, s, blob, in + n * ipx, H, W, keep + (size_t)n * H * W, 0, out + n * opx);
+}
+
+/* Box-masked mode: the bin is cut into cells of cell_h x cell_w pixels from its origin (cells at
+ * the right / bottom edge may be cut).  keep[b][y][x] = 1 where the cell of pixel (x, y) shares
+ * at least one pixel with a box placed in bin b (the box with its halo; a turned box occupies
+ * its exchanged extent), 0 elsewhere. */
+void orc_cell_keep(const int32_t* boxes, int n_boxes, int halo, int bin_size, int n_bins,
+                   int cell_h, int cell_w, uint8_t* keep)
+{
+    size_t S = (size_t)bin_size;
+    memset(keep, 0, (size_t)n_bins * S * S);
+    for (int i = 0; i < n_boxes; ++i) {
+        const int32_t* b = boxes + 10 * i;
+        int bin = b[6];
+        if (bin < 0 || bin >= n_bins) continue;
+        int bw = MBS * b[3] + 2 * halo, bh = MBS * b[4] + 2 * halo;
+        int fw = b[5] ? bh : bw, fh = b[5] ? bw : bh;            /* extent inside the bin */
+        int cx0 = b[7] / cell_w, cx1 = (b[7] + fw - 1) / cell_w;
+        int cy0 = b[8] / cell_h, cy1 = (b[8] + fh - 1) / cell_h;
+        for (int y = cy0 * cell_h; y < (cy1 + 1) * cell_h && y < (int)S; ++y)
+            for (int x = cx0 * cell_w; x < (cx1 + 1) * cell_w && x < (int)S; ++x)
+                keep[((size_t)bin * S + y) * S + x] = 1;
+    }
 }
 
 /* Exact-border mode: keep[b][y][x] = 0 where bin pixel (x, y) belongs to a placed box and its
