@@ -37,6 +37,21 @@ CONV_KERNEL = {64: "k_conv_mfma_duo<SKIP,RELU,10> (64-channel bf16-output convs 
                32: "k_conv_mfma<32,1,16,false,SKIP,RELU> (bf16-output 32-channel convs)"}
 
 
+def live_cell_fraction(boxes, halo, S, n_bins, cell_h=16, cell_w=32):
+    """Share of the bins' cell_h x cell_w cells that a placed box (with its halo) touches: what the
+    body convs of the box-masked enhance mode compute."""
+    cx, cy = -(-S // cell_w), -(-S // cell_h)
+    live = np.zeros((max(n_bins, 1), cy, cx), dtype=bool)
+    for b in boxes:
+        if int(b["bin"]) >= n_bins:
+            continue
+        bw, bh = 16 * int(b["wmb"]) + 2 * halo, 16 * int(b["hmb"]) + 2 * halo
+        fw, fh = (bh, bw) if int(b["rot"]) else (bw, bh)
+        x0, y0 = int(b["bx"]), int(b["by"])
+        live[int(b["bin"]), y0 // cell_h:(y0 + fh - 1) // cell_h + 1, x0 // cell_w:(x0 + fw - 1) // cell_w + 1] = True
+    return float(live.mean()) if n_bins else 1.0
+
+
 def net_flops(net, composed_tail):
     """Per packed low-resolution pixel: flop and launches of the profiled conv class (bf16 path: the
     C-input / bf16-output convs; 18*cin*cout per output pixel at the layer's resolution), the
@@ -84,6 +99,8 @@ class Runner:
         self.seg_rows = [tuple(r) for r in self.segs.tolist()]
         self.po = None
         self.exact = args.exact_border
+        self.masked = bool(getattr(args, "box_masked", False)) and cfg.precision == "bf16" and cfg.net.channels == 64
+        self.live_frac = 1.0      # box-masked mode: fraction of the 16 x 32 cells that the body convs compute
         self.sync_counts = args.sync_counts
         self.net_out = self.hr = None
         self.cap = 0
@@ -107,6 +124,8 @@ class Runner:
         self.po = po = rh.pack(self.d_frames, self.d_imp, mask, lst, n_sel, out=self.po)
         if self.exact:
             rh.enhance_exact(po.bins, po.boxes, po.counts, n=self.cap, n_valid=po.counts[1:2], out=self.net_out)
+        elif self.masked:
+            rh.enhance_masked(po.bins, po.boxes, po.counts, n=self.cap, n_valid=po.counts[1:2], out=self.net_out)
         elif self.sync_counts:
             rh.enhance(po.bins, n=rh.read_counts(po.counts)[1], out=self.net_out)
         else:
@@ -117,6 +136,8 @@ class Runner:
         """-> (ms per step, per-class kernel (ms, launches) per step, counts)."""
         torch, rh = self.torch, self.rh
         counts = self.plan_only()
+        if self.masked:
+            self.live_frac = live_cell_fraction(rh.boxes_np(self.po.boxes, counts[0]), self.cfg.halo, self.cfg.bin_size, counts[1])
         if self.net_out is None:
             # all outputs are allocated once, outside the timed region; the enhance call is sized by
             # the output capacity (the bins this batch needs plus slack) and told the device-side count
@@ -167,7 +188,7 @@ class Runner:
             cls_fl, cls_n = network_fl, len(wl.net_layers(cfg.net))      # fp32 path: all layers are one class
         conv_ms, conv_n = prof["conv"]
         launch_s = conv_ms / max(conv_n, 1) * 1e-3
-        flop_per_launch = cls_fl * px_lr / max(cls_n, 1)
+        flop_per_launch = cls_fl * px_lr * self.live_frac / max(cls_n, 1)      # box-masked mode: live cells only
         achieved = flop_per_launch / launch_s if launch_s > 0 else 0.0
         peak = MFMA_BF16_PEAK if cfg.precision == "bf16" else FP32_VALU_PEAK
         enh_s = sum(prof[k][0] for k in ("head", "conv", "conv_last")) * 1e-3
@@ -196,6 +217,10 @@ def main():
     ap.add_argument("--fraction", type=float, default=None, help="override the selected fraction of the configuration")
     ap.add_argument("--importance", choices=["clustered", "uniform"], default=None,
                     help="override the importance recipe (uniform = iid, isolated macroblocks: the packer's worst case)")
+    ap.add_argument("--box-masked", action="store_true",
+                    help="enhance with rh_enhance_masked (the body convs skip the 16 x 32 cells that no box touches; "
+                         "a different function near those cells)")
+    ap.add_argument("--no-box-masked-leg", action="store_true", help="skip the box-masked leg of the default run")
     ap.add_argument("--exact-border", action="store_true",
                     help="enhance with rh_enhance_exact (per-layer zeroing of the out-of-frame part of the boxes)")
     ap.add_argument("--per-layer-tail", action="store_true",
@@ -237,6 +262,8 @@ def main():
         cfg = wl.replace(cfg, name=f"{cfg.name}_exact_border")
     if args.per_layer_tail:
         cfg = wl.replace(cfg, name=f"{cfg.name}_per_layer_tail")
+    if args.box_masked:
+        cfg = wl.replace(cfg, name=f"{cfg.name}_box_masked")
     F, s, S = cfg.n_frames, cfg.net.scale, cfg.bin_size
 
     # A plain device copy of known size, outside every timed region: what rocprofv3's FETCH_SIZE /
@@ -393,6 +420,22 @@ def main():
     other_ms = sum(prof[k][0] for k in ("select", "plan", "gather", "unpack"))
     run.close()
     del run, rh, po
+
+    if not args.box_masked and not args.no_box_masked_leg and not args.exact_border and cfg.precision == "bf16" and cfg.net.channels == 64:
+        # The same batch with rh_enhance_masked: the body convs compute only the 16 x 32 cells that a box
+        # touches (the other cells hold zeros).  Not the headline: its output differs from rh_enhance's
+        # within the receptive field of the skipped cells.
+        args.box_masked = True
+        rm = Runner(cfg, args, max_box_mbs=args.max_box_mbs, per_layer_tail=args.per_layer_tail)
+        args.box_masked = False
+        ms_m, prof_m, counts_m = rm.timed(max(3, args.steps // 2), 2)
+        sm_m = rm.summary(ms_m, prof_m, counts_m)
+        result["box_masked"] = {"ms_per_step": ms_m, "macroblocks_per_s": sm_m["macroblocks_per_s"],
+                                "speedup_over_plain": ms_step / ms_m, "live_cell_fraction": rm.live_frac,
+                                "kernel_ms_per_step": sm_m["kernel_ms_per_step"],
+                                "conv_class_frac": sm_m["conv_class"]["frac_of_peak"]}
+        rm.close()
+        del rm
 
     if not args.no_other_configs:
         # The other benchmark configurations, GPU legs only (fewer steps): 1, 2 and 5 as listed, and

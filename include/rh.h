@@ -194,6 +194,25 @@ rh_status rh_enhance_exact(rh_ctx* ctx, const uint8_t* in, int32_t N, const rh_b
                            const uint32_t* counts, float* out, const uint32_t* n_valid);
 
 /*
+ * Box-masked variant of rh_enhance for packed bins (in: dev u8 [N][S][S][3], S = bin_size), for
+ * RH_BF16 networks with 64 channels.  A packed bin is only partly occupied (Sec. 3.3.2, occupy
+ * ratio), and the area no box covers is never pasted.  The bin is cut into cells of RH_CELL_H x
+ * RH_CELL_W pixels from its origin; a cell is live when a placed box (with its halo; a turned box
+ * with its exchanged extent) shares a pixel with it.  The output of the first conv and of every
+ * conv of the body (after its residual / long-skip addition) is zero outside the live cells, and
+ * the body's convs do not compute the other cells at all; the layers after the body (upsampling
+ * convs, pixel shuffles, last conv) run on that tensor everywhere, so every output pixel is
+ * written.  The result differs from rh_enhance's within the network's receptive field of a cell
+ * that is not live (there the plain mode sees the activations of an empty area instead of zeros).
+ * boxes / counts: dev, as written by rh_pack for these bins; N <= max_bins.  Costs three small
+ * extra launches.  RH_E_UNIMPLEMENTED for other networks.
+ */
+#define RH_CELL_H 16
+#define RH_CELL_W 32
+rh_status rh_enhance_masked(rh_ctx* ctx, const uint8_t* in, int32_t N, const rh_box* boxes,
+                            const uint32_t* counts, float* out, const uint32_t* n_valid);
+
+/*
  * Paste (Sec. 3.3.3; problem statement of Sec. 3.2.1: SR on selected MBs, bilinear IN(.)
  * elsewhere).  frames_hr u8 [F][s*H][s*W][3] = bilinear interpolation of frames_lr (integer
  * factor s, half-pixel centres, edge clamp, exact integer arithmetic, round half up); every

@@ -90,6 +90,7 @@ def load_library():
     L.rh_pack.argtypes = [vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp]
     L.rh_enhance.argtypes = [vp, vp, i32, i32, i32, vp, vp]
     L.rh_enhance_exact.argtypes = [vp, vp, i32, vp, vp, vp, vp]
+    L.rh_enhance_masked.argtypes = [vp, vp, i32, vp, vp, vp, vp]
     L.rh_unpack.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, i32, vp, vp]
     L.rh_identity_places.argtypes = [vp, i32, vp, vp]
     L.rh_read_counts.argtypes = [vp, vp, C.POINTER(C.c_uint32 * 4)]
@@ -232,6 +233,21 @@ class RH:
         if out is None:
             out = torch.empty((N, H * s, W * s, 3), dtype=torch.float32, device=self.device)
         self._check(self.lib.rh_enhance_exact(self.h, _ptr(bins), N, _ptr(boxes), _ptr(counts), _ptr(out), _ptr(n_valid)))
+        return out
+
+    def enhance_masked(self, bins: torch.Tensor, boxes: torch.Tensor, counts: torch.Tensor, n: int | None = None,
+                       n_valid: torch.Tensor | None = None, out: torch.Tensor | None = None) -> torch.Tensor:
+        """Box-masked variant of enhance for packed bins (boxes, counts as returned by pack): the body
+        convs skip the 16 x 32 cells that no box touches."""
+        assert bins.is_cuda and bins.dtype == torch.uint8 and bins.is_contiguous()
+        N, H, W, _ = bins.shape
+        assert H == W == self.cfg.bin_size
+        if n is not None:
+            N = n
+        s = self.scale
+        if out is None:
+            out = torch.empty((N, H * s, W * s, 3), dtype=torch.float32, device=self.device)
+        self._check(self.lib.rh_enhance_masked(self.h, _ptr(bins), N, _ptr(boxes), _ptr(counts), _ptr(out), _ptr(n_valid)))
         return out
 
     def unpack(self, enhanced: torch.Tensor, places, n_places, frames_lr: torch.Tensor, want_sel=False,

@@ -17,7 +17,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "librh.so")
 STAMP = LIB + ".sources"      # digest of the sources the library was built from
 SOURCES = ["rh_api.hip", "select.hip", "plan.hip", "pack.hip", "unpack.hip", "conv_fp32.hip", "conv_mfma.hip",
-           "conv_mfma_duo.hip", "conv_tail.hip", "conv_head.hip", "conv_fold.hip", "temporal.hip", "noalloc.hip"]
+           "conv_mfma_duo.hip", "conv_tail.hip", "conv_head.hip", "conv_fold.hip", "conv_mask.hip", "temporal.hip", "noalloc.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-ffp-contract=off"]
 

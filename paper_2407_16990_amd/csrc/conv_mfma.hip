@@ -450,6 +450,9 @@ static rh_status conv(rh_ctx* ctx, const rh_layer& L, const __bf16* in, void* ou
     a.out = out; a.skip = skip; a.n_valid = n_valid; a.N = N; a.H = H; a.W = W;
     a.relu = relu; a.ps = L.ps; a.n_chunks = last ? 1 : L.ps * L.ps; a.cout_real = L.cout; a.s_final = s_final;
     a.rev = (ctx->conv_parity ^= 1);       // alternate the direction from one conv to the next
+    // box-masked mode: the body's convs (same resolution in and out) walk the live cells only
+    const bool listed = ctx->mk_boxes && !last && L.ps == 1 && L.cin == 64;
+    a.tile_list = listed ? ctx->cell_live : nullptr; a.n_list = listed ? ctx->cell_cnt : nullptr;
     const int grid = ctx->n_cu;            // persistent kernels: one workgroup per compute unit (256 on MI355X)
     const int MT = last ? L.cout_pad / 32 : L.cin / 32;
     hipError_t e;
@@ -503,6 +506,8 @@ rh_status rh_launch_enhance_bf16(rh_ctx* ctx, const uint8_t* in, int N, int H, i
         rh_prof_scope ps(ctx, RH_PROF_HEAD);
         RH_HIP(ctx, rh_launch_head_mfma(ctx->stream, C, in, (const uint4*)((const uint8_t*)ctx->wpack + l0.wp_off),
                                         ctx->bpack + l0.bp_off, h, N, H, W, head_relu, n_valid));
+        // box-masked mode: from here to the end of the body the three tensors are zero outside the live cells
+        if (ctx->mk_boxes) { st = rh_launch_cell_lists(ctx, N, n_valid, h, a, t); if (st != RH_OK) return st; }
     }
     // exact-border mode (a no-op otherwise): clear the out-of-frame part of the boxes in a layer's output
 #define ZERO(buf, res) do { st = rh_zero_outside(ctx, (void*)(buf), C * 2, (res), N, n_valid); if (st != RH_OK) return st; } while (0)

@@ -38,7 +38,11 @@ __device__ __forceinline__ void for_each_step2(F& f)
 __device__ __forceinline__ void phase_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 __device__ __forceinline__ void idle_phase() { phase_barrier(); phase_barrier(); }
 
-template <bool SKIP, bool RELU, int MID>
+// LIST: the tiles to compute come from a.tile_list (box-masked mode) instead of being all tiles of
+// all images.  The entry of the next tile is requested with a vector load at the start of the
+// compute phase and read at the start of the drain phase, a whole phase later: a scalar load would
+// share its counter with the LDS fragment reads and turn their partial waits into full ones.
+template <bool SKIP, bool RELU, int MID, bool LIST>
 __global__ __launch_bounds__(512) void k_conv_mfma_duo(conv_args a)
 {
     constexpr int CIN = 64, MT = 2, KS = 4, NCH = 8, PIXB = 128, TH = 8, PH = TH + 2, RW = 2, NR = RW + 2;
@@ -67,7 +71,7 @@ __global__ __launch_bounds__(512) void k_conv_mfma_duo(conv_args a)
     const int n_img = a.n_valid ? min((int)*a.n_valid, a.N) : a.N;
     const int tiles_x = (a.W + 31) / 32, tiles_y = (a.H + 15) / 16;
     const int tiles_img = tiles_x * tiles_y;
-    const int n_tiles = n_img * tiles_img;
+    const int n_tiles = LIST ? (int)*a.n_list : n_img * tiles_img;
     // Tile order.  Workgroups go to the 8 XCDs round-robin; XCD x takes a contiguous run of tile
     // lanes so that neighbouring tiles (shared halo pixels) meet in one L2.
     // Layers with several output chunks (the upsampling convs): when the grid allows it the chunks
@@ -97,15 +101,24 @@ __global__ __launch_bounds__(512) void k_conv_mfma_duo(conv_args a)
     const int row_pitch = a.W * PIXB;
 
     // origin of team's half of tile number `tile` (rows y0..y0+7), image index n
-    auto tile_origin = [&](int tile, int& n, int& y0, int& x0) __attribute__((always_inline)) {
-        // Consecutive layers walk the tensor in opposite directions: what a layer touched last (the
-        // end of its input and output) is what the next layer touches first, while it is still in
-        // the memory-side cache.  Walking every layer front to back through buffers that together
-        // exceed that cache evicts each line just before it is needed again.
-        if (a.rev && tile < n_tiles) tile = n_tiles - 1 - tile;
+    auto decode = [&](int tile, int& n, int& y0, int& x0) __attribute__((always_inline)) {
         n = tile / tiles_img;
         const int tr = tile - n * tiles_img, ty = tr / tiles_x, tx = tr - ty * tiles_x;
         y0 = ty * 16 + team * TH; x0 = tx * 32;
+    };
+    // Consecutive layers walk the tensor in opposite directions: what a layer touched last (the
+    // end of its input and output) is what the next layer touches first, while it is still in
+    // the memory-side cache.  Walking every layer front to back through buffers that together
+    // exceed that cache evicts each line just before it is needed again.
+    __amdgpu_buffer_rsrc_t rlist = __builtin_amdgcn_make_buffer_rsrc((void*)a.tile_list, 0, LIST ? (uint32_t)n_tiles * 4u : 0u, RSRC_FLAGS);
+    auto list_load = [&](int idx) __attribute__((always_inline)) {       // entry of position idx (0 past the end)
+        const int pos = a.rev ? n_tiles - 1 - idx : idx;
+        return __builtin_amdgcn_raw_buffer_load_b32(rlist, idx < n_tiles ? (uint32_t)pos * 4u : OOB_OFF, 0, 0);
+    };
+    auto tile_origin = [&](int tile, int& n, int& y0, int& x0) __attribute__((always_inline)) {
+        if constexpr (LIST) tile = __builtin_amdgcn_readfirstlane(list_load(tile));
+        else if (a.rev && tile < n_tiles) tile = n_tiles - 1 - tile;
+        decode(tile, n, y0, x0);
     };
     uint4 pre[NPRE];
     auto load_piece = [&](int j, __amdgpu_buffer_rsrc_t rin, int y0, int x0) __attribute__((always_inline)) {
@@ -139,6 +152,7 @@ __global__ __launch_bounds__(512) void k_conv_mfma_duo(conv_args a)
                                                  tile < n_tiles ? in_img_bytes : 0u, RSRC_FLAGS);
     };
 
+    int cn = 0, cy0 = 0, cx0 = 0;                          // LIST: origin of the tile about to be computed
     for (int chunk = chunk_begin; chunk < chunk_end; ++chunk) {
         __syncthreads();                                   // all 8 waves: previous chunk completely done
         {   // the chunk's weights and the first patch of both teams: all loads are issued before
@@ -147,6 +161,7 @@ __global__ __launch_bounds__(512) void k_conv_mfma_duo(conv_args a)
             static_assert(NWL * 512 * 16 == WBYTES, "weights must split evenly over the workgroup");
             const uint4* src = a.wp + (size_t)chunk * (WBYTES / 16);
             int n, y0, x0; tile_origin(wg, n, y0, x0);
+            cn = n; cy0 = y0; cx0 = x0;
             __amdgpu_buffer_rsrc_t rin = in_rsrc(wg, wg < n_tiles ? n : 0);
 #pragma unroll
             for (int j = 0; j < NPRE; ++j) load_piece(j, rin, y0, x0);
@@ -182,7 +197,9 @@ __global__ __launch_bounds__(512) void k_conv_mfma_duo(conv_args a)
         if (team == 1) idle_phase();
         for (int it = 0; it < iters; ++it) {
             const int tile = wg + it * G, ntile = tile + G;
-            int n, y0, x0; tile_origin(tile, n, y0, x0);
+            int n, y0, x0, next_entry = 0;
+            if constexpr (LIST) { n = cn; y0 = cy0; x0 = cx0; next_entry = list_load(ntile); }
+            else tile_origin(tile, n, y0, x0);
             __amdgpu_buffer_rsrc_t rsk = __builtin_amdgcn_make_buffer_rsrc(
                 (void*)((uint8_t*)a.skip + (size_t)n * out_img_bytes), 0, SKIP ? out_img_bytes : 0u, RSRC_FLAGS);
             uint4 sk[SKIP ? NOUT : 1];
@@ -253,7 +270,9 @@ __global__ __launch_bounds__(512) void k_conv_mfma_duo(conv_args a)
             __builtin_amdgcn_s_setprio(0);
 
             // ---------------- drain phase ----------------
-            int nn, ny0, nx0; tile_origin(ntile, nn, ny0, nx0);
+            int nn, ny0, nx0;
+            if constexpr (LIST) { decode(__builtin_amdgcn_readfirstlane(next_entry), nn, ny0, nx0); cn = nn; cy0 = ny0; cx0 = nx0; }
+            else tile_origin(ntile, nn, ny0, nx0);
             __amdgpu_buffer_rsrc_t rin = in_rsrc(ntile, ntile < n_tiles ? nn : 0);
             __amdgpu_buffer_rsrc_t rout = __builtin_amdgcn_make_buffer_rsrc(
                 (void*)((uint8_t*)a.out + (size_t)n * out_img_bytes), 0, out_img_bytes, RSRC_FLAGS);
@@ -325,17 +344,17 @@ __global__ __launch_bounds__(512) void k_conv_mfma_duo(conv_args a)
     }
 }
 
-template <bool SKIP, bool RELU, int MID>
+template <bool SKIP, bool RELU, int MID, bool LIST>
 static hipError_t launch_duo(hipStream_t stream, int device, const conv_args& a, int grid)
 {
     constexpr int lds = 9 * 4 * 2 * 1024 + 2 * 10 * PW * 128 + 256;
     static bool attr_done[RH_MAX_DEVICES] = {};            // the attribute is per device
     if (!attr_done[device]) {
-        hipError_t e = hipFuncSetAttribute((const void*)k_conv_mfma_duo<SKIP, RELU, MID>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        hipError_t e = hipFuncSetAttribute((const void*)k_conv_mfma_duo<SKIP, RELU, MID, LIST>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (e != hipSuccess) return e;
         attr_done[device] = true;
     }
-    hipLaunchKernelGGL((k_conv_mfma_duo<SKIP, RELU, MID>), dim3(grid), dim3(512), lds, stream, a);
+    hipLaunchKernelGGL((k_conv_mfma_duo<SKIP, RELU, MID, LIST>), dim3(grid), dim3(512), lds, stream, a);
     return hipGetLastError();
 }
 
@@ -343,7 +362,13 @@ hipError_t rh_launch_conv_duo(hipStream_t stream, int device, const conv_args& a
 {
     // first barrier of the compute phase after 10 of the 12 steps (A/B on one box: 0.7 % better than 11, 9 is worse)
     constexpr int MID = 10;
-    if (skip) return launch_duo<true, false, MID>(stream, device, a, grid);
-    if (relu) return launch_duo<false, true, MID>(stream, device, a, grid);
-    return launch_duo<false, false, MID>(stream, device, a, grid);
+    if (a.tile_list) {
+        if (a.n_chunks != 1) return hipErrorInvalidValue;      // a tile list goes with single-chunk layers only
+        if (skip) return launch_duo<true, false, MID, true>(stream, device, a, grid);
+        if (relu) return launch_duo<false, true, MID, true>(stream, device, a, grid);
+        return launch_duo<false, false, MID, true>(stream, device, a, grid);
+    }
+    if (skip) return launch_duo<true, false, MID, false>(stream, device, a, grid);
+    if (relu) return launch_duo<false, true, MID, false>(stream, device, a, grid);
+    return launch_duo<false, false, MID, false>(stream, device, a, grid);
 }

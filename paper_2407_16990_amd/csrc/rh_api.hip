@@ -57,7 +57,8 @@ extern "C" void rh_destroy(rh_ctx* ctx)
     for (hipEvent_t e : ctx->prof_pool) (void)hipEventDestroy(e);
     void* ptrs[] = {ctx->w_f32, ctx->wpack, ctx->bpack, ctx->fold_w, ctx->fold_b, ctx->frame_seg, ctx->seg_par, ctx->seg_T, ctx->seg_budget,
                     ctx->frame_nsel, ctx->frame_ties, ctx->owner_id, ctx->rank_of_id, ctx->raw, ctx->sorted,
-                    ctx->pcount, ctx->slot_of_mb, ctx->tr_off, ctx->tr_A, ctx->tr_T, ctx->act};
+                    ctx->pcount, ctx->tr_off, ctx->tr_A, ctx->tr_T, ctx->act,
+                    ctx->cell_mark, ctx->cell_live, ctx->cell_dead, ctx->cell_cnt};
     for (void* p : ptrs) if (p) (void)hipFree(p);
     delete ctx;
 }
@@ -107,7 +108,7 @@ extern "C" rh_status rh_create(const rh_config* cfg, const float* weights, size_
     A(dalloc(&ctx->frame_nsel, cfg->max_frames)); A(dalloc(&ctx->frame_ties, cfg->max_frames));
     A(dalloc(&ctx->owner_id, total)); A(dalloc(&ctx->rank_of_id, total));
     A(dalloc(&ctx->raw, total)); A(dalloc(&ctx->sorted, total));
-    A(dalloc(&ctx->pcount, 8 + 2 * total)); A(dalloc(&ctx->slot_of_mb, total));
+    A(dalloc(&ctx->pcount, 8 + 2 * total));
     A(dalloc(&ctx->tr_off, (size_t)cfg->max_frames + 1)); A(dalloc(&ctx->tr_A, cfg->max_frames)); A(dalloc(&ctx->tr_T, cfg->max_frames));
 #undef A
     if (e != hipSuccess) {
@@ -115,6 +116,7 @@ extern "C" rh_status rh_create(const rh_config* cfg, const float* weights, size_
         st = (e == hipErrorOutOfMemory) ? RH_E_NOMEM : RH_E_DEVICE;
     }
     if (st == RH_OK) st = rh_plan_init(ctx);
+    if (st == RH_OK && cfg->precision == RH_BF16 && cfg->net.channels == 64) st = rh_mask_init(ctx);
     if (st == RH_OK && cfg->precision == RH_BF16) st = rh_pack_weights_bf16(ctx, weights);
     if (st == RH_OK && cfg->precision == RH_BF16 && !cfg->per_layer_tail) st = rh_fold_weights(ctx, weights);
     if (st != RH_OK) { rh_destroy(ctx); return st; }
@@ -276,6 +278,22 @@ extern "C" rh_status rh_enhance_exact(rh_ctx* ctx, const uint8_t* in, int32_t N,
     const rh_status st = ctx->cfg.precision == RH_BF16 ? rh_launch_enhance_bf16(ctx, in, N, S, S, out, n_valid)
                                                        : rh_launch_enhance_fp32(ctx, in, N, S, S, out, n_valid);
     ctx->bz_boxes = nullptr; ctx->bz_counts = nullptr;
+    return st;
+}
+
+extern "C" rh_status rh_enhance_masked(rh_ctx* ctx, const uint8_t* in, int32_t N, const rh_box* boxes,
+                                       const uint32_t* counts, float* out, const uint32_t* n_valid)
+{
+    if (!ctx) return RH_E_INVALID;
+    if (!in || !out || !boxes || !counts) RH_FAIL(ctx, RH_E_INVALID, "rh_enhance_masked: null argument");
+    if (ctx->cfg.precision != RH_BF16 || ctx->cfg.net.channels != 64)
+        RH_FAIL(ctx, RH_E_UNIMPLEMENTED, "rh_enhance_masked: only bf16 networks with 64 channels have a tile-list conv kernel");
+    if (N < 1 || N > ctx->cfg.max_bins) RH_FAIL(ctx, RH_E_CAPACITY, "rh_enhance_masked: N=%d outside [1,%d]", N, ctx->cfg.max_bins);
+    if ((uintptr_t)out & 15) RH_FAIL(ctx, RH_E_INVALID, "rh_enhance_masked: out must be 16-byte aligned");
+    const int S = ctx->cfg.bin_size;
+    ctx->mk_boxes = boxes; ctx->mk_counts = counts;
+    const rh_status st = rh_launch_enhance_bf16(ctx, in, N, S, S, out, n_valid);
+    ctx->mk_boxes = nullptr; ctx->mk_counts = nullptr;
     return st;
 }
 

@@ -73,8 +73,6 @@ struct rh_ctx {
     rh_rawbox* raw;         // [total MBs]
     rh_rawbox* sorted;      // [total MBs]
     uint32_t* pcount;       // [8] plan counters: 0 n_raw boxes
-    // unpack scratch
-    int32_t* slot_of_mb;    // [total MBs] index into places or -1
     // temporal reuse scratch (dev)
     int32_t* tr_off;        // [max_frames + 1] first frame of each stream
     uint64_t* tr_A;         // [max_frames] cumulative change before each frame
@@ -83,6 +81,15 @@ struct rh_ctx {
     // rh_enhance_exact call, null otherwise)
     const rh_box* bz_boxes;
     const uint32_t* bz_counts;
+    // box-masked mode: the boxes of the bins being enhanced (set for the duration of one
+    // rh_enhance_masked call, null otherwise) and the cell scratch (64-channel bf16 nets only)
+    const rh_box* mk_boxes;
+    const uint32_t* mk_counts;
+    int cells_x, cells_y;   // cells per bin row / column
+    uint8_t* cell_mark;     // [max_bins * cells] 1 while a box touches the cell; all zero between calls
+    uint32_t* cell_live;    // [max_bins * cells] live cells = tile indices of the body convs
+    uint32_t* cell_dead;    // [max_bins * cells] the others
+    uint32_t* cell_cnt;     // [2] entries of the two lists
     int conv_parity;        // direction of the next bf16 conv's tile walk (alternates)
     // enhance workspace (grow-only)
     void* act;
@@ -133,6 +140,10 @@ rh_status rh_launch_temporal_spread(rh_ctx*, float* imp, int F, const uint8_t* s
 rh_status rh_pack_weights_bf16(rh_ctx*, const float* host_blob);
 rh_status rh_fold_weights(rh_ctx*, const float* host_blob);
 rh_status rh_plan_init(rh_ctx*);
+rh_status rh_mask_init(rh_ctx*);
+// box-masked mode: the cell lists of the call in progress; zeros over the dead cells of three
+// [N][S][S][64] bf16 tensors
+rh_status rh_launch_cell_lists(rh_ctx*, int N, const uint32_t* n_valid, void* act0, void* act1, void* act2);
 // exact-border mode: zero the out-of-frame part of every box in an activation tensor
 // [N][S*res][S*res][px_bytes]; a no-op unless an rh_enhance_exact call is in progress
 rh_status rh_zero_outside(rh_ctx*, void* act, int px_bytes, int res, int N, const uint32_t* n_valid);

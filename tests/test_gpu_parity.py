@@ -14,7 +14,7 @@ pytestmark = pytest.mark.gpu
 
 
 def full_path_check(cfg, n_frames=None, precision=None, segs=None, max_bins=None, sort_policy="density", rotate=False,
-                    expect_turned=False, per_layer_tail=False):
+                    expect_turned=False, per_layer_tail=False, masked=False):
     F = cfg.n_frames if n_frames is None else n_frames
     precision = precision or cfg.precision
     frames, imp = wl.make_frames(cfg, F), wl.make_importance(cfg, F)
@@ -28,12 +28,24 @@ def full_path_check(cfg, n_frames=None, precision=None, segs=None, max_bins=None
         assert o_plan.boxes[:, 5].sum() > 0, "the case is meant to turn at least one box"
     s = cfg.net.scale
     # enhance: both the exact-N call and the device-count call
-    g_net = rh.enhance(po.bins, n=o_plan.n_bins)
-    o_net = oracle.sr_forward(cfg.net, blob, o_bins)
+    if masked:      # box-masked mode: the body skips the cells no box touches, which hold zeros
+        keep = oracle.cell_keep(o_plan.boxes, cfg.halo, cfg.bin_size, o_plan.n_bins)
+        print(f"[{cfg.name}] live cell fraction {keep.mean():.3f}", flush=True)
+        assert keep.mean() < 1.0, "the case is meant to have cells that no box touches"
+        g_net = rh.enhance_masked(po.bins, po.boxes, po.counts, n=o_plan.n_bins)
+        o_net = oracle.sr_forward(cfg.net, blob, o_bins, keep, body_only=True)
+    else:
+        g_net = rh.enhance(po.bins, n=o_plan.n_bins)
+        o_net = oracle.sr_forward(cfg.net, blob, o_bins)
     tol = 1e-5 if precision == "fp32" else 1e-2
-    check_net(g_net.cpu().numpy(), o_net, precision, f"{cfg.name} n_bins={o_plan.n_bins}")
+    check_net(g_net.cpu().numpy(), o_net, precision, f"{cfg.name} n_bins={o_plan.n_bins}{' masked' if masked else ''}")
     g_net2 = torch.zeros_like(g_net)
-    rh.enhance(po.bins, n=o_plan.n_bins, n_valid=po.counts[1:2], out=g_net2)
+    if masked:
+        rh.enhance(po.bins, n=o_plan.n_bins, out=g_net2)           # a plain call in between leaves other values in the workspace
+        assert not torch.equal(g_net, g_net2), "the masked mode is a different function"
+        rh.enhance_masked(po.bins, po.boxes, po.counts, n=o_plan.n_bins, n_valid=po.counts[1:2], out=g_net2)
+    else:
+        rh.enhance(po.bins, n=o_plan.n_bins, n_valid=po.counts[1:2], out=g_net2)
     assert torch.equal(g_net, g_net2)
     # unpack
     hr, sel = rh.unpack(g_net, po.places, po.counts[3:4], d_frames, want_sel=True)
@@ -256,6 +268,38 @@ def test_cfg3_two_frames_bf16_larger_output_amplitude():
     bar is claimed for): the error grows in proportion and the bar with it."""
     cfg = wl.config(3)
     full_path_check(wl.replace(cfg, net=wl.replace(cfg.net, tail_scale=0.02)), n_frames=2)
+
+
+# ---- box-masked enhance mode (Sec. 3.3.2: bins are only partly occupied) -------------------------
+
+@pytest.mark.parametrize("net", [wl.Net("edsr", 64, 2, 2, 0.05), wl.Net("edsr", 64, 1, 4, 0.02), wl.Net("res", 64, 2, 2, 0.05),
+                                 wl.Net("plain", 64, 4, 2, 0.05), wl.Net("edsr", 64, 2, 3, 0.05)],
+                         ids=lambda n: f"{n.topology}x{n.scale}")
+def test_masked_enhance_small_nets(net):
+    """320 x 192 frame, 64 x 64 bins (4 x 2 cells each), every topology of the 64-channel kernel."""
+    full_path_check(wl.replace(wl.config(1), net=net, precision="bf16"), masked=True)
+
+
+def test_masked_enhance_layer_by_layer_tail_and_odd_bin_side():
+    """Bins of 80 x 80 pixels: 5 x 3 cells, the last column cut in half; upsampler run layer by layer."""
+    cfg = wl.replace(wl.config(1), net=wl.Net("edsr", 64, 2, 4, 0.02), precision="bf16", bin_size=80)
+    full_path_check(cfg, masked=True, per_layer_tail=True)
+
+
+def test_cfg3_two_frames_bf16_masked():
+    full_path_check(wl.config(3), n_frames=2, masked=True)
+
+
+def test_masked_enhance_needs_the_64_channel_bf16_kernel():
+    cfg = wl.config(1)
+    blob = wl.make_weights(cfg.net, cfg.weight_seed, cfg.precision)
+    rh = make_rh(cfg, blob)
+    bins = torch.zeros((1, cfg.bin_size, cfg.bin_size, 3), dtype=torch.uint8, device="cuda")
+    boxes = torch.zeros((4, 24), dtype=torch.uint8, device="cuda")
+    counts = torch.zeros(4, dtype=torch.int32, device="cuda")
+    with pytest.raises(RuntimeError, match="64 channels"):
+        rh.enhance_masked(bins, boxes, counts)
+    rh.close()
 
 
 def test_frame_based_run_bf16_matches_oracle():
