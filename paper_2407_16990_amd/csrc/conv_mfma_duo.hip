@@ -2,8 +2,8 @@
 //
 // Same implicit GEMM, LDS layouts, fragment order and buffer addressing as k_conv_mfma
 // (conv_mfma.hip), but the workgroup has 8 waves = two teams of 4.  The teams share the
-// LDS-resident weights and own one 10 x 34 pixel patch each: team t computes rows 8t..8t+7 of
-// the workgroup's 16 x 32 tile.  The teams run half a tile apart: while one team is in its
+// LDS-resident weights and own one 10 x 34 pixel patch each: a team computes one half (8 x 32
+// pixels) of a 16 x 32 tile at a time.  The teams run one half apart: while one team is in its
 // MFMA loop, the other rounds its finished accumulators to bf16, adds the skip tensor, writes
 // the result, and puts its next patch into LDS.  Every SIMD holds one wave of each team, so the
 // matrix pipe is fed by one wave while the other does vector-ALU, LDS and memory work.
@@ -17,11 +17,16 @@
 //   drain phase   : issue the global loads (next patch, skip), accumulators -> bf16 -> own LDS
 //                   slice -> registers, + skip, global stores | barrier |
 //                   next patch registers -> LDS | barrier
-// Team 0 runs compute, drain, compute, ...; team 1 starts with an idle phase and team 0 ends
-// with one, so the phases pair up.  The number of phases depends only on kernel arguments and
-// the workgroup index (never on data), tiles past the end are "null" tiles (all loads out of
-// range -> zeros, all stores dropped), and no wave leaves the loop early: every barrier is
-// reached by all 8 waves.
+// Team 0 runs compute, drain, compute, ...; team 1 starts with an idle phase, so the phases
+// pair up.  The unit of work is the half tile (8 x 32 pixels): the halves are numbered 2 * tile +
+// half and dealt out so that workgroup w takes units w, w + G, w + 2G, ... alternately with team 0
+// and team 1 (G workgroups).  When the units do not divide evenly team 1 has one unit fewer than
+// team 0 and ends with the idle phase instead (a whole tile per workgroup as the unit would leave
+// half the chip idle for a full round whenever the tile count is not a multiple of G).  The
+// number of phases depends only on kernel arguments, the workgroup index and - with a tile list -
+// the list's length (never on anything that differs between the waves of a workgroup), the
+// prefetch past a team's last unit loads out of range (zeros), and no wave leaves the loop
+// early: every barrier is reached by all 8 waves.
 #include <stdlib.h>
 
 #include <type_traits>
@@ -72,6 +77,7 @@ __global__ __launch_bounds__(512) void k_conv_mfma_duo(conv_args a)
     const int tiles_x = (a.W + 31) / 32, tiles_y = (a.H + 15) / 16;
     const int tiles_img = tiles_x * tiles_y;
     const int n_tiles = LIST ? (int)*a.n_list : n_img * tiles_img;
+    const int n_units = 2 * n_tiles;                           // half tiles
     // Tile order.  Workgroups go to the 8 XCDs round-robin; XCD x takes a contiguous run of tile
     // lanes so that neighbouring tiles (shared halo pixels) meet in one L2.
     // Layers with several output chunks (the upsampling convs): when the grid allows it the chunks
@@ -85,7 +91,10 @@ __global__ __launch_bounds__(512) void k_conv_mfma_duo(conv_args a)
     const int wg = deal ? xcd * (G / 8) + local / a.n_chunks
                         : ((G % 8 == 0) ? xcd * (G / 8) + local : (int)blockIdx.x);
     const int chunk_begin = deal ? local % a.n_chunks : 0, chunk_end = deal ? chunk_begin + 1 : a.n_chunks;
-    const int iters = n_tiles > wg ? (n_tiles - wg + G - 1) / G : 0;          // same for all 512 threads
+    auto units_from = [&](int first) { return n_units > first ? (n_units - first + 2 * G - 1) / (2 * G) : 0; };
+    const int u_first = wg + team * G;                         // this team's units: u_first, u_first + 2G, ...
+    const int iters0 = units_from(wg), iters1 = units_from(wg + G);           // team 1 has as many as team 0 or one fewer
+    const int iters = team ? iters1 : iters0;
     const int ps = a.ps;
     const uint32_t in_img_bytes = (uint32_t)a.H * a.W * PIXB;
     const uint32_t out_img_bytes = (uint32_t)(a.H * ps) * (a.W * ps) * OPIXB;
@@ -100,25 +109,26 @@ __global__ __launch_bounds__(512) void k_conv_mfma_duo(conv_args a)
     const int o_rowpitch = a.W * ps * OPIXB;
     const int row_pitch = a.W * PIXB;
 
-    // origin of team's half of tile number `tile` (rows y0..y0+7), image index n
-    auto decode = [&](int tile, int& n, int& y0, int& x0) __attribute__((always_inline)) {
+    // origin of half `half` of tile number `tile` (rows y0..y0+7), image index n
+    auto decode = [&](int tile, int half, int& n, int& y0, int& x0) __attribute__((always_inline)) {
         n = tile / tiles_img;
         const int tr = tile - n * tiles_img, ty = tr / tiles_x, tx = tr - ty * tiles_x;
-        y0 = ty * 16 + team * TH; x0 = tx * 32;
+        y0 = ty * 16 + half * TH; x0 = tx * 32;
     };
     // Consecutive layers walk the tensor in opposite directions: what a layer touched last (the
     // end of its input and output) is what the next layer touches first, while it is still in
     // the memory-side cache.  Walking every layer front to back through buffers that together
     // exceed that cache evicts each line just before it is needed again.
     __amdgpu_buffer_rsrc_t rlist = __builtin_amdgcn_make_buffer_rsrc((void*)a.tile_list, 0, LIST ? (uint32_t)n_tiles * 4u : 0u, RSRC_FLAGS);
-    auto list_load = [&](int idx) __attribute__((always_inline)) {       // entry of position idx (0 past the end)
-        const int pos = a.rev ? n_tiles - 1 - idx : idx;
-        return __builtin_amdgcn_raw_buffer_load_b32(rlist, idx < n_tiles ? (uint32_t)pos * 4u : OOB_OFF, 0, 0);
+    auto walk = [&](int u) __attribute__((always_inline)) { return (a.rev && u < n_units) ? n_units - 1 - u : u; };
+    auto list_load = [&](int u) __attribute__((always_inline)) {         // list entry of unit u's tile (0 past the end)
+        return __builtin_amdgcn_raw_buffer_load_b32(rlist, u < n_units ? (uint32_t)(walk(u) >> 1) * 4u : OOB_OFF, 0, 0);
     };
-    auto tile_origin = [&](int tile, int& n, int& y0, int& x0) __attribute__((always_inline)) {
-        if constexpr (LIST) tile = __builtin_amdgcn_readfirstlane(list_load(tile));
-        else if (a.rev && tile < n_tiles) tile = n_tiles - 1 - tile;
-        decode(tile, n, y0, x0);
+    auto unit_origin = [&](int u, int& n, int& y0, int& x0) __attribute__((always_inline)) {
+        const int uu = walk(u);
+        int tile = uu >> 1;
+        if constexpr (LIST) tile = __builtin_amdgcn_readfirstlane(list_load(u));
+        decode(tile, uu & 1, n, y0, x0);
     };
     uint4 pre[NPRE];
     auto load_piece = [&](int j, __amdgpu_buffer_rsrc_t rin, int y0, int x0) __attribute__((always_inline)) {
@@ -147,9 +157,9 @@ __global__ __launch_bounds__(512) void k_conv_mfma_duo(conv_args a)
         const int off = (y * ps + si) * o_rowpitch + (xb * ps + sj) * OPIXB + o_lane;
         return ok ? (uint32_t)off : OOB_OFF;
     };
-    auto in_rsrc = [&](int tile, int n) __attribute__((always_inline)) {
+    auto in_rsrc = [&](int u, int n) __attribute__((always_inline)) {
         return __builtin_amdgcn_make_buffer_rsrc((void*)(a.in + (size_t)n * a.H * a.W * CIN), 0,
-                                                 tile < n_tiles ? in_img_bytes : 0u, RSRC_FLAGS);
+                                                 u < n_units ? in_img_bytes : 0u, RSRC_FLAGS);
     };
 
     int cn = 0, cy0 = 0, cx0 = 0;                          // LIST: origin of the tile about to be computed
@@ -160,9 +170,9 @@ __global__ __launch_bounds__(512) void k_conv_mfma_duo(conv_args a)
             constexpr int NWL = WBYTES / 16 / 512;         // 16-byte weight pieces per thread
             static_assert(NWL * 512 * 16 == WBYTES, "weights must split evenly over the workgroup");
             const uint4* src = a.wp + (size_t)chunk * (WBYTES / 16);
-            int n, y0, x0; tile_origin(wg, n, y0, x0);
+            int n, y0, x0; unit_origin(u_first, n, y0, x0);
             cn = n; cy0 = y0; cx0 = x0;
-            __amdgpu_buffer_rsrc_t rin = in_rsrc(wg, wg < n_tiles ? n : 0);
+            __amdgpu_buffer_rsrc_t rin = in_rsrc(u_first, u_first < n_units ? n : 0);
 #pragma unroll
             for (int j = 0; j < NPRE; ++j) load_piece(j, rin, y0, x0);
             constexpr int WB = 3;                          // weight pieces in flight per thread (register budget)
@@ -196,10 +206,10 @@ __global__ __launch_bounds__(512) void k_conv_mfma_duo(conv_args a)
         if constexpr (!SEED_IN_COMPUTE) seed_acc();
         if (team == 1) idle_phase();
         for (int it = 0; it < iters; ++it) {
-            const int tile = wg + it * G, ntile = tile + G;
+            const int unit = u_first + it * 2 * G, nunit = unit + 2 * G;
             int n, y0, x0, next_entry = 0;
-            if constexpr (LIST) { n = cn; y0 = cy0; x0 = cx0; next_entry = list_load(ntile); }
-            else tile_origin(tile, n, y0, x0);
+            if constexpr (LIST) { n = cn; y0 = cy0; x0 = cx0; next_entry = list_load(nunit); }
+            else unit_origin(unit, n, y0, x0);
             __amdgpu_buffer_rsrc_t rsk = __builtin_amdgcn_make_buffer_rsrc(
                 (void*)((uint8_t*)a.skip + (size_t)n * out_img_bytes), 0, SKIP ? out_img_bytes : 0u, RSRC_FLAGS);
             uint4 sk[SKIP ? NOUT : 1];
@@ -271,9 +281,9 @@ __global__ __launch_bounds__(512) void k_conv_mfma_duo(conv_args a)
 
             // ---------------- drain phase ----------------
             int nn, ny0, nx0;
-            if constexpr (LIST) { decode(__builtin_amdgcn_readfirstlane(next_entry), nn, ny0, nx0); cn = nn; cy0 = ny0; cx0 = nx0; }
-            else tile_origin(ntile, nn, ny0, nx0);
-            __amdgpu_buffer_rsrc_t rin = in_rsrc(ntile, ntile < n_tiles ? nn : 0);
+            if constexpr (LIST) { decode(__builtin_amdgcn_readfirstlane(next_entry), walk(nunit) & 1, nn, ny0, nx0); cn = nn; cy0 = ny0; cx0 = nx0; }
+            else unit_origin(nunit, nn, ny0, nx0);
+            __amdgpu_buffer_rsrc_t rin = in_rsrc(nunit, nunit < n_units ? nn : 0);
             __amdgpu_buffer_rsrc_t rout = __builtin_amdgcn_make_buffer_rsrc(
                 (void*)((uint8_t*)a.out + (size_t)n * out_img_bytes), 0, out_img_bytes, RSRC_FLAGS);
             // The global loads of the next tile's patch (stored to LDS at the end of the phase) are
@@ -340,7 +350,8 @@ __global__ __launch_bounds__(512) void k_conv_mfma_duo(conv_args a)
             store_patch();                                    // next tile's patch (zeros after the last tile)
             phase_barrier();                                  // 2
         }
-        if (team == 0) idle_phase();
+        // team 0's last drain phase pairs with team 1's last one, or - team 1 a unit short - with its idle phase
+        if (team == 0 ? iters1 == iters0 : iters1 < iters0) idle_phase();
     }
 }
 
