@@ -32,7 +32,7 @@ HBM_PEAK = 8.0e12          # B/s
 # HBM bytes per launch of the dominant kernel class on the default workload: NOT measured live but
 # taken from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in the named profile (scaled by
 # the plain-copy calibration stated there); only reported for that workload and kernel set.
-PROFILED_TRAFFIC = {"cfg3_16x480x272_edsr64_x4_bf16": (406.2e6, "profiles/conv_mfma_cfg3_hbm_counters.md")}
+PROFILED_TRAFFIC = {"cfg3_16x480x272_edsr64_x4_bf16": (404.2e6, "profiles/conv_mfma_cfg3_hbm_counters.md")}
 CONV_KERNEL = {64: "k_conv_mfma_duo<SKIP,RELU,10> (64-channel bf16-output convs of the network body: ReLU and skip-add instantiations)",
                32: "k_conv_mfma<32,1,16,false,SKIP,RELU> (bf16-output 32-channel convs)"}
 
