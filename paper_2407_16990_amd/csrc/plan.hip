@@ -165,11 +165,24 @@ __global__ __launch_bounds__(256) void k_plan_rank(const rh_rawbox* __restrict__
 // box_pos[i] = {bin | turned<<16, bx | by<<16}; pcount[1] = n_bins, pcount[2] = overflow.
 // rotate: a rectangle that cannot take the box upright may take it turned (RotatePacking).
 // The loop over the boxes is serial by definition, so its cost is the latency of one step.  It
-// runs in ONE wave: the 64 lanes test 64 free rectangles at a time and a ballot gives the first
-// fit.  The hardware executes the LDS traffic of a single wave in program order; wave_sync() after
-// every step in which lanes write what other lanes read next keeps the compiler from moving LDS
-// accesses across it.  Every lane tracks the list length and bin count in registers.
+// runs in ONE wave.  While the free list has at most 62 entries it lives in registers, entry j in
+// lane j: a ballot gives the first fit, the winner's fields are lane reads, and the entries behind
+// it move up or down by one lane with a whole-wave DPP shift - no memory in the loop at all.  The
+// first time the list could outgrow the wave it is written to LDS and stays there: the 64 lanes
+// then test 64 rectangles at a time; the hardware executes the LDS traffic of a single wave in
+// program order, and wave_sync() after every step in which lanes write what other lanes read next
+// keeps the compiler from moving LDS accesses across it.  Every lane tracks the list length and
+// bin count in registers.
 // One wave.  sizes: box i's (wmb | hmb << 16) comes from size_of(i).  Returns through n_bins / overflow.
+__device__ __forceinline__ uint32_t lane_from_below(uint32_t v)      // lane l gets lane l-1's value, lane 0 keeps its own
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x138 /* wave_shr:1 */, 0xF, 0xF, false);
+}
+__device__ __forceinline__ uint32_t lane_from_above(uint32_t v)      // lane l gets lane l+1's value, lane 63 keeps its own
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x130 /* wave_shl:1 */, 0xF, 0xF, false);
+}
+
 template <typename SizeOf>
 __device__ __forceinline__ void place_boxes(uint32_t n, SizeOf size_of, uint32_t* fxy, uint32_t* fwh, uint32_t* fbin,
                                             int halo, int S, int max_bins, int free_cap, int rotate,
@@ -177,8 +190,10 @@ __device__ __forceinline__ void place_boxes(uint32_t n, SizeOf size_of, uint32_t
 {
     const int lane = threadIdx.x & 63;
     const int minside = RH_MB + 2 * halo;
+    constexpr int REG_MAX = 62;                              // a step adds at most 2 entries
     int nfree = 0, nbins = 0;
     uint32_t i = 0, szv = 0, pos0 = 0, pos1 = 0;             // lane l keeps the position of box (i & ~63) + l
+    uint32_t rxy = 0, rwh = 0, rbn = 0;                      // register mode: free rectangle `lane`
     bool overflow = false;
     // Results leave in groups of 64: a global store per box would be waited for by the next box's
     // loads (stores and loads share the wave's memory counter), half a microsecond each.
@@ -186,10 +201,59 @@ __device__ __forceinline__ void place_boxes(uint32_t n, SizeOf size_of, uint32_t
         const uint32_t g0 = (upto - 1u) & ~63u;
         if (upto && g0 + lane < upto) { box_pos[2 * (g0 + lane)] = pos0; box_pos[2 * (g0 + lane) + 1] = pos1; }
     };
-    for (; i < n && !overflow; ++i) {
+    // ---- register mode: the whole step is lane arithmetic and a few scalar selects ----
+    for (; i < n && !overflow && nfree <= REG_MAX; ++i) {
         if ((i & 63u) == 0) {
             flush(i);
             szv = (i + lane < n) ? size_of(i + lane) : 0u;   // the next 64 box sizes, one per lane
+        }
+        const uint32_t sz = (uint32_t)__builtin_amdgcn_readlane((int)szv, (int)(i & 63u));
+        const int bw0 = RH_MB * (int)(sz & 0xFFFF) + 2 * halo, bh0 = RH_MB * (int)(sz >> 16) + 2 * halo;
+        const int w = (int)(rwh & 0xFFFF), h = (int)(rwh >> 16);
+        const bool fit = lane < nfree && ((w >= bw0 && h >= bh0) || (rotate && w >= bh0 && h >= bw0));
+        const unsigned long long m = __ballot(fit);
+        const bool found = m != 0;
+        if (found ? nfree + 1 > free_cap : (nbins >= max_bins || nfree + 2 > free_cap)) { overflow = true; break; }
+        const int at = found ? __ffsll((long long)m) - 1 : nfree;              // a new bin's area goes to the end of the list
+        const uint32_t lxy = (uint32_t)__builtin_amdgcn_readlane((int)rxy, at), lwh = (uint32_t)__builtin_amdgcn_readlane((int)rwh, at);
+        const uint32_t lbn = (uint32_t)__builtin_amdgcn_readlane((int)rbn, at);
+        const uint32_t exy = found ? lxy : 0u, ewh = found ? lwh : ((uint32_t)S | ((uint32_t)S << 16));
+        const int fb = found ? (int)lbn : nbins;
+        const int cur_n = found ? nfree : nfree + 1;
+        nbins += found ? 0 : 1;
+        const int fx = exy & 0xFFFF, fy = exy >> 16, fw = ewh & 0xFFFF, fh = ewh >> 16;
+        const bool turned = !(fw >= bw0 && fh >= bh0);       // upright whenever that fits
+        const int bw = turned ? bh0 : bw0, bh = turned ? bw0 : bh0;            // occupied size
+        if (lane == (int)(i & 63u)) { pos0 = (uint32_t)fb | (turned ? 0x10000u : 0u); pos1 = (uint32_t)fx | ((uint32_t)fy << 16); }
+        // remainder: the larger of (right strip, full height) and (bottom strip, full width),
+        // plus what is left of the other
+        const int rw = fw - bw, bhei = fh - bh;
+        const bool right_full = rw * fh >= fw * bhei;
+        const int rh = right_full ? fh : bh, bwid = right_full ? bw : fw;
+        const bool keep_r = min(rw, rh) >= minside, keep_b = min(bwid, bhei) >= minside;
+        const uint32_t Rxy = (uint32_t)(fx + bw) | ((uint32_t)fy << 16), Rwh = (uint32_t)rw | ((uint32_t)rh << 16);
+        const uint32_t Bxy = (uint32_t)fx | ((uint32_t)(fy + bh) << 16), Bwh = (uint32_t)bwid | ((uint32_t)bhei << 16);
+        const bool b_first = keep_b && (!keep_r || bwid * bhei < rw * rh);     // both kept: the smaller one first
+        const uint32_t e0xy = b_first ? Bxy : Rxy, e0wh = b_first ? Bwh : Rwh, e1xy = b_first ? Rxy : Bxy, e1wh = b_first ? Rwh : Bwh;
+        const int ni = (keep_r ? 1 : 0) + (keep_b ? 1 : 0);
+        // the survivors replace entry `at`: the entries behind it move by ni - 1 lanes
+        const uint32_t dxy = lane_from_below(rxy), dwh = lane_from_below(rwh), dbn = lane_from_below(rbn);
+        const uint32_t uxy = lane_from_above(rxy), uwh = lane_from_above(rwh), ubn = lane_from_above(rbn);
+        const bool down = ni == 2 && lane > at + 1, up = ni == 0 && lane >= at;
+        rxy = down ? dxy : up ? uxy : rxy; rwh = down ? dwh : up ? uwh : rwh; rbn = down ? dbn : up ? ubn : rbn;
+        const bool s0 = ni > 0 && lane == at, s1 = ni > 1 && lane == at + 1;
+        rxy = s0 ? e0xy : s1 ? e1xy : rxy; rwh = s0 ? e0wh : s1 ? e1wh : rwh; rbn = (s0 || s1) ? (uint32_t)fb : rbn;
+        nfree = cur_n + ni - 1;
+    }
+    // ---- the list has outgrown the wave: it moves to LDS for the rest of the boxes ----
+    if (i < n && !overflow) {
+        if (lane < nfree) { fxy[lane] = rxy; fwh[lane] = rwh; fbin[lane] = rbn; }
+        wave_sync();
+    }
+    for (; i < n && !overflow; ++i) {
+        if ((i & 63u) == 0) {
+            flush(i);
+            szv = (i + lane < n) ? size_of(i + lane) : 0u;
         }
         const uint32_t sz = (uint32_t)__builtin_amdgcn_readlane((int)szv, (int)(i & 63u));
         int bw = RH_MB * (int)(sz & 0xFFFF) + 2 * halo, bh = RH_MB * (int)(sz >> 16) + 2 * halo;
@@ -223,13 +287,11 @@ __device__ __forceinline__ void place_boxes(uint32_t n, SizeOf size_of, uint32_t
         const bool turned = !(fw >= bw && fh >= bh);         // upright whenever that fits
         if (turned) { const int t = bw; bw = bh; bh = t; }   // occupied size
         if (lane == (int)(i & 63u)) { pos0 = (uint32_t)fb | (turned ? 0x10000u : 0u); pos1 = (uint32_t)fx | ((uint32_t)fy << 16); }
-        // remainder: the larger of (right strip, full height) and (bottom strip, full width),
-        // plus what is left of the other
         const int ar = (fw - bw) * fh, ab = fw * (fh - bh);
         int rx = fx + bw, ry = fy, rw = fw - bw, rh, bx = fx, by = fy + bh, bwid, bhei = fh - bh;
         if (ar >= ab) { rh = fh; bwid = bw; } else { rh = bh; bwid = fw; }
         const bool keep_r = rw >= minside && rh >= minside, keep_b = bwid >= minside && bhei >= minside;
-        uint32_t ixy[2], iwh[2]; int ni = 0;
+        uint32_t ixy[2] = {0, 0}, iwh[2] = {0, 0}; int ni = 0;
         const uint32_t Rxy = rx | (ry << 16), Rwh = rw | (rh << 16), Bxy = bx | (by << 16), Bwh = bwid | (bhei << 16);
         if (keep_r && keep_b) {
             if (bwid * bhei < rw * rh) { ixy[0] = Bxy; iwh[0] = Bwh; ixy[1] = Rxy; iwh[1] = Rwh; }
