@@ -28,16 +28,21 @@ __device__ __forceinline__ uint32_t imp_key(float v)
 __device__ __forceinline__ void hist_add(uint32_t* hist, bool todo, uint32_t bin, bool aggregate)
 {
     if (!aggregate) { if (todo) atomicAdd(&hist[bin], 1u); return; }
-    // the top byte (sign and exponent) puts most keys into a few bins: lanes of a wave that
-    // hit the same bin are counted with one ballot and added by one lane
-    while (__any(todo)) {
-        const unsigned long long act = __ballot(todo);
+    // the top byte (sign and exponent) can put most keys of a wave into a few bins, which would
+    // serialise their atomics: the lanes that share the bin of the first pending lane are counted
+    // with one ballot and added by one lane, twice; what is left after that is spread out
+    unsigned long long act = __ballot(todo);
+#pragma unroll
+    for (int round = 0; round < 2; ++round) {
+        if (!act) break;
         const int first = __ffsll((long long)act) - 1;
-        const uint32_t b = __shfl(bin, first);
+        const uint32_t b = (uint32_t)__builtin_amdgcn_readlane((int)bin, first);
         const unsigned long long same = __ballot(todo && bin == b);
         if ((int)(threadIdx.x & 63) == first) atomicAdd(&hist[b], (uint32_t)__popcll(same));
+        act &= ~same;
         todo = todo && bin != b;
     }
+    if (todo) atomicAdd(&hist[bin], 1u);
 }
 
 __global__ __launch_bounds__(1024) void k_select_kth(const float* __restrict__ imp,
@@ -132,14 +137,14 @@ __global__ __launch_bounds__(1024) void k_select_kth(const float* __restrict__ i
                 const uint32_t i = (uint32_t)j * 1024u + tid;
                 const bool gt = i < n && keys[j] > T, eq = i < n && keys[j] == T;
                 const uint32_t fr = i / (uint32_t)per;             // frame within the segment
-                bool todo = gt || eq;
-                while (__any(todo)) {                              // one round per frame present in the wave
-                    const int first = __ffsll((long long)__ballot(todo)) - 1;
-                    const uint32_t fs = __shfl(fr, first);
-                    const bool same = todo && fr == fs;
-                    const uint32_t ng = (uint32_t)__popcll(__ballot(same && gt)), ne = (uint32_t)__popcll(__ballot(same && eq));
+                unsigned long long act = __ballot(gt || eq);
+                while (act) {                                      // one round per frame present in the wave
+                    const int first = __ffsll((long long)act) - 1;
+                    const uint32_t fs = (uint32_t)__builtin_amdgcn_readlane((int)fr, first);
+                    const unsigned long long mg = __ballot(gt && fr == fs), me = __ballot(eq && fr == fs);
+                    const uint32_t ng = (uint32_t)__popcll(mg), ne = (uint32_t)__popcll(me);
                     if (lane == first) { if (ng) atomicAdd(&s_gt[fs], ng); if (ne) atomicAdd(&s_eq[fs], ne); }
-                    todo = todo && !same;
+                    act &= ~(mg | me);
                 }
             }
         } else {                                               // one wave per frame, from global memory
