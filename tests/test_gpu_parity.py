@@ -290,6 +290,34 @@ def test_cfg3_two_frames_bf16_masked():
     full_path_check(wl.config(3), n_frames=2, masked=True)
 
 
+def test_masked_enhance_turned_boxes():
+    """RotatePacking: a turned box marks the cells of its exchanged extent."""
+    cfg = wl.replace(wl.config(3), n_frames=2, width=160, height=112, halo=6, bin_size=96, importance="uniform", frac=0.4,
+                     net=wl.Net("edsr", 64, 2, 4, 0.05))
+    full_path_check(cfg, rotate=True, expect_turned=True, masked=True)
+
+
+def test_masked_enhance_without_boxes_is_the_tail_of_zero():
+    """No box at all: every cell is cleared, the body computes nothing, and the layers after it
+    run on a zero tensor; and a batch count of zero on the device writes nothing."""
+    net = wl.Net("edsr", 64, 2, 4, 0.05)
+    cfg = wl.replace(wl.config(3), net=net)
+    blob = wl.make_weights(net, 2, "bf16")
+    rh = make_rh(cfg, blob, max_bins=8)
+    S = cfg.bin_size
+    bins = torch.randint(0, 256, (2, S, S, 3), dtype=torch.uint8, device="cuda")
+    boxes = torch.zeros((4, 24), dtype=torch.uint8, device="cuda")
+    counts = torch.zeros(4, dtype=torch.int32, device="cuda")
+    rh.enhance(bins)                                           # leaves other values in the workspace
+    g = rh.enhance_masked(bins, boxes, counts).cpu().numpy()
+    o = oracle.sr_forward(net, blob, bins.cpu().numpy(), np.zeros((2, S, S), dtype=np.uint8), body_only=True)
+    check_net(g, o, "bf16", "masked, no boxes")
+    out = torch.full((2, 4 * S, 4 * S, 3), 7.0, dtype=torch.float32, device="cuda")
+    rh.enhance_masked(bins, boxes, counts, n_valid=counts[1:2], out=out)
+    assert bool((out == 7.0).all())
+    rh.close()
+
+
 def test_masked_enhance_needs_the_64_channel_bf16_kernel():
     cfg = wl.config(1)
     blob = wl.make_weights(cfg.net, cfg.weight_seed, cfg.precision)
