@@ -37,7 +37,7 @@ CONV_KERNEL = {64: "k_conv_mfma_duo<SKIP,RELU,10> (64-channel bf16-output convs 
                32: "k_conv_mfma<32,1,16,false,SKIP,RELU> (bf16-output 32-channel convs)"}
 
 
-def live_cell_fraction(boxes, halo, S, n_bins, cell_h=16, cell_w=32):
+def live_cell_fraction(boxes, halo, S, n_bins, cell_h=8, cell_w=32):
     """Share of the bins' cell_h x cell_w cells that a placed box (with its halo) touches: what the
     body convs of the box-masked enhance mode compute."""
     cx, cy = -(-S // cell_w), -(-S // cell_h)
@@ -100,7 +100,7 @@ class Runner:
         self.po = None
         self.exact = args.exact_border
         self.masked = bool(getattr(args, "box_masked", False)) and cfg.precision == "bf16" and cfg.net.channels == 64
-        self.live_frac = 1.0      # box-masked mode: fraction of the 16 x 32 cells that the body convs compute
+        self.live_frac = 1.0      # box-masked mode: fraction of the 8 x 32 cells that the body convs compute
         self.sync_counts = args.sync_counts
         self.net_out = self.hr = None
         self.cap = 0
@@ -218,7 +218,7 @@ def main():
     ap.add_argument("--importance", choices=["clustered", "uniform"], default=None,
                     help="override the importance recipe (uniform = iid, isolated macroblocks: the packer's worst case)")
     ap.add_argument("--box-masked", action="store_true",
-                    help="enhance with rh_enhance_masked (the body convs skip the 16 x 32 cells that no box touches; "
+                    help="enhance with rh_enhance_masked (the body convs skip the 8 x 32 cells that no box touches; "
                          "a different function near those cells)")
     ap.add_argument("--no-box-masked-leg", action="store_true", help="skip the box-masked leg of the default run")
     ap.add_argument("--exact-border", action="store_true",
@@ -422,7 +422,7 @@ def main():
     del run, rh, po
 
     if not args.box_masked and not args.no_box_masked_leg and not args.exact_border and cfg.precision == "bf16" and cfg.net.channels == 64:
-        # The same batch with rh_enhance_masked: the body convs compute only the 16 x 32 cells that a box
+        # The same batch with rh_enhance_masked: the body convs compute only the 8 x 32 cells that a box
         # touches (the other cells hold zeros).  Not the headline: its output differs from rh_enhance's
         # within the receptive field of the skipped cells.
         args.box_masked = True

@@ -207,7 +207,7 @@ rh_status rh_enhance_exact(rh_ctx* ctx, const uint8_t* in, int32_t N, const rh_b
  * boxes / counts: dev, as written by rh_pack for these bins; N <= max_bins.  Costs three small
  * extra launches.  RH_E_UNIMPLEMENTED for other networks.
  */
-#define RH_CELL_H 16
+#define RH_CELL_H 8
 #define RH_CELL_W 32
 rh_status rh_enhance_masked(rh_ctx* ctx, const uint8_t* in, int32_t N, const rh_box* boxes,
                             const uint32_t* counts, float* out, const uint32_t* n_valid);

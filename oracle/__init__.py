@@ -141,7 +141,7 @@ def border_keep(frame_h: int, frame_w: int, boxes: np.ndarray, halo: int, bin_si
     return keep
 
 
-def cell_keep(boxes: np.ndarray, halo: int, bin_size: int, n_bins: int, cell_h: int = 16, cell_w: int = 32) -> np.ndarray:
+def cell_keep(boxes: np.ndarray, halo: int, bin_size: int, n_bins: int, cell_h: int = 8, cell_w: int = 32) -> np.ndarray:
     """Box-masked mode: u8 [n_bins,S,S], 1 in every cell_h x cell_w cell that a placed box touches."""
     boxes = np.ascontiguousarray(boxes, dtype=np.int32).reshape(-1, 10)
     keep = np.zeros((n_bins, bin_size, bin_size), dtype=np.uint8)

@@ -238,7 +238,7 @@ class RH:
     def enhance_masked(self, bins: torch.Tensor, boxes: torch.Tensor, counts: torch.Tensor, n: int | None = None,
                        n_valid: torch.Tensor | None = None, out: torch.Tensor | None = None) -> torch.Tensor:
         """Box-masked variant of enhance for packed bins (boxes, counts as returned by pack): the body
-        convs skip the 16 x 32 cells that no box touches."""
+        convs skip the 8 x 32 cells that no box touches."""
         assert bins.is_cuda and bins.dtype == torch.uint8 and bins.is_contiguous()
         N, H, W, _ = bins.shape
         assert H == W == self.cfg.bin_size

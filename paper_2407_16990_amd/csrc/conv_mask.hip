@@ -1,9 +1,9 @@
 // Box-masked enhance mode (Sec. 3.3.2: a packed bin is only partly occupied).
 //
-// A bin is cut into cells of RH_CELL_H x RH_CELL_W pixels - the tile of the 64-channel conv
-// kernel - and a cell is live when a placed box (with its halo) shares a pixel with it.  The body
-// convs compute the live cells only; every other cell of the three activation tensors they read
-// is zero.  Three small launches per call:
+// A bin is cut into cells of RH_CELL_H x RH_CELL_W pixels - the half tile that is the unit of
+// work of the 64-channel conv kernel - and a cell is live when a placed box (with its halo)
+// shares a pixel with it.  The body convs compute the live cells only; every other cell of the
+// three activation tensors they read is zero.  Three small launches per call:
 //   k_cell_mark  : one thread per box sets the mark byte of every cell the box touches
 //   k_cell_lists : one wave per bin turns the marks into the list of live cells (what the conv
 //                  kernel walks) and the list of the others (what gets cleared), and clears the

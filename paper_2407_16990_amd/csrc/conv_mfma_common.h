@@ -19,8 +19,9 @@ struct conv_args {
     int relu, ps, n_chunks;  // bf16 output mode
     int cout_real, s_final;  // fp32 output mode
     int rev;                 // 1: walk the tiles from the last to the first (k_conv_mfma_duo)
-    // box-masked mode (k_conv_mfma_duo): only the tiles listed are computed.  tile_list: indices
-    // n * tiles_per_image + ty * tiles_x + tx in any order, n_list: their number (both dev); null: all tiles
+    // box-masked mode (k_conv_mfma_duo): only the half tiles (8 rows x 32 pixels) listed are computed.
+    // tile_list: indices n * cells_per_image + cy * tiles_x + tx in any order, cy counting rows of 8;
+    // n_list: their number (both dev); null: all tiles
     const uint32_t* tile_list;
     const uint32_t* n_list;
 };

@@ -43,7 +43,7 @@ __device__ __forceinline__ void for_each_step2(F& f)
 __device__ __forceinline__ void phase_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 __device__ __forceinline__ void idle_phase() { phase_barrier(); phase_barrier(); }
 
-// LIST: the tiles to compute come from a.tile_list (box-masked mode) instead of being all tiles of
+// LIST: the half tiles to compute come from a.tile_list (box-masked mode) instead of being all of
 // all images.  The entry of the next tile is requested with a vector load at the start of the
 // compute phase and read at the start of the drain phase, a whole phase later: a scalar load would
 // share its counter with the LDS fragment reads and turn their partial waits into full ones.
@@ -76,8 +76,9 @@ __global__ __launch_bounds__(512) void k_conv_mfma_duo(conv_args a)
     const int n_img = a.n_valid ? min((int)*a.n_valid, a.N) : a.N;
     const int tiles_x = (a.W + 31) / 32, tiles_y = (a.H + 15) / 16;
     const int tiles_img = tiles_x * tiles_y;
-    const int n_tiles = LIST ? (int)*a.n_list : n_img * tiles_img;
-    const int n_units = 2 * n_tiles;                           // half tiles
+    // half tiles; with a list, its entries are half tiles (n * cells_per_image + row-of-8 * tiles_x + tx)
+    const int n_units = LIST ? (int)*a.n_list : 2 * n_img * tiles_img;
+    const int cells_img = tiles_x * ((a.H + 7) / 8);
     // Tile order.  Workgroups go to the 8 XCDs round-robin; XCD x takes a contiguous run of tile
     // lanes so that neighbouring tiles (shared halo pixels) meet in one L2.
     // Layers with several output chunks (the upsampling convs): when the grid allows it the chunks
@@ -119,16 +120,19 @@ __global__ __launch_bounds__(512) void k_conv_mfma_duo(conv_args a)
     // end of its input and output) is what the next layer touches first, while it is still in
     // the memory-side cache.  Walking every layer front to back through buffers that together
     // exceed that cache evicts each line just before it is needed again.
-    __amdgpu_buffer_rsrc_t rlist = __builtin_amdgcn_make_buffer_rsrc((void*)a.tile_list, 0, LIST ? (uint32_t)n_tiles * 4u : 0u, RSRC_FLAGS);
+    __amdgpu_buffer_rsrc_t rlist = __builtin_amdgcn_make_buffer_rsrc((void*)a.tile_list, 0, LIST ? (uint32_t)n_units * 4u : 0u, RSRC_FLAGS);
     auto walk = [&](int u) __attribute__((always_inline)) { return (a.rev && u < n_units) ? n_units - 1 - u : u; };
-    auto list_load = [&](int u) __attribute__((always_inline)) {         // list entry of unit u's tile (0 past the end)
-        return __builtin_amdgcn_raw_buffer_load_b32(rlist, u < n_units ? (uint32_t)(walk(u) >> 1) * 4u : OOB_OFF, 0, 0);
+    auto list_load = [&](int u) __attribute__((always_inline)) {         // list entry of unit u (0 past the end)
+        return __builtin_amdgcn_raw_buffer_load_b32(rlist, u < n_units ? (uint32_t)walk(u) * 4u : OOB_OFF, 0, 0);
+    };
+    auto decode_cell = [&](int cell, int& n, int& y0, int& x0) __attribute__((always_inline)) {
+        n = cell / cells_img;
+        const int cr = cell - n * cells_img, cy = cr / tiles_x, cx = cr - cy * tiles_x;
+        y0 = cy * TH; x0 = cx * 32;
     };
     auto unit_origin = [&](int u, int& n, int& y0, int& x0) __attribute__((always_inline)) {
-        const int uu = walk(u);
-        int tile = uu >> 1;
-        if constexpr (LIST) tile = __builtin_amdgcn_readfirstlane(list_load(u));
-        decode(tile, uu & 1, n, y0, x0);
+        if constexpr (LIST) decode_cell(__builtin_amdgcn_readfirstlane(list_load(u)), n, y0, x0);
+        else { const int uu = walk(u); decode(uu >> 1, uu & 1, n, y0, x0); }
     };
     uint4 pre[NPRE];
     auto load_piece = [&](int j, __amdgpu_buffer_rsrc_t rin, int y0, int x0) __attribute__((always_inline)) {
@@ -281,7 +285,7 @@ __global__ __launch_bounds__(512) void k_conv_mfma_duo(conv_args a)
 
             // ---------------- drain phase ----------------
             int nn, ny0, nx0;
-            if constexpr (LIST) { decode(__builtin_amdgcn_readfirstlane(next_entry), walk(nunit) & 1, nn, ny0, nx0); cn = nn; cy0 = ny0; cx0 = nx0; }
+            if constexpr (LIST) { decode_cell(__builtin_amdgcn_readfirstlane(next_entry), nn, ny0, nx0); cn = nn; cy0 = ny0; cx0 = nx0; }
             else unit_origin(nunit, nn, ny0, nx0);
             __amdgpu_buffer_rsrc_t rin = in_rsrc(nunit, nunit < n_units ? nn : 0);
             __amdgpu_buffer_rsrc_t rout = __builtin_amdgcn_make_buffer_rsrc(

@@ -276,12 +276,12 @@ def test_cfg3_two_frames_bf16_larger_output_amplitude():
                                  wl.Net("plain", 64, 4, 2, 0.05), wl.Net("edsr", 64, 2, 3, 0.05)],
                          ids=lambda n: f"{n.topology}x{n.scale}")
 def test_masked_enhance_small_nets(net):
-    """320 x 192 frame, 64 x 64 bins (4 x 2 cells each), every topology of the 64-channel kernel."""
+    """320 x 192 frame, 64 x 64 bins (8 x 2 cells each), every topology of the 64-channel kernel."""
     full_path_check(wl.replace(wl.config(1), net=net, precision="bf16"), masked=True)
 
 
 def test_masked_enhance_layer_by_layer_tail_and_odd_bin_side():
-    """Bins of 80 x 80 pixels: 5 x 3 cells, the last column cut in half; upsampler run layer by layer."""
+    """Bins of 80 x 80 pixels: 10 x 3 cells, the last column cut in half; upsampler run layer by layer."""
     cfg = wl.replace(wl.config(1), net=wl.Net("edsr", 64, 2, 4, 0.02), precision="bf16", bin_size=80)
     full_path_check(cfg, masked=True, per_layer_tail=True)
 

@@ -59,16 +59,23 @@ def test_cell_keep_hand_case(orc):
         [0, 9, 9, 1, 1, 0, 2, 31, 15, 2],      # 22 x 22 at (31, 15): cols 31..52 -> both cell cols; rows 15..36 -> cell rows 0..2
         [0, 3, 3, 1, 1, 0, 0xFFFF, 0, 0, 3],   # did not fit: no bin
     ], dtype=np.int32)
-    keep = orc.cell_keep(boxes, 3, 64, 4)
+    keep = orc.cell_keep(boxes, 3, 64, 4, cell_h=16, cell_w=32)
     want = np.zeros((4, 64, 64), dtype=np.uint8)
     want[0, 0:32, 0:32] = 1
     want[1, 16:64, 32:64] = 1
     want[2, 0:48, 0:64] = 1
     assert np.array_equal(keep, want)
     # a bin whose side is not a multiple of the cell: the cut cells at the edge
-    keep = orc.cell_keep(np.array([[0, 0, 0, 1, 1, 0, 0, 26, 26, 0]], dtype=np.int32), 3, 48, 1)
+    keep = orc.cell_keep(np.array([[0, 0, 0, 1, 1, 0, 0, 26, 26, 0]], dtype=np.int32), 3, 48, 1, cell_h=16, cell_w=32)
     want = np.zeros((1, 48, 48), dtype=np.uint8)
     want[0, 16:48, 0:48] = 1                    # rows 26..47 -> cell rows 1, 2; cols 26..47 -> cell cols 0 and the cut cell 1
+    assert np.array_equal(keep, want)
+    # the library's cells (the default): 8 rows x 32 columns
+    keep = orc.cell_keep(boxes, 3, 64, 4)
+    want = np.zeros((4, 64, 64), dtype=np.uint8)
+    want[0, 0:24, 0:32] = 1                     # rows 0..21 -> rows of 8: 0, 1, 2
+    want[1, 16:64, 32:64] = 1                   # rows 20..57 -> 2..7
+    want[2, 8:40, 0:64] = 1                     # rows 15..36 -> 1..4
     assert np.array_equal(keep, want)
 
 
