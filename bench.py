@@ -52,6 +52,22 @@ def live_cell_fraction(boxes, halo, S, n_bins, cell_h=8, cell_w=32):
     return float(live.mean()) if n_bins else 1.0
 
 
+def needed_cell_fractions(places, S, n_bins, radii, cell_h=8, cell_w=32):
+    """Needed-region mode: for every radius, the share of the bins' cells within that Chebyshev distance
+    of a placed macroblock (what the layer of that radius computes)."""
+    cx, cy = -(-S // cell_w), -(-S // cell_h)
+    dmin = np.full((max(n_bins, 1), cy, cx), 1 << 30, dtype=np.int64)
+    ys, xs = np.arange(cy) * cell_h, np.arange(cx) * cell_w
+    for p in places:
+        b, x0, y0 = int(p["bin"]), int(p["px"]), int(p["py"])
+        if b >= n_bins:
+            continue
+        gy = np.maximum(0, np.maximum(ys - (y0 + 15), y0 - (ys + cell_h - 1)))
+        gx = np.maximum(0, np.maximum(xs - (x0 + 15), x0 - (xs + cell_w - 1)))
+        np.minimum(dmin[b], np.maximum(gy[:, None], gx[None, :]), out=dmin[b])
+    return [float((dmin <= r).mean()) for r in radii]
+
+
 def net_flops(net, composed_tail):
     """Per packed low-resolution pixel: flop and launches of the profiled conv class (bf16 path: the
     C-input / bf16-output convs; 18*cin*cout per output pixel at the layer's resolution), the
@@ -100,7 +116,9 @@ class Runner:
         self.po = None
         self.exact = args.exact_border
         self.masked = bool(getattr(args, "box_masked", False)) and cfg.precision == "bf16" and cfg.net.channels == 64
-        self.live_frac = 1.0      # box-masked mode: fraction of the 8 x 32 cells that the body convs compute
+        self.live_frac = 1.0      # box-masked / needed-region mode: mean fraction of the 8 x 32 cells that the body convs compute
+        self.needed = (bool(getattr(args, "needed_region", False)) and cfg.precision == "bf16" and cfg.net.channels == 64
+                       and not per_layer_tail)
         self.sync_counts = args.sync_counts
         self.net_out = self.hr = None
         self.cap = 0
@@ -126,6 +144,8 @@ class Runner:
             rh.enhance_exact(po.bins, po.boxes, po.counts, n=self.cap, n_valid=po.counts[1:2], out=self.net_out)
         elif self.masked:
             rh.enhance_masked(po.bins, po.boxes, po.counts, n=self.cap, n_valid=po.counts[1:2], out=self.net_out)
+        elif self.needed:
+            rh.enhance_needed(po.bins, po.places, po.counts, n=self.cap, n_valid=po.counts[1:2], out=self.net_out)
         elif self.sync_counts:
             rh.enhance(po.bins, n=rh.read_counts(po.counts)[1], out=self.net_out)
         else:
@@ -138,6 +158,12 @@ class Runner:
         counts = self.plan_only()
         if self.masked:
             self.live_frac = live_cell_fraction(rh.boxes_np(self.po.boxes, counts[0]), self.cfg.halo, self.cfg.bin_size, counts[1])
+        if self.needed:
+            from paper_2407_16990_amd import needed_radii
+            radii = needed_radii(self.cfg.net)
+            fr = needed_cell_fractions(rh.places_np(self.po.places, counts[3]), self.cfg.bin_size, counts[1], radii)
+            self.live_frac = float(np.mean(fr[1:-1])) if len(fr) > 2 else 1.0
+            self.tail_frac = fr[-1]
         if self.net_out is None:
             # all outputs are allocated once, outside the timed region; the enhance call is sized by
             # the output capacity (the bins this batch needs plus slack) and told the device-side count
@@ -221,6 +247,10 @@ def main():
                     help="enhance with rh_enhance_masked (the body convs skip the 8 x 32 cells that no box touches; "
                          "a different function near those cells)")
     ap.add_argument("--no-box-masked-leg", action="store_true", help="skip the box-masked leg of the default run")
+    ap.add_argument("--needed-region", action="store_true",
+                    help="enhance with rh_enhance_needed (every layer computes only the cells that can reach a pasted "
+                         "pixel; pasted pixels bit-identical to rh_enhance)")
+    ap.add_argument("--no-needed-region-leg", action="store_true", help="skip the needed-region leg of the default run")
     ap.add_argument("--exact-border", action="store_true",
                     help="enhance with rh_enhance_exact (per-layer zeroing of the out-of-frame part of the boxes)")
     ap.add_argument("--per-layer-tail", action="store_true",
@@ -264,6 +294,8 @@ def main():
         cfg = wl.replace(cfg, name=f"{cfg.name}_per_layer_tail")
     if args.box_masked:
         cfg = wl.replace(cfg, name=f"{cfg.name}_box_masked")
+    if args.needed_region:
+        cfg = wl.replace(cfg, name=f"{cfg.name}_needed_region")
     F, s, S = cfg.n_frames, cfg.net.scale, cfg.bin_size
 
     # A plain device copy of known size, outside every timed region: what rocprofv3's FETCH_SIZE /
@@ -436,6 +468,25 @@ def main():
                                 "conv_class_frac": sm_m["conv_class"]["frac_of_peak"]}
         rm.close()
         del rm
+
+    if (not args.needed_region and not args.box_masked and not args.no_needed_region_leg and not args.exact_border
+            and not args.per_layer_tail and cfg.precision == "bf16" and cfg.net.channels == 64):
+        # The same batch with rh_enhance_needed: every layer computes only the cells within its own radius of a
+        # pasted macroblock.  frames_hr and the enhanced pixels are bit-identical to the headline run's; the
+        # enhance output outside the pasted macroblocks (which nothing reads) is not produced.
+        args.needed_region = True
+        rn = Runner(cfg, args, max_box_mbs=args.max_box_mbs)
+        args.needed_region = False
+        ms_n, prof_n, counts_n = rn.timed(max(3, args.steps // 2), 2)
+        sm_n = rn.summary(ms_n, prof_n, counts_n)
+        result["needed_region"] = {"ms_per_step": ms_n, "macroblocks_per_s": sm_n["macroblocks_per_s"],
+                                   "speedup_over_plain": ms_step / ms_n, "mean_cell_fraction_body_convs": rn.live_frac,
+                                   "cell_fraction_tail": rn.tail_frac,
+                                   "kernel_ms_per_step": sm_n["kernel_ms_per_step"],
+                                   "conv_class_frac": sm_n["conv_class"]["frac_of_peak"],
+                                   "output": "frames_hr and enhanced pixels bit-identical to the headline run"}
+        rn.close()
+        del rn
 
     if not args.no_other_configs:
         # The other benchmark configurations, GPU legs only (fewer steps): 1, 2 and 5 as listed, and

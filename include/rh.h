@@ -213,6 +213,29 @@ rh_status rh_enhance_masked(rh_ctx* ctx, const uint8_t* in, int32_t N, const rh_
                             const uint32_t* counts, float* out, const uint32_t* n_valid);
 
 /*
+ * Needed-region variant of rh_enhance for packed bins (in: dev u8 [N][S][S][3]), for RH_BF16 networks
+ * with 64 channels.  Only the pixels of placed macroblocks are pasted (Sec. 3.3.3), and a conv
+ * output is read by the next conv within one pixel, so the part of a bin that can reach a pasted
+ * pixel shrinks from layer to layer.  Every layer computes only the RH_CELL_H x RH_CELL_W cells
+ * within its own radius (rh_needed_radii) of a placed macroblock.  On the pixels of the placed
+ * macroblocks - what rh_unpack reads - the output is bit-identical to rh_enhance's; everywhere else
+ * it is unspecified (not written, or computed from values that were not).  places / counts: dev,
+ * as written by rh_pack for these bins (counts[3] = number of placement rows); N <= max_bins.
+ * Costs two small extra launches; the first call allocates the mode's scratch.
+ * RH_E_UNIMPLEMENTED for other networks and with per_layer_tail.
+ */
+rh_status rh_enhance_needed(rh_ctx* ctx, const uint8_t* in, int32_t N, const rh_mbplace* places,
+                            const uint32_t* counts, float* out, const uint32_t* n_valid);
+
+/*
+ * Host only.  The radius, in low-resolution pixels (Chebyshev distance to the nearest pasted pixel),
+ * within which each layer's output must be right for the pasted pixels to be: radii[0] the first
+ * conv, radii[1 .. nb] the nb convs after it in execution order, radii[nb + 1] = 0 the layers
+ * after the body.  Returns nb, or -1 when the mode does not cover the network or cap < nb + 2.
+ */
+int32_t rh_needed_radii(const rh_net_desc* net, int32_t per_layer_tail, int32_t* radii, int32_t cap);
+
+/*
  * Paste (Sec. 3.3.3; problem statement of Sec. 3.2.1: SR on selected MBs, bilinear IN(.)
  * elsewhere).  frames_hr u8 [F][s*H][s*W][3] = bilinear interpolation of frames_lr (integer
  * factor s, half-pixel centres, edge clamp, exact integer arithmetic, round half up); every

@@ -91,6 +91,9 @@ def load_library():
     L.rh_enhance.argtypes = [vp, vp, i32, i32, i32, vp, vp]
     L.rh_enhance_exact.argtypes = [vp, vp, i32, vp, vp, vp, vp]
     L.rh_enhance_masked.argtypes = [vp, vp, i32, vp, vp, vp, vp]
+    L.rh_enhance_needed.argtypes = [vp, vp, i32, vp, vp, vp, vp]
+    L.rh_needed_radii.argtypes = [C.POINTER(NetDesc), i32, C.POINTER(i32), i32]
+    L.rh_needed_radii.restype = i32
     L.rh_unpack.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, i32, vp, vp]
     L.rh_identity_places.argtypes = [vp, i32, vp, vp]
     L.rh_read_counts.argtypes = [vp, vp, C.POINTER(C.c_uint32 * 4)]
@@ -112,6 +115,16 @@ def _segments(segments):
     for i, s in enumerate(segments):
         segs[i] = Segment(int(s[0]), int(s[1]), int(s[2]), float(s[3]) if len(s) > 3 else 0.0)
     return segs
+
+
+def needed_radii(net, per_layer_tail: bool = False):
+    """rh_needed_radii: [radius of the first conv, of each conv after it ..., 0 for the tail], or None
+    when the needed-region mode does not cover the network."""
+    L = load_library()
+    out = (C.c_int32 * 512)()
+    nb = L.rh_needed_radii(C.byref(NetDesc(TOPOLOGY[net.topology], net.channels, net.n_blocks, net.scale)),
+                           1 if per_layer_tail else 0, out, 512)
+    return None if nb < 0 else [int(out[i]) for i in range(nb + 2)]
 
 
 def select_regions_noalloc(importance: torch.Tensor, segments, mask: torch.Tensor, lst: torch.Tensor,
@@ -248,6 +261,22 @@ class RH:
         if out is None:
             out = torch.empty((N, H * s, W * s, 3), dtype=torch.float32, device=self.device)
         self._check(self.lib.rh_enhance_masked(self.h, _ptr(bins), N, _ptr(boxes), _ptr(counts), _ptr(out), _ptr(n_valid)))
+        return out
+
+    def enhance_needed(self, bins: torch.Tensor, places: torch.Tensor, counts: torch.Tensor, n: int | None = None,
+                       n_valid: torch.Tensor | None = None, out: torch.Tensor | None = None) -> torch.Tensor:
+        """Needed-region variant of enhance for packed bins (places, counts as returned by pack): every
+        layer computes only the cells that can reach a pasted pixel; the output is defined on the
+        pixels of the placed macroblocks only, where it equals enhance's bit for bit."""
+        assert bins.is_cuda and bins.dtype == torch.uint8 and bins.is_contiguous()
+        N, H, W, _ = bins.shape
+        assert H == W == self.cfg.bin_size
+        if n is not None:
+            N = n
+        s = self.scale
+        if out is None:
+            out = torch.zeros((N, H * s, W * s, 3), dtype=torch.float32, device=self.device)
+        self._check(self.lib.rh_enhance_needed(self.h, _ptr(bins), N, _ptr(places), _ptr(counts), _ptr(out), _ptr(n_valid)))
         return out
 
     def unpack(self, enhanced: torch.Tensor, places, n_places, frames_lr: torch.Tensor, want_sel=False,

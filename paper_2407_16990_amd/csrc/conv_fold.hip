@@ -44,6 +44,8 @@ struct fold_args {
     int N, H, W;
     int s, n_chunks, rows, ipc;   // scale, chunks, valid rows per chunk, output rows i per chunk
     int rev;
+    const uint32_t* tile_list;   // the tiles to compute (needed-region mode), or null: all tiles
+    const uint32_t* n_list;
 };
 
 // Stores the 16 accumulator values of one lane: rows 8q + 4hi + e of chunk `chunk` for
@@ -78,9 +80,11 @@ __device__ __forceinline__ void fold_each_step(F& f)
     if constexpr (I < N) { f(std::integral_constant<int, I>{}); fold_each_step<N, I + 1>(f); }
 }
 
-template <int CIN>
+template <int CIN, bool LIST>
 __global__ __launch_bounds__(256) void k_conv_fold(fold_args a)
 {
+    // LIST: the tiles come from a.tile_list.  An entry is requested two tiles ahead with a vector
+    // load (a scalar load would share its counter with the LDS fragment reads) and read a tile later.
     constexpr int KS = CIN / 16, NCH = CIN / 8, PIXB = CIN * 2, TH = FOLD_TH, PH = TH + 4, PW = FOLD_PW, RW = 2, NR = RW + 4;
     constexpr int WBYTES = 25 * KS * 1024, NPIECE = PH * PW * NCH, NPRE = (NPIECE + 255) / 256, NSTEP = 5 * KS;
     constexpr int SWZ_SH = (NCH == 8) ? 0 : 1;
@@ -92,7 +96,7 @@ __global__ __launch_bounds__(256) void k_conv_fold(fold_args a)
 
     const int n_img = a.n_valid ? min((int)*a.n_valid, a.N) : a.N;
     const int tiles_x = (a.W + 31) / 32, tiles_y = (a.H + TH - 1) / TH, tiles_img = tiles_x * tiles_y;
-    const int n_tiles = n_img * tiles_img;
+    const int n_tiles = LIST ? (int)*a.n_list : n_img * tiles_img;
     // tile lanes and chunks: as in the 3 x 3 kernel, the chunks of a layer are dealt to the workgroups
     // of one XCD that share a tile lane (the input then comes from HBM once), XCD-contiguous tile runs
     const bool deal = a.n_chunks > 1 && gridDim.x % (8 * a.n_chunks) == 0;
@@ -125,11 +129,23 @@ __global__ __launch_bounds__(256) void k_conv_fold(fold_args a)
                 *(uint4*)(lds_p + (row * PW + col) * PIXB + ((c ^ ((col >> SWZ_SH) & (NCH - 1))) << 4)) = pre[j];
         }
     };
-    auto tile_origin = [&](int tile, int& n, int& y0, int& x0) __attribute__((always_inline)) {
-        if (a.rev && tile < n_tiles) tile = n_tiles - 1 - tile;     // walk back over what the previous layer wrote last
+    auto decode = [&](int tile, int& n, int& y0, int& x0) __attribute__((always_inline)) {
         n = tile / tiles_img;
         const int tr = tile - n * tiles_img, ty = tr / tiles_x, tx = tr - ty * tiles_x;
         y0 = ty * TH; x0 = tx * 32;
+    };
+    __amdgpu_buffer_rsrc_t rlist = __builtin_amdgcn_make_buffer_rsrc((void*)a.tile_list, 0, LIST ? (uint32_t)n_tiles * 4u : 0u, RSRC_FLAGS);
+    auto list_load = [&](int idx) __attribute__((always_inline)) {       // entry of walk position idx (0 past the end)
+        const int pos = a.rev ? n_tiles - 1 - idx : idx;
+        return __builtin_amdgcn_raw_buffer_load_b32(rlist, idx < n_tiles ? (uint32_t)pos * 4u : OOB_OFF, 0, 0);
+    };
+    auto decode_cell = [&](int cell, int& n, int& y0, int& x0) __attribute__((always_inline)) {    // RH_CELL_ENTRY
+        n = (int)((uint32_t)cell >> 16); y0 = (int)(((uint32_t)cell >> 7) & 511u) * TH; x0 = (int)((uint32_t)cell & 127u) * 32;
+    };
+    auto tile_origin = [&](int tile, int& n, int& y0, int& x0) __attribute__((always_inline)) {
+        if constexpr (LIST) { decode_cell(__builtin_amdgcn_readfirstlane(list_load(tile)), n, y0, x0); return; }
+        if (a.rev && tile < n_tiles) tile = n_tiles - 1 - tile;          // walk back over what the previous layer wrote last
+        decode(tile, n, y0, x0);
     };
     auto in_rsrc = [&](int tile, int n) __attribute__((always_inline)) {
         return __builtin_amdgcn_make_buffer_rsrc((void*)(a.in + (size_t)n * a.H * a.W * CIN), 0,
@@ -146,19 +162,27 @@ __global__ __launch_bounds__(256) void k_conv_fold(fold_args a)
 #pragma unroll
         for (int e = 0; e < 16; ++e) biasv[e] = a.bias[chunk * 32 + (e >> 2) * 8 + hi * 4 + (e & 3)];
         int tile = wg;
+        int cn = 0, cy0 = 0, cx0 = 0, e_next = 0;         // LIST: origin of the current tile, entry of the next one
         {
             int n, y0, x0; tile_origin(tile, n, y0, x0);
+            cn = n; cy0 = y0; cx0 = x0;
+            if constexpr (LIST) e_next = list_load(tile + G);
             __amdgpu_buffer_rsrc_t rin = in_rsrc(tile, tile < n_tiles ? n : 0);
 #pragma unroll
             for (int j = 0; j < NPRE; ++j) load_piece(j, rin, y0, x0);
         }
         for (; tile < n_tiles; tile += G) {                // trip count uniform over the workgroup
-            int n, y0, x0; tile_origin(tile, n, y0, x0);
+            int n, y0, x0;
+            if constexpr (LIST) { n = cn; y0 = cy0; x0 = cx0; } else tile_origin(tile, n, y0, x0);
+            int e_after = 0;
+            if constexpr (LIST) e_after = list_load(tile + 2 * G);
             lds_barrier();                                 // LDS reads of the previous tile are done
             store_patch();
             lds_barrier();
             const int nt = tile + G;
-            int nn, ny0, nx0; tile_origin(nt, nn, ny0, nx0);
+            int nn, ny0, nx0;
+            if constexpr (LIST) { decode_cell(__builtin_amdgcn_readfirstlane(e_next), nn, ny0, nx0); cn = nn; cy0 = ny0; cx0 = nx0; e_next = e_after; }
+            else tile_origin(nt, nn, ny0, nx0);
             __amdgpu_buffer_rsrc_t rin = in_rsrc(nt, nt < n_tiles ? nn : 0);
 
             f32x16 acc[RW];
@@ -445,14 +469,16 @@ static hipError_t launch_fold(rh_ctx* ctx, const fold_args& a)
     constexpr int lds = 25 * (CIN / 16) * 1024 + (FOLD_TH + 4) * FOLD_PW * CIN * 2;
     static bool attr_done[RH_MAX_DEVICES] = {};
     if (!attr_done[ctx->device]) {
-        hipError_t e = hipFuncSetAttribute((const void*)k_conv_fold<CIN>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        hipError_t e = hipFuncSetAttribute((const void*)k_conv_fold<CIN, false>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_conv_fold<CIN, true>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (e != hipSuccess) return e;
         attr_done[ctx->device] = true;
     }
     fold_args m = a;                                       // main kernel: the middle class (number 4)
     m.wp = a.wp + (size_t)4 * a.n_chunks * (25 * (CIN / 16) * 64);
     m.bias = a.bias + 4 * a.n_chunks * 32;
-    hipLaunchKernelGGL(k_conv_fold<CIN>, dim3(ctx->n_cu), dim3(256), lds, ctx->stream, m);
+    if (a.tile_list) hipLaunchKernelGGL((k_conv_fold<CIN, true>), dim3(ctx->n_cu), dim3(256), lds, ctx->stream, m);
+    else hipLaunchKernelGGL((k_conv_fold<CIN, false>), dim3(ctx->n_cu), dim3(256), lds, ctx->stream, m);
     const long longest = (long)a.N * (a.W > a.H ? a.W : a.H);
     const long groups = (longest + 31) / 32;
     if (groups > 0x7FFFFFFFL) return hipErrorInvalidValue;
@@ -461,9 +487,11 @@ static hipError_t launch_fold(rh_ctx* ctx, const fold_args& a)
 }
 
 // t: the body's output [N][H][W][C] bf16 -> raw network output fp32 [N][sH][sW][3]; two launches.
-rh_status rh_launch_fold(rh_ctx* ctx, const __bf16* t, float* out, int N, int H, int W, const uint32_t* n_valid, int rev)
+rh_status rh_launch_fold(rh_ctx* ctx, const __bf16* t, float* out, int N, int H, int W, const uint32_t* n_valid, int rev,
+                         const uint32_t* tile_list, const uint32_t* n_list)
 {
     fold_args a;
+    a.tile_list = tile_list; a.n_list = n_list;
     a.in = t; a.wp = (const uint4*)ctx->fold_w; a.bias = ctx->fold_b; a.out = out; a.n_valid = n_valid;
     a.N = N; a.H = H; a.W = W; a.s = ctx->cfg.net.scale; a.n_chunks = ctx->fold_chunks; a.rows = ctx->fold_rows;
     a.ipc = ctx->fold_ipc; a.rev = rev;

@@ -451,8 +451,14 @@ static rh_status conv(rh_ctx* ctx, const rh_layer& L, const __bf16* in, void* ou
     a.relu = relu; a.ps = L.ps; a.n_chunks = last ? 1 : L.ps * L.ps; a.cout_real = L.cout; a.s_final = s_final;
     a.rev = (ctx->conv_parity ^= 1);       // alternate the direction from one conv to the next
     // box-masked mode: the body's convs (same resolution in and out) walk the live cells only
-    const bool listed = ctx->mk_boxes && !last && L.ps == 1 && L.cin == 64;
-    a.tile_list = listed ? ctx->cell_live : nullptr; a.n_list = listed ? ctx->cell_cnt : nullptr;
+    const bool body = !last && L.ps == 1 && L.cin == 64;
+    a.tile_list = nullptr; a.n_list = nullptr;
+    if (ctx->mk_boxes && body) { a.tile_list = ctx->cell_live; a.n_list = ctx->cell_cnt; }
+    // needed-region mode: the cells within this conv's radius of a placed macroblock
+    if (ctx->nd_places && body) {
+        const int r = ctx->nd_radii[1 + ctx->nd_conv++];
+        if (r <= RH_NEED_RMAX) { a.tile_list = ctx->need_lists + (size_t)r * ctx->need_cap; a.n_list = ctx->need_cnt + r; }
+    }
     const int grid = ctx->n_cu;            // persistent kernels: one workgroup per compute unit (256 on MI355X)
     const int MT = last ? L.cout_pad / 32 : L.cin / 32;
     hipError_t e;
@@ -508,6 +514,7 @@ rh_status rh_launch_enhance_bf16(rh_ctx* ctx, const uint8_t* in, int N, int H, i
                                         ctx->bpack + l0.bp_off, h, N, H, W, head_relu, n_valid));
         // box-masked mode: from here to the end of the body the three tensors are zero outside the live cells
         if (ctx->mk_boxes) { st = rh_launch_cell_lists(ctx, N, n_valid, h, a, t); if (st != RH_OK) return st; }
+        if (ctx->nd_places) { ctx->nd_conv = 0; st = rh_launch_need_lists(ctx, N, n_valid); if (st != RH_OK) return st; }
     }
     // exact-border mode (a no-op otherwise): clear the out-of-frame part of the boxes in a layer's output
 #define ZERO(buf, res) do { st = rh_zero_outside(ctx, (void*)(buf), C * 2, (res), N, n_valid); if (st != RH_OK) return st; } while (0)
@@ -536,7 +543,9 @@ rh_status rh_launch_enhance_bf16(rh_ctx* ctx, const uint8_t* in, int N, int H, i
             if (fold) {
                 rh_prof_end(ctx, n_conv);
                 rh_prof_scope ps_(ctx, RH_PROF_CONV_LAST, 2);
-                st = rh_launch_fold(ctx, t, out, N, H, W, n_valid, ctx->conv_parity ^= 1);
+                // needed-region mode: the composed tail's output is needed on the pasted macroblocks only (radius 0)
+                st = rh_launch_fold(ctx, t, out, N, H, W, n_valid, ctx->conv_parity ^= 1,
+                                    ctx->nd_places ? ctx->need_lists : nullptr, ctx->nd_places ? ctx->need_cnt : nullptr);
                 if (st != RH_OK) return st;
             } else {
                 const int r = (s == 4) ? 2 : s;

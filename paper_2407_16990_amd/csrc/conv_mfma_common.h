@@ -20,8 +20,8 @@ struct conv_args {
     int cout_real, s_final;  // fp32 output mode
     int rev;                 // 1: walk the tiles from the last to the first (k_conv_mfma_duo)
     // box-masked mode (k_conv_mfma_duo): only the half tiles (8 rows x 32 pixels) listed are computed.
-    // tile_list: indices n * cells_per_image + cy * tiles_x + tx in any order, cy counting rows of 8;
-    // n_list: their number (both dev); null: all tiles
+    // tile_list: RH_CELL_ENTRY(n, cy, tx) in any order, cy counting rows of 8; n_list: their number
+    // (both dev); null: all tiles
     const uint32_t* tile_list;
     const uint32_t* n_list;
 };
@@ -66,4 +66,6 @@ hipError_t rh_launch_conv_tail3(hipStream_t stream, int device, const conv_args&
 hipError_t rh_launch_head_mfma(hipStream_t stream, int C, const uint8_t* in, const uint4* wp, const float* bias, __bf16* out,
                                int N, int H, int W, int relu, const uint32_t* n_valid);
 // upsampler + last conv of an EDSR-shaped net as one composed 5 x 5 conv (conv_fold.hip): t -> raw network output
-rh_status rh_launch_fold(rh_ctx* ctx, const __bf16* t, float* out, int N, int H, int W, const uint32_t* n_valid, int rev);
+// tile_list / n_list (dev, or null for all tiles): the 8 x 32 tiles to compute, as RH_CELL_ENTRY(n, ty, tx)
+rh_status rh_launch_fold(rh_ctx* ctx, const __bf16* t, float* out, int N, int H, int W, const uint32_t* n_valid, int rev,
+                         const uint32_t* tile_list, const uint32_t* n_list);

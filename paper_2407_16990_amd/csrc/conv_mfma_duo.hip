@@ -76,9 +76,8 @@ __global__ __launch_bounds__(512) void k_conv_mfma_duo(conv_args a)
     const int n_img = a.n_valid ? min((int)*a.n_valid, a.N) : a.N;
     const int tiles_x = (a.W + 31) / 32, tiles_y = (a.H + 15) / 16;
     const int tiles_img = tiles_x * tiles_y;
-    // half tiles; with a list, its entries are half tiles (n * cells_per_image + row-of-8 * tiles_x + tx)
+    // half tiles; with a list, its entries are half tiles packed as RH_CELL_ENTRY(image, row of 8, column of 32)
     const int n_units = LIST ? (int)*a.n_list : 2 * n_img * tiles_img;
-    const int cells_img = tiles_x * ((a.H + 7) / 8);
     // Tile order.  Workgroups go to the 8 XCDs round-robin; XCD x takes a contiguous run of tile
     // lanes so that neighbouring tiles (shared halo pixels) meet in one L2.
     // Layers with several output chunks (the upsampling convs): when the grid allows it the chunks
@@ -126,9 +125,7 @@ __global__ __launch_bounds__(512) void k_conv_mfma_duo(conv_args a)
         return __builtin_amdgcn_raw_buffer_load_b32(rlist, u < n_units ? (uint32_t)walk(u) * 4u : OOB_OFF, 0, 0);
     };
     auto decode_cell = [&](int cell, int& n, int& y0, int& x0) __attribute__((always_inline)) {
-        n = cell / cells_img;
-        const int cr = cell - n * cells_img, cy = cr / tiles_x, cx = cr - cy * tiles_x;
-        y0 = cy * TH; x0 = cx * 32;
+        n = (int)((uint32_t)cell >> 16); y0 = (int)(((uint32_t)cell >> 7) & 511u) * TH; x0 = (int)((uint32_t)cell & 127u) * 32;
     };
     auto unit_origin = [&](int u, int& n, int& y0, int& x0) __attribute__((always_inline)) {
         if constexpr (LIST) decode_cell(__builtin_amdgcn_readfirstlane(list_load(u)), n, y0, x0);
@@ -274,6 +271,10 @@ __global__ __launch_bounds__(512) void k_conv_mfma_duo(conv_args a)
                     sk[st] = make_uint4(v[0], v[1], v[2], v[3]);
                     __builtin_amdgcn_sched_barrier(0);
                 }
+                if constexpr (LIST && st == MID - 1) {              // the next unit's list entry has long arrived: decode it here,
+                    decode_cell(__builtin_amdgcn_readfirstlane(next_entry), cn, cy0, cx0);   // off the drain phase's critical path
+                    __builtin_amdgcn_sched_barrier(0);
+                }
                 if constexpr (st == MID - 1 || st == NSTEP - 1) {   // the two barriers of the compute phase
                     asm volatile("s_barrier" ::: "memory");
                     __builtin_amdgcn_sched_barrier(0);
@@ -285,7 +286,7 @@ __global__ __launch_bounds__(512) void k_conv_mfma_duo(conv_args a)
 
             // ---------------- drain phase ----------------
             int nn, ny0, nx0;
-            if constexpr (LIST) { decode_cell(__builtin_amdgcn_readfirstlane(next_entry), nn, ny0, nx0); cn = nn; cy0 = ny0; cx0 = nx0; }
+            if constexpr (LIST) { nn = cn; ny0 = cy0; nx0 = cx0; }
             else unit_origin(nunit, nn, ny0, nx0);
             __amdgpu_buffer_rsrc_t rin = in_rsrc(nunit, nunit < n_units ? nn : 0);
             __amdgpu_buffer_rsrc_t rout = __builtin_amdgcn_make_buffer_rsrc(

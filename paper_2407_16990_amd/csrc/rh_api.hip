@@ -58,7 +58,7 @@ extern "C" void rh_destroy(rh_ctx* ctx)
     void* ptrs[] = {ctx->w_f32, ctx->wpack, ctx->bpack, ctx->fold_w, ctx->fold_b, ctx->frame_seg, ctx->seg_par, ctx->seg_T, ctx->seg_budget,
                     ctx->frame_nsel, ctx->frame_ties, ctx->owner_id, ctx->rank_of_id, ctx->raw, ctx->sorted,
                     ctx->pcount, ctx->tr_off, ctx->tr_A, ctx->tr_T, ctx->act,
-                    ctx->cell_mark, ctx->cell_live, ctx->cell_dead, ctx->cell_cnt};
+                    ctx->cell_mark, ctx->cell_live, ctx->cell_dead, ctx->cell_cnt, ctx->need_dmin, ctx->need_lists, ctx->need_cnt};
     for (void* p : ptrs) if (p) (void)hipFree(p);
     delete ctx;
 }
@@ -294,6 +294,24 @@ extern "C" rh_status rh_enhance_masked(rh_ctx* ctx, const uint8_t* in, int32_t N
     ctx->mk_boxes = boxes; ctx->mk_counts = counts;
     const rh_status st = rh_launch_enhance_bf16(ctx, in, N, S, S, out, n_valid);
     ctx->mk_boxes = nullptr; ctx->mk_counts = nullptr;
+    return st;
+}
+
+extern "C" rh_status rh_enhance_needed(rh_ctx* ctx, const uint8_t* in, int32_t N, const rh_mbplace* places,
+                                       const uint32_t* counts, float* out, const uint32_t* n_valid)
+{
+    if (!ctx) return RH_E_INVALID;
+    if (!in || !out || !places || !counts) RH_FAIL(ctx, RH_E_INVALID, "rh_enhance_needed: null argument");
+    if (ctx->cfg.precision != RH_BF16 || ctx->cfg.net.channels != 64)
+        RH_FAIL(ctx, RH_E_UNIMPLEMENTED, "rh_enhance_needed: only bf16 networks with 64 channels have a tile-list conv kernel");
+    if (N < 1 || N > ctx->cfg.max_bins) RH_FAIL(ctx, RH_E_CAPACITY, "rh_enhance_needed: N=%d outside [1,%d]", N, ctx->cfg.max_bins);
+    if ((uintptr_t)out & 15) RH_FAIL(ctx, RH_E_INVALID, "rh_enhance_needed: out must be 16-byte aligned");
+    const int nb = rh_needed_radii(&ctx->cfg.net, ctx->cfg.per_layer_tail, ctx->nd_radii, RH_NEED_MAX_LAYERS);
+    if (nb < 0) RH_FAIL(ctx, RH_E_UNIMPLEMENTED, "rh_enhance_needed: not with the upsampler run layer by layer (per_layer_tail)");
+    const int S = ctx->cfg.bin_size;
+    ctx->nd_places = places; ctx->nd_counts = counts;
+    const rh_status st = rh_launch_enhance_bf16(ctx, in, N, S, S, out, n_valid);
+    ctx->nd_places = nullptr; ctx->nd_counts = nullptr;
     return st;
 }
 

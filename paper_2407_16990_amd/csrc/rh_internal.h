@@ -9,6 +9,12 @@
 
 #define RH_MB 16
 #define RH_NO_BIN 0xFFFFu
+// A cell-list entry (box-masked and needed-region modes): image n, cell row cy (rows of RH_CELL_H),
+// cell column cx packed as n << 16 | cy << 7 | cx  (bin_size <= 4096: cy < 512, cx < 128; n < 65536),
+// so that the kernels that walk a list decode an entry with shifts
+#define RH_CELL_ENTRY(n, cy, cx) (((uint32_t)(n) << 16) | ((uint32_t)(cy) << 7) | (uint32_t)(cx))
+#define RH_NEED_RMAX 63          // largest layer radius that has a cell list of its own (needed-region mode)
+#define RH_NEED_MAX_LAYERS 512
 #define RH_MAX_DEVICES 64     // device indexes a context may live on (per-device launch attributes)
 
 struct rh_layer {
@@ -90,6 +96,16 @@ struct rh_ctx {
     uint32_t* cell_live;    // [max_bins * cells] live cells = tile indices of the body convs
     uint32_t* cell_dead;    // [max_bins * cells] the others
     uint32_t* cell_cnt;     // [2] entries of the two lists
+    // needed-region mode: the placement rows of the bins being enhanced (set for the duration of one
+    // rh_enhance_needed call, null otherwise), the radius of every layer, and the scratch
+    const rh_mbplace* nd_places;
+    const uint32_t* nd_counts;
+    int nd_radii[RH_NEED_MAX_LAYERS];   // [0] first conv, [1 + c] bf16-output conv c, then 0 for the tail
+    int nd_conv;            // bf16-output convs launched so far in the call
+    uint32_t* need_dmin;    // [max_bins * cells] smallest distance of a cell to a placed macroblock; all "none" between calls
+    uint32_t* need_lists;   // [RH_NEED_RMAX + 1][need_cap] cells at distance <= r
+    uint32_t* need_cnt;     // [RH_NEED_RMAX + 1] their numbers
+    size_t need_cap;
     int conv_parity;        // direction of the next bf16 conv's tile walk (alternates)
     // enhance workspace (grow-only)
     void* act;
@@ -144,6 +160,9 @@ rh_status rh_mask_init(rh_ctx*);
 // box-masked mode: the cell lists of the call in progress; zeros over the dead cells of three
 // [N][S][S][64] bf16 tensors
 rh_status rh_launch_cell_lists(rh_ctx*, int N, const uint32_t* n_valid, void* act0, void* act1, void* act2);
+// needed-region mode: the per-radius cell lists of the call in progress
+rh_status rh_launch_need_lists(rh_ctx*, int N, const uint32_t* n_valid);
+extern "C" int32_t rh_needed_radii(const rh_net_desc* net, int32_t per_layer_tail, int32_t* radii, int32_t cap);
 // exact-border mode: zero the out-of-frame part of every box in an activation tensor
 // [N][S*res][S*res][px_bytes]; a no-op unless an rh_enhance_exact call is in progress
 rh_status rh_zero_outside(rh_ctx*, void* act, int px_bytes, int res, int N, const uint32_t* n_valid);

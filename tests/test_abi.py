@@ -67,6 +67,8 @@ def test_new_entry_points_reject_null_arguments():
     lib = pkg.load_library()
     assert lib.rh_enhance_exact(None, None, 1, None, None, None, None) == 1
     assert lib.rh_enhance_masked(None, None, 1, None, None, None, None) == 1
+    assert lib.rh_enhance_needed(None, None, 1, None, None, None, None) == 1
+    assert lib.rh_needed_radii(None, 0, None, 0) == -1
     assert lib.rh_temporal_phi(None, None, 1, 0, 1, None) == 1
     assert lib.rh_temporal_select(None, None, None, 1, 1, None, None, None, None) == 1
     assert lib.rh_temporal_spread(None, None, 1, None, None) == 1

@@ -14,7 +14,7 @@ pytestmark = pytest.mark.gpu
 
 
 def full_path_check(cfg, n_frames=None, precision=None, segs=None, max_bins=None, sort_policy="density", rotate=False,
-                    expect_turned=False, per_layer_tail=False, masked=False):
+                    expect_turned=False, per_layer_tail=False, masked=False, needed=False):
     F = cfg.n_frames if n_frames is None else n_frames
     precision = precision or cfg.precision
     frames, imp = wl.make_frames(cfg, F), wl.make_importance(cfg, F)
@@ -28,7 +28,21 @@ def full_path_check(cfg, n_frames=None, precision=None, segs=None, max_bins=None
         assert o_plan.boxes[:, 5].sum() > 0, "the case is meant to turn at least one box"
     s = cfg.net.scale
     # enhance: both the exact-N call and the device-count call
-    if masked:      # box-masked mode: the body skips the cells no box touches, which hold zeros
+    if needed:      # needed-region mode: defined on the pasted macroblocks only, and there it is the plain mode's output
+        on = np.zeros((o_plan.n_bins, cfg.bin_size * s, cfg.bin_size * s), dtype=bool)
+        for g, box, b, px, py in o_plan.places.tolist():
+            on[b, py * s:(py + 16) * s, px * s:(px + 16) * s] = True
+        g_plain = rh.enhance(po.bins, n=o_plan.n_bins)
+        g_net = torch.full_like(g_plain, float("nan"))           # whatever the mode leaves unwritten stays NaN
+        rh.enhance_needed(po.bins, po.places, po.counts, n=o_plan.n_bins, out=g_net)
+        assert torch.equal(g_net[torch.from_numpy(on).cuda()], g_plain[torch.from_numpy(on).cuda()]), "not bit-identical on the pasted pixels"
+        o_net = oracle.sr_forward(cfg.net, blob, o_bins)
+        check_net(g_net.cpu().numpy()[on], o_net[on], precision, f"{cfg.name} n_bins={o_plan.n_bins} needed-region, pasted pixels")
+        g_net2 = torch.full_like(g_plain, float("nan"))
+        rh.enhance_needed(po.bins, po.places, po.counts, n=o_plan.n_bins, n_valid=po.counts[1:2], out=g_net2)
+        assert torch.equal(g_net2[torch.from_numpy(on).cuda()], g_plain[torch.from_numpy(on).cuda()])
+        del g_net2, g_plain
+    elif masked:    # box-masked mode: the body skips the cells no box touches, which hold zeros
         keep = oracle.cell_keep(o_plan.boxes, cfg.halo, cfg.bin_size, o_plan.n_bins)
         print(f"[{cfg.name}] live cell fraction {keep.mean():.3f}", flush=True)
         assert keep.mean() < 1.0, "the case is meant to have cells that no box touches"
@@ -38,15 +52,18 @@ def full_path_check(cfg, n_frames=None, precision=None, segs=None, max_bins=None
         g_net = rh.enhance(po.bins, n=o_plan.n_bins)
         o_net = oracle.sr_forward(cfg.net, blob, o_bins)
     tol = 1e-5 if precision == "fp32" else 1e-2
-    check_net(g_net.cpu().numpy(), o_net, precision, f"{cfg.name} n_bins={o_plan.n_bins}{' masked' if masked else ''}")
-    g_net2 = torch.zeros_like(g_net)
-    if masked:
+    if not needed:
+        check_net(g_net.cpu().numpy(), o_net, precision, f"{cfg.name} n_bins={o_plan.n_bins}{' masked' if masked else ''}")
+    g_net2 = None if needed else torch.zeros_like(g_net)
+    if needed:
+        pass
+    elif masked:
         rh.enhance(po.bins, n=o_plan.n_bins, out=g_net2)           # a plain call in between leaves other values in the workspace
         assert not torch.equal(g_net, g_net2), "the masked mode is a different function"
         rh.enhance_masked(po.bins, po.boxes, po.counts, n=o_plan.n_bins, n_valid=po.counts[1:2], out=g_net2)
     else:
         rh.enhance(po.bins, n=o_plan.n_bins, n_valid=po.counts[1:2], out=g_net2)
-    assert torch.equal(g_net, g_net2)
+    assert needed or torch.equal(g_net, g_net2)
     # unpack
     hr, sel = rh.unpack(g_net, po.places, po.counts[3:4], d_frames, want_sel=True)
     o_hr, o_sel = oracle.unpack(frames, s, o_net, o_plan.places, place_rot=o_plan.place_rot)
@@ -268,6 +285,37 @@ def test_cfg3_two_frames_bf16_larger_output_amplitude():
     bar is claimed for): the error grows in proportion and the bar with it."""
     cfg = wl.config(3)
     full_path_check(wl.replace(cfg, net=wl.replace(cfg.net, tail_scale=0.02)), n_frames=2)
+
+
+# ---- needed-region enhance mode (only pasted pixels matter, Sec. 3.3.3) ---------------------------
+
+@pytest.mark.parametrize("net", [wl.Net("edsr", 64, 2, 2, 0.05), wl.Net("edsr", 64, 3, 4, 0.02), wl.Net("res", 64, 2, 2, 0.05),
+                                 wl.Net("plain", 64, 4, 2, 0.05), wl.Net("edsr", 64, 2, 3, 0.05)],
+                         ids=lambda n: f"{n.topology}x{n.scale}")
+def test_needed_region_enhance_small_nets(net):
+    full_path_check(wl.replace(wl.config(1), net=net, precision="bf16"), needed=True)
+
+
+def test_needed_region_enhance_turned_boxes_and_odd_bin_side():
+    cfg = wl.replace(wl.config(3), n_frames=2, width=160, height=112, halo=6, bin_size=88, importance="uniform", frac=0.4,
+                     net=wl.Net("edsr", 64, 2, 4, 0.05))
+    full_path_check(cfg, rotate=True, expect_turned=True, needed=True)
+
+
+def test_cfg3_two_frames_bf16_needed_region():
+    full_path_check(wl.config(3), n_frames=2, needed=True)
+
+
+def test_needed_region_enhance_rejects_the_layer_by_layer_tail():
+    cfg = wl.replace(wl.config(3), n_frames=1, net=wl.Net("edsr", 64, 1, 4, 0.02))
+    blob = wl.make_weights(cfg.net, 1, "bf16")
+    rh = make_rh(cfg, blob, max_bins=4, per_layer_tail=True)
+    bins = torch.zeros((1, cfg.bin_size, cfg.bin_size, 3), dtype=torch.uint8, device="cuda")
+    places = torch.zeros((4, 16), dtype=torch.uint8, device="cuda")
+    counts = torch.zeros(4, dtype=torch.int32, device="cuda")
+    with pytest.raises(RuntimeError, match="per_layer_tail"):
+        rh.enhance_needed(bins, places, counts)
+    rh.close()
 
 
 # ---- box-masked enhance mode (Sec. 3.3.2: bins are only partly occupied) -------------------------
