@@ -498,6 +498,39 @@ def test_full_size_bf16(ci, sample):
     rh.close()
 
 
+@pytest.mark.parametrize("ci", [3, 5])
+def test_full_size_needed_region_pastes_the_same_frames(ci):
+    """Configurations 3 and 5 in the launch configuration bench.py times (capacity-sized call, device-side
+    bin count): the needed-region mode's pasted frames and enhanced pixels equal the plain mode's bit for
+    bit (the plain mode's are compared with the oracle in test_full_size_bf16), whatever the workspace
+    and the output buffer held before."""
+    cfg = wl.config(ci)
+    s, S = cfg.net.scale, cfg.bin_size
+    frames, imp, segs = wl.make_frames(cfg), wl.make_importance(cfg), wl.make_segments(cfg)
+    blob = wl.make_weights(cfg.net, cfg.weight_seed, cfg.precision)
+    max_bins = 512 if ci == 5 else 256
+    rh = make_rh(cfg, blob, max_bins=max_bins)
+    d_frames, d_imp = dev(frames), dev(imp)
+    seg_rows = [tuple(r) for r in np.asarray(segs).tolist()]
+    mask, lst, n_sel = rh.select_regions(d_imp, seg_rows)
+    po = rh.pack(d_frames, d_imp, mask, lst, n_sel)
+    nb = int(po.counts[1])
+    cap = nb + 3
+    net = torch.empty((cap, S * s, S * s, 3), dtype=torch.float32, device="cuda")
+    rh.enhance(po.bins[:cap], n=cap, n_valid=po.counts[1:2], out=net)
+    hr0, sel0 = rh.unpack(net, po.places, po.counts[3:4], d_frames, want_sel=True)
+    net.fill_(float("nan"))
+    rh.enhance_needed(po.bins[:cap], po.places, po.counts, n=cap, n_valid=po.counts[1:2], out=net)
+    hr1, sel1 = rh.unpack(net, po.places, po.counts[3:4], d_frames, want_sel=True)
+    k = int(po.counts[3])
+    assert k > 1000 and torch.equal(sel0[:k], sel1[:k]) and torch.equal(hr0, hr1)
+    assert not bool(torch.isnan(sel1[:k]).any())
+    written = float((~torch.isnan(net[:nb])).float().mean())
+    print(f"[{cfg.name}] needed-region mode wrote {written:.3f} of the bins' output pixels", flush=True)
+    assert written < 0.9                                       # the tail really skipped what is not pasted
+    rh.close()
+
+
 @pytest.mark.timeout(300)
 def test_frame_based_run_bf16_full_size_frames():
     """The 100 % run of the fraction sweep at its real shape: whole 480 x 272 frames through rh_enhance
