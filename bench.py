@@ -539,6 +539,14 @@ def main():
                 pl["chosen"].update({"measured_ms_per_step": ms2, "measured_macroblocks_per_s": cn2[3] / (ms2 * 1e-3),
                                      "speedup_over_configured_bin_size": ms_step / ms2})
                 r2.close()
+                if cfg.net.channels == 64 and not args.per_layer_tail and not args.exact_border and not args.box_masked:
+                    # the chosen geometry with rh_enhance_needed (same pasted pixels): the two gains compose
+                    was, args.needed_region = args.needed_region, True
+                    r3 = Runner(wl.replace(cfg, bin_size=ch.bin_size), args)
+                    args.needed_region = was
+                    ms3, _, cn3 = r3.timed(max(3, args.steps // 2), 2)
+                    pl["chosen"].update({"needed_region_ms_per_step": ms3, "needed_region_macroblocks_per_s": cn3[3] / (ms3 * 1e-3)})
+                    r3.close()
             else:
                 pl["chosen"].update({"measured_ms_per_step": ms_step, "speedup_over_configured_bin_size": 1.0})
             result["planner_lite"] = pl
