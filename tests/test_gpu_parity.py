@@ -306,6 +306,13 @@ def test_cfg3_two_frames_bf16_needed_region():
     full_path_check(wl.config(3), n_frames=2, needed=True)
 
 
+@pytest.mark.parametrize("mode", ["needed", "masked"])
+def test_list_modes_with_more_than_64_cells_per_bin(mode):
+    """192 x 192 bins: 24 x 6 = 144 cells, so the list kernels go through a bin in three chunks of lanes."""
+    cfg = wl.replace(wl.config(3), bin_size=192, net=wl.Net("edsr", 64, 2, 4, 0.02))
+    full_path_check(cfg, n_frames=3, needed=mode == "needed", masked=mode == "masked")
+
+
 def test_needed_region_enhance_rejects_the_layer_by_layer_tail():
     cfg = wl.replace(wl.config(3), n_frames=1, net=wl.Net("edsr", 64, 1, 4, 0.02))
     blob = wl.make_weights(cfg.net, 1, "bf16")
