@@ -507,6 +507,15 @@ def main():
             d["frame_based_ms"] = fb
             d["region_speedup"] = fb / ms
             r.close()
+            if c.precision == "bf16" and c.net.channels == 64 and not args.per_layer_tail and not args.exact_border and not args.box_masked:
+                # the same leg with rh_enhance_needed (pasted pixels bit-identical)
+                was, args.needed_region = args.needed_region, True
+                rn_ = Runner(c, args)
+                args.needed_region = was
+                ms_n_, _, _ = rn_.timed(o_steps, 2)
+                d["needed_region_ms"] = ms_n_
+                d["needed_region_speedup_over_frame_based"] = fb / ms_n_
+                rn_.close()
             return d, fb
         for ci in (1, 2, 5):
             c = wl.config(ci)
