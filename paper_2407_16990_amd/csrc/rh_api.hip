@@ -307,7 +307,9 @@ extern "C" rh_status rh_enhance_needed(rh_ctx* ctx, const uint8_t* in, int32_t N
     if (N < 1 || N > ctx->cfg.max_bins) RH_FAIL(ctx, RH_E_CAPACITY, "rh_enhance_needed: N=%d outside [1,%d]", N, ctx->cfg.max_bins);
     if ((uintptr_t)out & 15) RH_FAIL(ctx, RH_E_INVALID, "rh_enhance_needed: out must be 16-byte aligned");
     const int nb = rh_needed_radii(&ctx->cfg.net, ctx->cfg.per_layer_tail, ctx->nd_radii, RH_NEED_MAX_LAYERS);
-    if (nb < 0) RH_FAIL(ctx, RH_E_UNIMPLEMENTED, "rh_enhance_needed: not with the upsampler run layer by layer (per_layer_tail)");
+    if (nb < 0)
+        RH_FAIL(ctx, RH_E_UNIMPLEMENTED, "rh_enhance_needed: not with the upsampler run layer by layer (per_layer_tail), nor with more than %d layers",
+                RH_NEED_MAX_LAYERS - 2);
     const int S = ctx->cfg.bin_size;
     ctx->nd_places = places; ctx->nd_counts = counts;
     const rh_status st = rh_launch_enhance_bf16(ctx, in, N, S, S, out, n_valid);
