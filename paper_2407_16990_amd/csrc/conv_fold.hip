@@ -479,6 +479,9 @@ static hipError_t launch_fold(rh_ctx* ctx, const fold_args& a)
     m.bias = a.bias + 4 * a.n_chunks * 32;
     if (a.tile_list) hipLaunchKernelGGL((k_conv_fold<CIN, true>), dim3(ctx->n_cu), dim3(256), lds, ctx->stream, m);
     else hipLaunchKernelGGL((k_conv_fold<CIN, false>), dim3(ctx->n_cu), dim3(256), lds, ctx->stream, m);
+    // Needed-region mode: a pasted macroblock lies at least `halo` pixels inside its box, hence inside
+    // the bin, so with a halo no pasted pixel is on the outermost ring and the ring pass has nothing to add.
+    if (a.tile_list && ctx->cfg.halo >= 1) return hipGetLastError();
     const long longest = (long)a.N * (a.W > a.H ? a.W : a.H);
     const long groups = (longest + 31) / 32;
     if (groups > 0x7FFFFFFFL) return hipErrorInvalidValue;

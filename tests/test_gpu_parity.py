@@ -302,6 +302,12 @@ def test_needed_region_enhance_turned_boxes_and_odd_bin_side():
     full_path_check(cfg, rotate=True, expect_turned=True, needed=True)
 
 
+def test_needed_region_enhance_without_a_halo():
+    """halo 0: pasted macroblocks touch the bin border, so the composed tail's border pass is needed too."""
+    cfg = wl.replace(wl.config(1), net=wl.Net("edsr", 64, 2, 4, 0.02), precision="bf16", halo=0)
+    full_path_check(cfg, needed=True)
+
+
 def test_cfg3_two_frames_bf16_needed_region():
     full_path_check(wl.config(3), n_frames=2, needed=True)
 
